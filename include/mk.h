@@ -1,0 +1,191 @@
+/*
+ * mk.h -- C ABI of the MI355X decode-step megakernel library (libmk.so).
+ *
+ * The library runs one batch-1..8 LLM decode step (RMSNorm -> QKV projection
+ * + RoPE -> GQA attention over the KV cache -> O projection + residual ->
+ * SwiGLU MLP -> final norm + LM head) as ONE persistent kernel launch whose
+ * execution order is fixed offline.  This mirrors the two phases of the paper
+ * (Sec. 3): Phase I, offline synthesis -- the decoder and LM head are parsed
+ * into a dependency DAG, candidates are pruned by the on-chip memory budget
+ * (Sec. 4.1.1, Eq. 1-2), simulated, and the chosen trace is serialised
+ * (Sec. 4.2.2, Steps 1-4); Phase II, online execution of the serialised trace
+ * with no run-time scheduling decisions (Sec. 4.2.2, "execution-path
+ * solidification").  The host engine keeps owning KV-cache allocation and
+ * prefill (Sec. 4.3.1); the library owns only the decode step.
+ *
+ * Conventions
+ *   - Every function returns 0 (MK_OK) or a negative MK_E* code; no C++
+ *     exception crosses the boundary.  mk_last_error() returns a thread-local
+ *     text for the last failure on the calling thread.
+ *   - "dev" pointers are device (HBM) addresses on the device the schedule was
+ *     bound to; "host" pointers are ordinary host memory.  Streams are passed
+ *     as void* (a hipStream_t; NULL = the default stream).
+ *   - A schedule handle is not thread-safe; decode steps on one handle must be
+ *     stream-ordered.
+ *   - bf16 means the upper 16 bits of an IEEE fp32, round-to-nearest-even.
+ */
+#ifndef MK_H_
+#define MK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MK_OK = 0,
+    MK_EINVAL = -1,      /* bad config, shape or argument                           */
+    MK_ENOMEM = -2,      /* workspace too small / host allocation failed             */
+    MK_EINFEASIBLE = -3, /* no candidate fits the LDS budget (Eq. 1-2)               */
+    MK_ESCHED = -4,      /* the schedule failed verification                         */
+    MK_EHIP = -5,        /* a HIP runtime call failed                                */
+    MK_ETIMEOUT = -6,    /* a dependency wait inside the kernel hit its spin limit   */
+    MK_ESTATE = -7       /* call order violated (e.g. decode before load_weights)    */
+};
+
+/* Fixed deployment configuration (paper abstract / Sec. 3: under a fixed
+ * configuration the execution path is determined offline).  Model dimensions
+ * follow the public Qwen2 / Qwen3 decoder family. */
+typedef struct mk_config {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
+    int32_t qkv_bias;        /* 1: Q/K/V projections carry a bias                    */
+    int32_t qk_norm;         /* 1: per-head RMSNorm on q and k before RoPE           */
+    int32_t tie_embeddings;  /* 1: LM head shares the embedding matrix               */
+    float rope_theta, rms_eps;
+    int32_t max_batch;       /* 1..8                                                 */
+    int32_t max_context;     /* KV slots per sequence                                */
+    int32_t n_workgroups;    /* persistent grid size; 0 = one per CU of device_id    */
+    int32_t device_id;       /* only read when n_workgroups == 0 or at bind time     */
+    int32_t use_mfma;        /* -1 auto (batch>1 -> MFMA), 0 VALU GEMV, 1 MFMA GEMV  */
+    int32_t ring_kb;         /* LDS weight-page ring in KB; 0 = no ring (direct loads), -1 = auto */
+    int32_t split_qkv, split_o, split_gateup, split_down; /* K splits; 0 = search    */
+    int32_t attn_chunks;     /* attention tasks per (sequence, KV head); 0 = search  */
+    uint32_t spin_limit;     /* dependency-wait poll limit; 0 = library default      */
+    uint32_t flags;          /* MK_F_*                                               */
+} mk_config;
+
+enum {
+    MK_F_TRACE = 1u,         /* record per-task clocks into the trace buffer          */
+    MK_F_TIMING = 2u         /* bracket each step's launch(es) with HIP events         */
+};
+
+typedef struct mk_schedule mk_schedule; /* opaque, library-owned host object */
+
+/* Caller-owned DEVICE pointers, bf16, row-major [out][in].  Per-layer members
+ * are HOST arrays of n_layers device pointers.  Bias / qk-norm arrays may be
+ * NULL when the matching flag is 0; lm_head may be NULL when tied. */
+typedef struct mk_weights {
+    const void *embed;      /* [vocab][hidden]  */
+    const void *lm_head;    /* [vocab][hidden]  */
+    const void *final_norm; /* [hidden]         */
+    const void *const *attn_norm, *const *wq, *const *wk, *const *wv;
+    const void *const *bq, *const *bk, *const *bv, *const *q_norm, *const *k_norm;
+    const void *const *wo, *const *mlp_norm, *const *w_gate, *const *w_up, *const *w_down;
+} mk_weights;
+
+typedef struct mk_stats {
+    int32_t n_workgroups, threads_per_wg, n_tasks, n_counters, max_instr_per_wg;
+    int32_t split_qkv, split_o, split_gateup, split_down, attn_chunks, use_mfma;
+    int32_t lds_bytes, ring_pages, page_bytes, n_stage;  /* Eq. 1-2 outcome            */
+    int64_t weight_bytes_per_step;   /* repacked weight bytes streamed by one step     */
+    int64_t workspace_bytes;
+    double sim_makespan_us;          /* cost-model prediction for one step             */
+    double sim_duty_cycle;           /* sum of busy time / (workgroups * makespan)     */
+    int32_t candidates_tried, candidates_pruned;
+} mk_stats;
+
+/* Phase I (host only, touches no GPU unless n_workgroups == 0): build the
+ * tile-task DAG of the decoder + LM head (Sec. 4.2.1 / Step 1-2), prune and
+ * search the tiling space with the page-budget model and the pipeline
+ * simulator (Step 3-4), verify, and emit the static per-workgroup instruction
+ * lists.  *out is set only on success. */
+int mk_build_schedule(const mk_config *cfg, mk_schedule **out);
+
+/* Structural check of an emitted schedule against its DAG: every tile of every
+ * operator appears exactly once; every counter's wait target equals its number
+ * of signalling tasks; replaying the per-workgroup lists with blocking waits
+ * terminates; every read-after-write, write-after-read and write-after-write
+ * pair found by walking the tasks in topological (operator) order with a
+ * last-writers table (Sec. 4.2.2 Step 2) is ordered by the emitted
+ * waits/signals.  Returns MK_OK or MK_ESCHED (text in mk_last_error). */
+int mk_schedule_verify(const mk_schedule *s);
+
+/* Serialise / restore a schedule ("the trace is serialised for runtime
+ * invocation", Sec. 3).  dump: if buf is NULL only *bytes is written. */
+int mk_schedule_dump(const mk_schedule *s, void *host_buf, size_t *bytes);
+int mk_schedule_load(const void *host_buf, size_t bytes, mk_schedule **out);
+
+int mk_get_stats(const mk_schedule *s, mk_stats *out);
+int mk_get_config(const mk_schedule *s, mk_config *out);
+
+/* Test / inspection hooks on the instruction lists (32 dwords per instruction). */
+int mk_instr_count(const mk_schedule *s, int32_t wg);
+int mk_instr_get(const mk_schedule *s, int32_t wg, int32_t idx, uint32_t *out32);
+int mk_instr_set(mk_schedule *s, int32_t wg, int32_t idx, const uint32_t *in32);
+
+/* Eq. 1 and Eq. 2 of Sec. 4.1.1 (integer floors). */
+int64_t mk_pages_available(int64_t smem_max, int64_t n_stage, int64_t instr_buf, int64_t semaphores,
+                           int64_t scratch, int64_t page_size);
+int64_t mk_pipeline_stages(int64_t pages_total, int64_t pages_weight, int64_t pages_scale,
+                           int64_t pages_act, int64_t pages_per_stage);
+
+/* Device memory the caller must provide (repacked weights, activation and
+ * partial-sum scratch, counters, instruction lists, RoPE table, trace). */
+size_t mk_workspace_bytes(const mk_schedule *s);
+
+/* Hand the library its workspace (dev pointer, 256-byte aligned, caller-owned,
+ * must outlive the handle's use).  Uploads the instruction lists and the RoPE
+ * table and zeroes the counters on `stream`.  Checks that the bound device
+ * can keep n_workgroups workgroups co-resident. */
+int mk_bind_workspace(mk_schedule *s, void *dev_workspace, size_t bytes, void *stream);
+
+/* Offline weight reorder (cf. Sec. 4.3.2 "weight reorder"): copy every matrix
+ * into the workspace in the tile-major order the kernel streams (16 rows x 32
+ * k per 1 KB chunk, lane-major).  Asynchronous on `stream`; the caller's
+ * buffers may be freed once the stream has been synchronised. */
+int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream);
+
+/* One decode step as ONE persistent kernel launch, asynchronous on `stream`.
+ * For each sequence b < batch: embeds token_ids[b], appends its K/V at slot
+ * positions[b] of kv_cache, attends over slots 0..positions[b], writes
+ * logits_out[b][vocab] (fp32).
+ *   token_ids, positions : dev int32 [batch]; 0 <= id < vocab, 0 <= pos < max_context
+ *     (the kernel clamps out-of-range values and raises the error flag)
+ *   kv_cache  : dev bf16 [n_layers][2][max_batch][n_kv_heads][max_context][head_dim]
+ *   logits_out: dev fp32 [batch][vocab]
+ *   next_token_out : dev int32 [batch] or NULL; unused by this entry point (reserved) */
+int mk_decode_step(mk_schedule *s, const int32_t *token_ids, const int32_t *positions,
+                   void *kv_cache, float *logits_out, int32_t batch, void *stream);
+
+/* Baseline with the same device task bodies and the same instruction lists,
+ * but one kernel launch per DAG operator (stream order supplies the
+ * dependencies).  Same arguments and results (bit-identical) as
+ * mk_decode_step. */
+int mk_decode_step_per_op(mk_schedule *s, const int32_t *token_ids, const int32_t *positions,
+                          void *kv_cache, float *logits_out, int32_t batch, void *stream);
+
+/* Synchronises `stream` and reports the kernel's sticky error flag:
+ * MK_OK, MK_ETIMEOUT (a wait hit spin_limit) or MK_EINVAL (bad token/position).
+ * Clears the flag and re-arms the counters when an error was found. */
+int mk_check(mk_schedule *s, void *stream);
+
+/* Duration in milliseconds of the kernels launched by the most recent
+ * mk_decode_step / mk_decode_step_per_op on this handle, measured with HIP
+ * events recorded on the launch stream around the launch(es).  Synchronises
+ * on the closing event. */
+int mk_last_step_ms(mk_schedule *s, float *ms);
+
+/* Copy the per-task trace (MK_F_TRACE) to host: records of 4 x uint64
+ * {wg<<32|instr, t_begin, t_dep_ready, t_end} in device wall-clock ticks.
+ * *n_records in: capacity, out: records written. */
+int mk_read_trace(mk_schedule *s, uint64_t *host_out, size_t *n_records, void *stream);
+
+void mk_destroy(mk_schedule *s);
+const char *mk_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MK_H_ */

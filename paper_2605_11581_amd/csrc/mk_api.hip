@@ -1,0 +1,385 @@
+// C ABI of libmk.so: argument checks, HIP runtime glue, kernel launches.
+// All device work is in mk_kernels.hip (included here so that the kernels and
+// their launches live in one translation unit); the offline synthesis is in
+// mk_sched.cpp and touches no GPU.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "mk_kernels.hip"
+#include "mk_sched.h"
+
+namespace mk {
+const char *last_error_text();
+}
+
+namespace {
+
+int hip_fail(hipError_t e, const char *what)
+{
+    char buf[256];
+    snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    mk::set_error(buf);
+    return MK_EHIP;
+}
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv,
+                       float *logits, int batch)
+{
+    mk::Params P{};
+    P.ws = s->ws; P.lay = s->lay;
+    P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
+    P.batch = batch; P.max_batch = s->dm.Bm; P.max_context = s->dm.Tm;
+    P.n_layers = s->dm.L; P.hidden = s->dm.H; P.n_q_heads = s->dm.nq; P.n_kv_heads = s->dm.nkv;
+    P.head_dim = s->dm.d; P.inter_pad = s->dm.ipad; P.vocab = s->dm.V;
+    P.qk_norm = s->cfg.qk_norm; P.rms_eps = s->cfg.rms_eps;
+    P.epoch = s->epoch; P.spin_limit = s->cfg.spin_limit ? s->cfg.spin_limit : (1u << 20);
+    P.max_instr = (uint32_t)s->max_instr; P.flags = s->cfg.flags;
+    P.embed_chunk = s->wm.embed; P.only_seq = mk::kNone;
+    return P;
+}
+
+int check_step_args(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits, int batch)
+{
+    if (!s) { mk::set_error("null schedule"); return MK_EINVAL; }
+    if (!s->bound) { mk::set_error("mk_decode_step before mk_bind_workspace"); return MK_ESTATE; }
+    if (!s->loaded) { mk::set_error("mk_decode_step before mk_load_weights"); return MK_ESTATE; }
+    if (!tokens || !positions || !kv || !logits) { mk::set_error("null device pointer"); return MK_EINVAL; }
+    if (batch < 1 || batch > s->dm.Bm) { mk::set_error("batch outside 1..max_batch"); return MK_EINVAL; }
+    return MK_OK;
+}
+
+int fill_u32(void *dst, uint32_t v, size_t n, hipStream_t st)
+{
+    if (!n) return MK_OK;
+    hipLaunchKernelGGL(mk_fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint32_t *)dst, v, n);
+    HIP_TRY(hipGetLastError());
+    return MK_OK;
+}
+
+int reset_sync_state(mk_schedule *s, hipStream_t st)
+{
+    int rc = fill_u32(s->ws + s->lay.counters, 0u, (size_t)s->n_counters * mk::kCounterStride, st);
+    if (rc) return rc;
+    rc = fill_u32(s->ws + s->lay.err, 0u, 16, st);
+    s->epoch = 0;
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mk_last_error(void) { return mk::last_error_text(); }
+
+int64_t mk_pages_available(int64_t a, int64_t b, int64_t c, int64_t d, int64_t e, int64_t f) { return mk::pages_available(a, b, c, d, e, f); }
+int64_t mk_pipeline_stages(int64_t a, int64_t b, int64_t c, int64_t d, int64_t e) { return mk::pipeline_stages(a, b, c, d, e); }
+
+int mk_build_schedule(const mk_config *cfg, mk_schedule **out)
+{
+    if (!cfg || !out) { mk::set_error("null argument"); return MK_EINVAL; }
+    mk_config c = *cfg;
+    if (c.n_workgroups == 0) {
+        hipDeviceProp_t prop;
+        HIP_TRY(hipGetDeviceProperties(&prop, c.device_id));
+        c.n_workgroups = prop.multiProcessorCount;
+    }
+    try {
+        return mk::build_schedule(&c, out);
+    } catch (const std::exception &e) {
+        mk::set_error(std::string("mk_build_schedule: ") + e.what());
+        return MK_ENOMEM;
+    }
+}
+
+int mk_schedule_verify(const mk_schedule *s)
+{
+    try { return mk::verify_schedule(s); }
+    catch (const std::exception &e) { mk::set_error(std::string("mk_schedule_verify: ") + e.what()); return MK_ENOMEM; }
+}
+
+int mk_schedule_dump(const mk_schedule *s, void *buf, size_t *bytes) { return mk::dump_schedule(s, buf, bytes); }
+
+int mk_schedule_load(const void *buf, size_t bytes, mk_schedule **out)
+{
+    try { return mk::load_schedule(buf, bytes, out); }
+    catch (const std::exception &e) { mk::set_error(std::string("mk_schedule_load: ") + e.what()); return MK_ENOMEM; }
+}
+
+int mk_get_config(const mk_schedule *s, mk_config *out)
+{
+    if (!s || !out) { mk::set_error("null argument"); return MK_EINVAL; }
+    *out = s->cfg;
+    return MK_OK;
+}
+
+int mk_get_stats(const mk_schedule *s, mk_stats *o)
+{
+    if (!s || !o) { mk::set_error("null argument"); return MK_EINVAL; }
+    memset(o, 0, sizeof *o);
+    o->n_workgroups = s->n_wg; o->threads_per_wg = mk::kWgThreads; o->n_tasks = s->n_tasks; o->n_counters = s->n_counters;
+    o->max_instr_per_wg = s->max_instr - 1;
+    o->split_qkv = s->tl.s_qkv; o->split_o = s->tl.s_o; o->split_gateup = s->tl.s_gu; o->split_down = s->tl.s_d;
+    o->attn_chunks = s->tl.nc; o->use_mfma = s->tl.mfma;
+    o->lds_bytes = (int32_t)s->lds_total; o->ring_pages = s->tl.ring_pages; o->page_bytes = s->tl.page_bytes; o->n_stage = s->tl.n_stage;
+    const mk::Dims &d = s->dm;
+    int64_t per_layer = (int64_t)d.rb_qkv * d.kb_h + (int64_t)d.rb_o * d.kb_qd + (int64_t)d.rb_gu * d.kb_h + (int64_t)d.rb_d * d.kb_i;
+    o->weight_bytes_per_step = (per_layer * d.L + (int64_t)d.rb_v * d.kb_h) * mk::kChunkBytes;
+    o->workspace_bytes = (int64_t)s->lay.total;
+    o->sim_makespan_us = s->sim.makespan_us; o->sim_duty_cycle = s->sim.duty;
+    o->candidates_tried = s->cand_tried; o->candidates_pruned = s->cand_pruned;
+    return MK_OK;
+}
+
+int mk_instr_count(const mk_schedule *s, int32_t wg)
+{
+    if (!s || wg < 0 || wg >= s->n_wg) { mk::set_error("bad workgroup index"); return MK_EINVAL; }
+    const mk::Instr *l = (const mk::Instr *)s->instr.data() + (size_t)wg * s->max_instr;
+    int n = 0;
+    while (n < s->max_instr && l[n].op != mk::OP_END) ++n;
+    return n;
+}
+
+int mk_instr_get(const mk_schedule *s, int32_t wg, int32_t idx, uint32_t *out32)
+{
+    if (!s || !out32 || wg < 0 || wg >= s->n_wg || idx < 0 || idx >= s->max_instr) { mk::set_error("bad instruction index"); return MK_EINVAL; }
+    memcpy(out32, s->instr.data() + ((size_t)wg * s->max_instr + idx) * mk::kInstrDwords, mk::kInstrDwords * 4);
+    return MK_OK;
+}
+
+int mk_instr_set(mk_schedule *s, int32_t wg, int32_t idx, const uint32_t *in32)
+{
+    if (!s || !in32 || wg < 0 || wg >= s->n_wg || idx < 0 || idx >= s->max_instr) { mk::set_error("bad instruction index"); return MK_EINVAL; }
+    if (s->bound) { mk::set_error("instructions are frozen once the workspace is bound"); return MK_ESTATE; }
+    memcpy(s->instr.data() + ((size_t)wg * s->max_instr + idx) * mk::kInstrDwords, in32, mk::kInstrDwords * 4);
+    return MK_OK;
+}
+
+size_t mk_workspace_bytes(const mk_schedule *s) { return s ? (size_t)s->lay.total : 0; }
+
+int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
+{
+    if (!s || !dev) { mk::set_error("null argument"); return MK_EINVAL; }
+    if (bytes < s->lay.total) { mk::set_error("workspace smaller than mk_workspace_bytes()"); return MK_ENOMEM; }
+    if (((uintptr_t)dev & 255u) != 0) { mk::set_error("workspace must be 256-byte aligned"); return MK_EINVAL; }
+    if (mk::verify_schedule(s) != MK_OK) return MK_ESCHED;
+    hipStream_t st = (hipStream_t)stream;
+    hipPointerAttribute_t attr;
+    HIP_TRY(hipPointerGetAttributes(&attr, dev));
+    if (attr.type != hipMemoryTypeDevice) { mk::set_error("workspace is not device memory"); return MK_EINVAL; }
+    s->device = attr.device;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, s->device));
+    if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    int per_cu = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel, mk::kWgThreads, s->lds_total));
+    if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
+        char buf[200];
+        snprintf(buf, sizeof buf, "the device keeps only %d x %d workgroups resident, the schedule needs %d", per_cu, prop.multiProcessorCount, s->n_wg);
+        mk::set_error(buf);
+        return MK_EINFEASIBLE;
+    }
+    s->ws = (char *)dev; s->ws_bytes = bytes;
+    // instruction lists
+    HIP_TRY(hipMemcpyAsync(s->ws + s->lay.instr, s->instr.data(), s->instr.size() * 4, hipMemcpyHostToDevice, st));
+    // RoPE table: angle = pos * theta^(-2i/d), evaluated in double, stored as (cos, sin) fp32
+    {
+        const int d = s->dm.d, T = s->dm.Tm;
+        std::vector<float> tab((size_t)T * d);
+        std::vector<double> freq(d / 2);
+        for (int i = 0; i < d / 2; ++i) freq[i] = std::pow((double)s->cfg.rope_theta, -2.0 * i / d);
+        for (int p = 0; p < T; ++p)
+            for (int i = 0; i < d / 2; ++i) {
+                double ang = (double)p * freq[i];
+                tab[((size_t)p * (d / 2) + i) * 2] = (float)std::cos(ang);
+                tab[((size_t)p * (d / 2) + i) * 2 + 1] = (float)std::sin(ang);
+            }
+        HIP_TRY(hipMemcpyAsync(s->ws + s->lay.rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));   // the host vectors above die here
+    }
+    int rc = reset_sync_state(s, st);
+    if (rc) return rc;
+    if (s->cfg.flags & MK_F_TRACE) {
+        rc = fill_u32(s->ws + s->lay.trace, 0u, (size_t)s->n_wg * s->max_instr * 8, st);
+        if (rc) return rc;
+    }
+    if (!s->ev_valid) {
+        hipEvent_t a, b;
+        HIP_TRY(hipEventCreate(&a));
+        HIP_TRY(hipEventCreate(&b));
+        s->ev0 = a; s->ev1 = b; s->ev_valid = true;
+    }
+    s->bound = true; s->loaded = false;
+    return MK_OK;
+}
+
+static int repack(const void *src, int n_rows, int n_cols, char *ws, uint64_t wbase, uint32_t chunk0, uint32_t kbt,
+                  uint32_t rb0, uint32_t rb_stride, uint32_t n_rb, hipStream_t st)
+{
+    if (!src) { mk::set_error("mk_load_weights: a required matrix pointer is NULL"); return MK_EINVAL; }
+    size_t total = (size_t)n_rb * kbt * 64;
+    mk::u32x4 *dst = (mk::u32x4 *)(ws + wbase) + (size_t)chunk0 * 64;
+    hipLaunchKernelGGL(mk_repack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t *)src, n_rows,
+                       n_cols, dst, kbt, rb0, rb_stride, n_rb);
+    HIP_TRY(hipGetLastError());
+    return MK_OK;
+}
+
+static int copy_vec(const void *src, size_t n, char *ws, uint64_t vbase, uint32_t off, hipStream_t st)
+{
+    if (!src) { mk::set_error("mk_load_weights: a required vector pointer is NULL"); return MK_EINVAL; }
+    hipLaunchKernelGGL(mk_copy_u16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const uint16_t *)src,
+                       (uint16_t *)(ws + vbase) + off, n);
+    HIP_TRY(hipGetLastError());
+    return MK_OK;
+}
+
+int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
+{
+    if (!s || !w) { mk::set_error("null argument"); return MK_EINVAL; }
+    if (!s->bound) { mk::set_error("mk_load_weights before mk_bind_workspace"); return MK_ESTATE; }
+    hipStream_t st = (hipStream_t)stream;
+    const mk::Dims &d = s->dm;
+    const mk::WeightMap &m = s->wm;
+    char *ws = s->ws;
+    const uint64_t wb = s->lay.weights, vb = s->lay.vecs;
+    if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up || !w->w_down) {
+        mk::set_error("mk_load_weights: a per-layer pointer table is NULL");
+        return MK_EINVAL;
+    }
+    if (s->cfg.qkv_bias && (!w->bq || !w->bk || !w->bv)) { mk::set_error("mk_load_weights: qkv_bias set but a bias table is NULL"); return MK_EINVAL; }
+    if (s->cfg.qk_norm && (!w->q_norm || !w->k_norm)) { mk::set_error("mk_load_weights: qk_norm set but a gain table is NULL"); return MK_EINVAL; }
+    int rc;
+#define TRY(x) do { rc = (x); if (rc) return rc; } while (0)
+    for (int l = 0; l < d.L; ++l) {
+        TRY(repack(w->wq[l], d.qd, d.H, ws, wb, m.qkv[l], d.kb_h, 0, 1, d.qd / 16, st));
+        TRY(repack(w->wk[l], d.kvd, d.H, ws, wb, m.qkv[l], d.kb_h, d.qd / 16, 1, d.kvd / 16, st));
+        TRY(repack(w->wv[l], d.kvd, d.H, ws, wb, m.qkv[l], d.kb_h, (d.qd + d.kvd) / 16, 1, d.kvd / 16, st));
+        TRY(repack(w->wo[l], d.H, d.qd, ws, wb, m.o[l], d.kb_qd, 0, 1, d.rb_o, st));
+        TRY(repack(w->w_gate[l], d.I, d.H, ws, wb, m.gu[l], d.kb_h, 0, 2, d.ipad / 16, st));
+        TRY(repack(w->w_up[l], d.I, d.H, ws, wb, m.gu[l], d.kb_h, 1, 2, d.ipad / 16, st));
+        TRY(repack(w->w_down[l], d.H, d.I, ws, wb, m.down[l], d.kb_i, 0, 1, d.rb_d, st));
+        TRY(copy_vec(w->attn_norm[l], d.H, ws, vb, m.g_attn[l], st));
+        TRY(copy_vec(w->mlp_norm[l], d.H, ws, vb, m.g_mlp[l], st));
+        if (s->cfg.qkv_bias) {
+            TRY(copy_vec(w->bq[l], d.qd, ws, vb, m.bias[l], st));
+            TRY(copy_vec(w->bk[l], d.kvd, ws, vb, m.bias[l] + d.qd, st));
+            TRY(copy_vec(w->bv[l], d.kvd, ws, vb, m.bias[l] + d.qd + d.kvd, st));
+        }
+        if (s->cfg.qk_norm) {
+            TRY(copy_vec(w->q_norm[l], d.d, ws, vb, m.qn[l], st));
+            TRY(copy_vec(w->k_norm[l], d.d, ws, vb, m.kn[l], st));
+        }
+    }
+    TRY(repack(w->embed, d.V, d.H, ws, wb, m.embed, d.kb_h, 0, 1, d.rb_v, st));
+    if (!s->cfg.tie_embeddings) TRY(repack(w->lm_head, d.V, d.H, ws, wb, m.head, d.kb_h, 0, 1, d.rb_v, st));
+    TRY(copy_vec(w->final_norm, d.H, ws, vb, m.g_final, st));
+#undef TRY
+    s->loaded = true;
+    return MK_OK;
+}
+
+int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                   int32_t batch, void *stream)
+{
+    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (s->epoch >= 0x00800000u) {   // keep epoch * signals far from wrapping
+        rc = reset_sync_state(s, st);
+        if (rc) return rc;
+    }
+    s->epoch += 1;
+    mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
+    const bool timing = (s->cfg.flags & 2u) != 0;
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
+    hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    HIP_TRY(hipGetLastError());
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
+    return MK_OK;
+}
+
+int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                          int32_t batch, void *stream)
+{
+    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
+    const bool timing = (s->cfg.flags & 2u) != 0;
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
+    for (uint32_t seq : s->ref_seqs) {
+        P.only_seq = seq;
+        hipLaunchKernelGGL(mk_op_kernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    }
+    HIP_TRY(hipGetLastError());
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
+    return MK_OK;
+}
+
+int mk_check(mk_schedule *s, void *stream)
+{
+    if (!s || !s->bound) { mk::set_error("mk_check on an unbound schedule"); return MK_ESTATE; }
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipStreamSynchronize(st));
+    uint32_t e[8] = {0};
+    HIP_TRY(hipMemcpy(e, s->ws + s->lay.err, sizeof e, hipMemcpyDeviceToHost));
+    if (e[0] == 0 && e[1] == 0) return MK_OK;
+    int rc = reset_sync_state(s, st);
+    HIP_TRY(hipStreamSynchronize(st));
+    if (rc) return rc;
+    char buf[200];
+    if (e[0]) {
+        snprintf(buf, sizeof buf, "a dependency wait hit the spin limit (first reported at instruction %u of some workgroup)", e[0] - 1);
+        mk::set_error(buf);
+        return MK_ETIMEOUT;
+    }
+    mk::set_error(e[1] == 1 ? "token id outside [0, vocab)" : "position outside [0, max_context)");
+    return MK_EINVAL;
+}
+
+int mk_last_step_ms(mk_schedule *s, float *ms)
+{
+    if (!s || !ms || !s->ev_valid) { mk::set_error("no timed step"); return MK_ESTATE; }
+    if (!(s->cfg.flags & 2u)) { mk::set_error("step timing needs flag bit 1 (value 2) in mk_config.flags"); return MK_ESTATE; }
+    HIP_TRY(hipEventSynchronize((hipEvent_t)s->ev1));
+    HIP_TRY(hipEventElapsedTime(ms, (hipEvent_t)s->ev0, (hipEvent_t)s->ev1));
+    return MK_OK;
+}
+
+int mk_read_trace(mk_schedule *s, uint64_t *host_out, size_t *n_records, void *stream)
+{
+    if (!s || !host_out || !n_records || !s->bound) { mk::set_error("bad argument"); return MK_EINVAL; }
+    if (!(s->cfg.flags & MK_F_TRACE)) { mk::set_error("schedule was built without MK_F_TRACE"); return MK_ESTATE; }
+    size_t have = (size_t)s->n_wg * s->max_instr;
+    size_t n = *n_records < have ? *n_records : have;
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    HIP_TRY(hipMemcpy(host_out, s->ws + s->lay.trace, n * 32, hipMemcpyDeviceToHost));
+    *n_records = n;
+    return MK_OK;
+}
+
+void mk_destroy(mk_schedule *s)
+{
+    if (!s) return;
+    if (s->ev_valid) {
+        (void)hipEventDestroy((hipEvent_t)s->ev0);
+        (void)hipEventDestroy((hipEvent_t)s->ev1);
+    }
+    delete s;
+}
+
+}  // extern "C"

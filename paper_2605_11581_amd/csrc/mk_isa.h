@@ -1,0 +1,140 @@
+// Instruction format, workspace layout and kernel parameters shared by the
+// host scheduler and the device interpreter.  Plain C++ PODs, no HIP types.
+//
+// The static schedule (paper Sec. 4.2.2 Step 4, "execution-path
+// solidification") is one array of fixed-size instructions per workgroup.
+// Every decision -- which tiles a workgroup computes, in which order, which
+// dependency counters it waits on and signals, which LDS pages its weight
+// stream lands in -- is a constant of this list; the kernel only walks it.
+#pragma once
+#include <stdint.h>
+
+namespace mk {
+
+constexpr int kWgThreads = 256;        // 4 wavefronts of 64
+constexpr int kWaves = kWgThreads / 64;
+constexpr int kChunkBytes = 1024;      // one wavefront-wide 128-bit load: 16 rows x 32 k of bf16
+constexpr int kChunkRows = 16;
+constexpr int kChunkK = 32;
+constexpr int kInstrDwords = 32;
+constexpr uint32_t kNone = 0xffffffffu;
+constexpr int kMaxBatch = 8;
+constexpr int kMaxGroup = 8;           // q heads per kv head
+constexpr int kCounterStride = 32;     // dwords between counters (one 128-byte line each)
+constexpr int kPrefetch = 8;           // 128-bit weight loads a lane keeps in flight (direct-load path)
+
+// LDS map of a workgroup:
+//   [0, 256)    current instruction
+//   [256, 512)  block-reduction scratch, flags
+//   [512, ...)  cross-wave partial sums (red), then the staged input vector / attention scratch (xs)
+constexpr int kLdsInstr = 0;
+constexpr int kLdsMisc = 256;
+constexpr int kLdsRed = 512;
+
+enum Op : uint32_t { OP_END = 0, OP_GEMV = 1, OP_ATT = 2, OP_COMB = 3 };
+
+// stage of an operator instance inside a layer; ref_seq = layer * 8 + stage
+enum Stage : uint32_t { ST_QKV = 0, ST_ATT = 1, ST_COMB = 2, ST_O = 3, ST_GU = 4, ST_DOWN = 5, ST_HEAD = 6 };
+
+enum Pro : uint32_t {
+    PRO_EMBED_NORM = 0,  // x = embedding row; store slice; RMSNorm
+    PRO_RESID_NORM = 1,  // x = base + sum(partials); store slice; RMSNorm
+    PRO_PLAIN = 2,       // x[k] = sum(partials)[k] over the unit's k range
+    PRO_SILU = 3         // x[k] = silu(sum gate partials[k]) * sum up partials[k]
+};
+
+enum Flags : uint32_t {
+    F_SKIP_PRO = 1u,   // LDS already holds this task's input vector (same operator, previous task)
+    F_MFMA = 2u,       // matrix-core GEMV/thin GEMM instead of VALU FMA
+    F_LOGITS = 4u,     // output goes to the caller's logits buffer
+    F_NO_WAIT_FENCE = 8u
+};
+
+struct Instr {                 // 32 dwords
+    uint32_t op;               // 0
+    uint32_t flags;            // 1
+    uint32_t ref_seq;          // 2  topological rank of the operator instance
+    uint32_t layer;            // 3
+    uint32_t wait_ctr[2];      // 4,5   counter index or kNone
+    uint32_t wait_cnt[2];      // 6,7   signals per step the counter receives
+    uint32_t sig_ctr;          // 8     counter to signal once the outputs are stored (kNone: none)
+    // ---- GEMV: units u0 .. u0+nu of a matrix; unit u = (row block u / S, split u % S)
+    uint32_t w_chunk;          // 9   first 1 KB chunk of the matrix inside the weight region
+    uint32_t kbt;              // 10  k blocks per row block
+    uint32_t nkb;              // 11  k blocks per unit (last split of a row block may be shorter)
+    uint32_t S;                // 12  splits per row block
+    uint32_t u0;               // 13
+    uint32_t nu;               // 14
+    uint32_t n_rows;           // 15  valid output rows of the matrix
+    uint32_t pro;              // 16
+    uint32_t in_base;          // 17  float offset: residual base (RESID) / unused
+    uint32_t in_parts;         // 18  float offset of partial 0 (PRO_SILU: gate rows; up rows follow at +in_aux)
+    uint32_t n_parts;          // 19
+    uint32_t part_stride;      // 20  floats between partials
+    uint32_t in_ld;            // 21  floats between sequences (batch rows) of the input
+    uint32_t xs_lo, xs_hi;     // 22,23 slice of the new residual this task stores
+    uint32_t xs_out;           // 24  float offset of the residual store buffer
+    uint32_t gain;             // 25  bf16 element offset of the norm gain in the vector region
+    uint32_t out;              // 26  float offset of output partial 0
+    uint32_t out_split_stride; // 27  floats between output partials
+    uint32_t out_ld;           // 28  floats between sequences of the output
+    uint32_t bias;             // 29  bf16 element offset of the bias or kNone
+    uint32_t k_len;            // 30  true K (input elements beyond it are zero)
+    uint32_t in_aux;           // 31  PRO_SILU: float distance from gate rows to up rows; EMBED: unused
+};
+
+// ATT / COMB view of the same 32 dwords (fields 0..8 identical).
+struct InstrAtt {
+    uint32_t op, flags, ref_seq, layer, wait_ctr[2], wait_cnt[2], sig_ctr;
+    uint32_t b;                // 9   sequence
+    uint32_t g;                // 10  kv head
+    uint32_t c;                // 11  chunk task index within (b, g)
+    uint32_t nc;               // 12  chunk tasks per (b, g)
+    uint32_t bs;               // 13  positions per block (blocks c, c+nc, ... belong to task c)
+    uint32_t in_parts;         // 14  float offset of QKV partial 0
+    uint32_t n_parts;          // 15
+    uint32_t part_stride;      // 16
+    uint32_t in_ld;            // 17  floats between sequences in the QKV buffer
+    uint32_t qn_gain, kn_gain; // 18,19 bf16 element offsets (qk_norm) or kNone
+    uint32_t out;              // 20  float offset of the partial buffer [b][head][nc][d+2]
+    uint32_t h0, nh;           // 21,22 COMB: first q head and number of q heads to combine
+    uint32_t o_out;            // 23  COMB: float offset of o[b][nq*d]
+    uint32_t o_ld;             // 24
+    uint32_t pad[7];
+};
+static_assert(sizeof(Instr) == kInstrDwords * 4, "instruction size");
+static_assert(sizeof(InstrAtt) == kInstrDwords * 4, "instruction size");
+
+// Byte offsets into the caller-provided workspace.
+struct Layout {
+    uint64_t weights;    // repacked matrices, 1 KB chunks
+    uint64_t vecs;       // bf16 vectors: norm gains, biases
+    uint64_t rope;       // float [max_context][head_dim/2][2] (cos, sin)
+    uint64_t act;        // fp32 activations, partial sums, attention partials
+    uint64_t counters;   // uint32, one per 128-byte line
+    uint64_t instr;      // Instr[n_wg][max_instr]
+    uint64_t err;        // uint32[8] sticky error flags
+    uint64_t trace;      // uint64[n_wg][max_instr][4]
+    uint64_t total;
+};
+
+struct Params {
+    char *ws;
+    Layout lay;
+    const int32_t *tokens;
+    const int32_t *positions;
+    uint16_t *kv;
+    float *logits;
+    int32_t batch, max_batch, max_context;
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, inter_pad, vocab;
+    int32_t qk_norm;
+    float rms_eps;
+    uint32_t epoch;       // step number since the counters were last zeroed (>= 1)
+    uint32_t spin_limit;
+    uint32_t max_instr;
+    uint32_t flags;
+    uint32_t embed_chunk; // first chunk of the (repacked) embedding matrix
+    uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
+};
+
+}  // namespace mk

@@ -1,0 +1,913 @@
+// Offline synthesis of the static schedule (paper Sec. 3 Phase I).
+//
+//   Step 1-2 (Sec. 4.2.2): the decoder + LM head become a DAG of tile-tasks.
+//     Tasks are emitted operator by operator; their dependency edges are the
+//     read-after-write pairs a last-writers table finds when the tasks are
+//     walked in topological (operator) order.  At run time the edges are
+//     carried by global counters: a task signals its operator instance's
+//     counter, a consumer waits until the counter has all of its signals.
+//   Step 3 (Sec. 4.2.2) + Sec. 4.1.1: candidates (K splits per operator,
+//     attention chunking, LDS page ring) are pruned by the on-chip memory
+//     budget of Eq. 1-2.
+//   Step 4: every surviving candidate is run through a pipeline simulator; the
+//     one with the smallest makespan (ties: highest duty cycle) is serialised
+//     as per-workgroup instruction lists.
+#include "mk_sched.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <numeric>
+
+namespace mk {
+
+static thread_local std::string g_err;
+void set_error(const std::string &msg) { g_err = msg; }
+const char *last_error_text() { return g_err.c_str(); }
+
+constexpr int64_t kLdsMax = 160 * 1024;   // LDS per CU on CDNA4
+constexpr int kMaxHidden = 16 * kWgThreads;
+
+int64_t pages_available(int64_t smem_max, int64_t n_stage, int64_t instr_buf, int64_t semaphores,
+                        int64_t scratch, int64_t page_size)
+{
+    int64_t left = smem_max - n_stage * (instr_buf + semaphores + scratch);
+    if (left < 0 || page_size <= 0) return 0;
+    return left / page_size;
+}
+
+int64_t pipeline_stages(int64_t pages_total, int64_t pages_weight, int64_t pages_scale, int64_t pages_act,
+                        int64_t pages_per_stage)
+{
+    int64_t left = pages_total - pages_weight - pages_scale - pages_act;
+    if (left < 0 || pages_per_stage <= 0) return 0;
+    return left / pages_per_stage;
+}
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+static int derive_dims(const mk_config &c, Dims &d)
+{
+    char buf[256];
+    auto bad = [&](const char *what) {
+        snprintf(buf, sizeof buf, "mk_config: %s", what);
+        set_error(buf);
+        return MK_EINVAL;
+    };
+    if (c.n_layers < 1 || c.hidden < 32 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.intermediate < 1 || c.vocab < 1)
+        return bad("non-positive dimension");
+    if (c.hidden % 32 != 0) return bad("hidden must be a multiple of 32");
+    if (c.hidden > kMaxHidden) return bad("hidden larger than 4096 is not supported");
+    if (c.head_dim != 64 && c.head_dim != 128) return bad("head_dim must be 64 or 128");
+    if (c.n_q_heads % c.n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
+    if (c.n_q_heads / c.n_kv_heads > kMaxGroup) return bad("more than 8 q heads per kv head");
+    if (c.max_batch < 1 || c.max_batch > kMaxBatch) return bad("max_batch must be 1..8");
+    if (c.max_context < 1) return bad("max_context must be positive");
+    if (c.n_workgroups < 1 || c.n_workgroups > 4096) return bad("n_workgroups must be 1..4096");
+    if (!(c.rms_eps > 0.f) || !(c.rope_theta > 0.f)) return bad("rms_eps and rope_theta must be positive");
+    d.L = c.n_layers; d.H = c.hidden; d.nq = c.n_q_heads; d.nkv = c.n_kv_heads; d.d = c.head_dim;
+    d.I = c.intermediate; d.V = c.vocab; d.Bm = c.max_batch; d.Tm = c.max_context; d.G = d.nq / d.nkv;
+    d.qd = d.nq * d.d; d.kvd = d.nkv * d.d; d.nqkv = d.qd + 2 * d.kvd;
+    d.ipad = ceil_div(d.I, 16) * 16; d.ngu = 2 * d.ipad;
+    d.kb_h = d.H / 32; d.kb_qd = d.qd / 32; d.kb_i = ceil_div(d.I, 32);
+    d.rb_qkv = d.nqkv / 16; d.rb_o = d.H / 16; d.rb_gu = d.ngu / 16; d.rb_d = d.H / 16; d.rb_v = ceil_div(d.V, 16);
+    return MK_OK;
+}
+
+// ---------------------------------------------------------------- memory maps
+static void plan_weights(const mk_config &c, const Dims &d, WeightMap &w)
+{
+    uint64_t ch = 0, ve = 0;
+    auto take = [&](uint64_t n) { uint64_t at = ch; ch += n; return (uint32_t)at; };
+    auto takev = [&](uint64_t n) { uint64_t at = ve; ve += (n + 7) / 8 * 8; return (uint32_t)at; };
+    w.qkv.resize(d.L); w.o.resize(d.L); w.gu.resize(d.L); w.down.resize(d.L);
+    w.g_attn.resize(d.L); w.g_mlp.resize(d.L); w.bias.assign(d.L, kNone); w.qn.assign(d.L, kNone); w.kn.assign(d.L, kNone);
+    for (int l = 0; l < d.L; ++l) {
+        w.qkv[l] = take((uint64_t)d.rb_qkv * d.kb_h);
+        w.o[l] = take((uint64_t)d.rb_o * d.kb_qd);
+        w.gu[l] = take((uint64_t)d.rb_gu * d.kb_h);
+        w.down[l] = take((uint64_t)d.rb_d * d.kb_i);
+        w.g_attn[l] = takev(d.H); w.g_mlp[l] = takev(d.H);
+        if (c.qkv_bias) w.bias[l] = takev(d.nqkv);
+        if (c.qk_norm) { w.qn[l] = takev(d.d); w.kn[l] = takev(d.d); }
+    }
+    w.embed = take((uint64_t)d.rb_v * d.kb_h);
+    w.head = c.tie_embeddings ? w.embed : take((uint64_t)d.rb_v * d.kb_h);
+    w.g_final = takev(d.H);
+    w.n_chunks = ch; w.n_vec = ve;
+}
+
+static void plan_act(const Dims &d, const Tiling &t, ActMap &a)
+{
+    uint64_t f = 0;
+    auto take = [&](uint64_t n) { uint64_t at = f; f += (n + 63) / 64 * 64; return (uint32_t)at; };
+    a.xa = take((uint64_t)d.Bm * d.H);
+    a.xb = take((uint64_t)d.Bm * d.H);
+    a.pqkv = take((uint64_t)t.s_qkv * d.Bm * d.nqkv);
+    a.attp = take((uint64_t)d.Bm * d.nq * t.nc * (d.d + 2));
+    a.o = take((uint64_t)d.Bm * d.qd);
+    a.po = take((uint64_t)t.s_o * d.Bm * d.H);
+    a.gu = take((uint64_t)t.s_gu * d.Bm * d.ngu);
+    a.pd = take((uint64_t)t.s_d * d.Bm * d.H);
+    a.n_floats = f;
+}
+
+static uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- LDS budget (Eq. 1-2)
+struct LdsBudget {
+    int cap_units;        // units per GEMV task the cross-wave reduction area can hold
+    uint32_t red_bytes;
+    uint32_t xs_cap;      // bytes left for the staged input vector
+};
+
+static uint32_t att_scratch_bytes(const Dims &d)
+{
+    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * d.G * (d.d + 2)) * 4u;
+}
+
+static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
+{
+    int nterm = d.Bm <= 5 ? 3 : 2;
+    return t.mfma ? (uint32_t)(d.Bm * nterm) * ((uint32_t)d.H * 2u + 16u) : (uint32_t)d.H * 4u;
+}
+
+static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
+{
+    int cols = t.mfma ? d.Bm : 1;
+    b.cap_units = std::max(1, 64 / cols);
+    b.red_bytes = (uint32_t)(kWaves * b.cap_units * 16 * cols * 4);
+    int64_t fixed = kLdsRed + b.red_bytes;                       // instruction buffer + semaphores + scratch
+    int64_t ring = (int64_t)t.ring_pages * t.page_bytes;
+    int64_t left = kLdsMax - fixed - ring;
+    int64_t need = std::max<int64_t>(att_scratch_bytes(d), norm_stage_bytes(d, t));
+    if (left < need) return false;
+    b.xs_cap = (uint32_t)left;
+    return true;
+}
+
+// ---------------------------------------------------------------- emission
+struct Builder {
+    const mk_config &cfg;
+    const Dims &d;
+    const Tiling &t;
+    const WeightMap &wm;
+    const ActMap &am;
+    LdsBudget lb;
+    int n_wg;
+    std::vector<std::vector<Instr>> lists;
+    std::vector<double> load;           // accumulated chunk-equivalents per workgroup
+    std::vector<uint32_t> ctr_signals;  // signals per step of every counter
+    uint32_t max_xs_bytes = 0;
+    int n_tasks = 0;
+
+    Builder(const mk_config &c, const Dims &dd, const Tiling &tt, const WeightMap &w, const ActMap &a)
+        : cfg(c), d(dd), t(tt), wm(w), am(a), n_wg(c.n_workgroups), lists(c.n_workgroups), load(c.n_workgroups, 0.0) {}
+
+    uint32_t new_counter() { ctr_signals.push_back(0); return (uint32_t)ctr_signals.size() - 1; }
+
+    // workgroups ordered by accumulated load (stable), so the larger shares go to the idlest
+    std::vector<int> by_load() const
+    {
+        std::vector<int> o(n_wg);
+        std::iota(o.begin(), o.end(), 0);
+        std::stable_sort(o.begin(), o.end(), [&](int a, int b) { return load[a] < load[b]; });
+        return o;
+    }
+
+    uint32_t stage_bytes(uint32_t nkblocks) const
+    {
+        int nterm = d.Bm <= 5 ? 3 : 2;
+        return t.mfma ? (uint32_t)(d.Bm * nterm) * (nkblocks * kChunkK * 2u + 16u) : nkblocks * kChunkK * 4u;
+    }
+
+    // Partition the units of one GEMV operator instance over the workgroups and emit its tasks.
+    // `proto` carries everything except u0/nu/xs range/flags/signal.  Returns false if a task cannot fit LDS.
+    bool emit_gemv(Instr proto, int nrb, uint32_t wait_ctr, uint32_t sig_ctr)
+    {
+        const uint32_t S = proto.S, kbt = proto.kbt, nkb = proto.nkb;
+        const uint32_t U = (uint32_t)nrb * S;
+        const int parts = (int)std::min<uint32_t>((uint32_t)n_wg, U);
+        const bool normk = proto.pro == PRO_EMBED_NORM || proto.pro == PRO_RESID_NORM;
+        std::vector<int> order = by_load();
+        uint32_t base = U / parts, rem = U % parts, u = 0;
+        for (int pi = 0; pi < parts; ++pi) {
+            const int wg = order[pi];
+            uint32_t share = base + ((uint32_t)pi < rem ? 1u : 0u);
+            uint32_t u_end = u + share;
+            bool first = true;
+            uint32_t prev_lo = kNone, prev_n = kNone;
+            while (u < u_end) {
+                // grow the task unit by unit while the reduction area and the staged input fit
+                uint32_t nu = 0, klo = 0, khi = 0;
+                while (u + nu < u_end && (int)nu < lb.cap_units) {
+                    uint32_t uu = u + nu, s = uu % S;
+                    uint32_t lo = s * nkb, hi = (s == S - 1) ? kbt : lo + nkb;
+                    uint32_t nlo = nu ? std::min(klo, lo) : lo, nhi = nu ? std::max(khi, hi) : hi;
+                    if (!normk && stage_bytes(nhi - nlo) > lb.xs_cap) break;
+                    klo = nlo; khi = nhi; ++nu;
+                }
+                if (nu == 0) return false;
+                Instr I = proto;
+                I.u0 = u; I.nu = nu;
+                I.wait_ctr[0] = wait_ctr; I.wait_ctr[1] = kNone;
+                I.wait_cnt[0] = wait_ctr == kNone ? 0 : ctr_signals[wait_ctr];
+                I.wait_cnt[1] = 0;
+                I.sig_ctr = kNone;
+                if (normk) {
+                    // the first task of each participant stores its slice of the new residual
+                    I.xs_lo = first ? (uint32_t)((uint64_t)d.H * pi / parts) : 0;
+                    I.xs_hi = first ? (uint32_t)((uint64_t)d.H * (pi + 1) / parts) : 0;
+                    if (!first) I.flags |= F_SKIP_PRO;
+                    max_xs_bytes = std::max(max_xs_bytes, norm_stage_bytes(d, t));
+                } else {
+                    I.xs_lo = klo; I.xs_hi = khi - klo;
+                    if (!first && prev_lo == I.xs_lo && prev_n == I.xs_hi) I.flags |= F_SKIP_PRO;
+                    prev_lo = I.xs_lo; prev_n = I.xs_hi;
+                    max_xs_bytes = std::max(max_xs_bytes, stage_bytes(khi - klo));
+                }
+                if (u + nu == u_end) { I.sig_ctr = sig_ctr; if (sig_ctr != kNone) ++ctr_signals[sig_ctr]; }
+                lists[wg].push_back(I);
+                ++n_tasks;
+                // load: chunks streamed + a fixed per-task cost (in chunk equivalents)
+                uint32_t c0 = (u / S) * kbt + (u % S) * nkb, ue = u + nu, c1 = (ue / S) * kbt + (ue % S) * nkb;
+                load[wg] += (double)(c1 - c0) + 4.0;
+                u += nu; first = false;
+            }
+        }
+        return true;
+    }
+
+    bool build()
+    {
+        if (!lds_budget(d, t, lb)) return false;
+        const uint32_t fl = t.mfma ? F_MFMA : 0u;
+        uint32_t prev_done = kNone;   // counter of the operator producing the residual partials of the layer below
+        for (int l = 0; l < d.L; ++l) {
+            const uint32_t c_qkv = new_counter(), c_comb = new_counter(), c_o = new_counter(), c_gu = new_counter(),
+                           c_d = new_counter();
+            std::vector<uint32_t> c_att(d.Bm * d.nkv);
+            for (auto &c : c_att) c = new_counter();
+
+            // ---- QKV projection: prologue = (embedding | residual + down partials) -> RMSNorm
+            Instr q{};
+            q.op = OP_GEMV; q.flags = fl; q.ref_seq = l * 8 + ST_QKV; q.layer = l;
+            q.w_chunk = wm.qkv[l]; q.kbt = d.kb_h; q.S = t.s_qkv; q.nkb = ceil_div(d.kb_h, t.s_qkv);
+            q.n_rows = d.nqkv; q.k_len = d.H;
+            q.pro = l == 0 ? PRO_EMBED_NORM : PRO_RESID_NORM;
+            q.in_base = am.xb; q.in_parts = am.pd; q.n_parts = l == 0 ? 0 : t.s_d; q.part_stride = d.Bm * d.H; q.in_ld = d.H;
+            q.xs_out = am.xa; q.gain = wm.g_attn[l];
+            q.out = am.pqkv; q.out_split_stride = d.Bm * d.nqkv; q.out_ld = d.nqkv; q.bias = wm.bias[l];
+            if (!emit_gemv(q, d.rb_qkv, prev_done, c_qkv)) return false;
+
+            // ---- attention partials: one task per (sequence, kv head, chunk)
+            {
+                std::vector<int> order = by_load();
+                int oi = 0;
+                for (int b = 0; b < d.Bm; ++b)
+                    for (int g = 0; g < d.nkv; ++g)
+                        for (int c = 0; c < t.nc; ++c) {
+                            InstrAtt a{};
+                            a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l;
+                            a.wait_ctr[0] = c_qkv; a.wait_cnt[0] = ctr_signals[c_qkv]; a.wait_ctr[1] = kNone;
+                            a.sig_ctr = c_att[b * d.nkv + g]; ++ctr_signals[a.sig_ctr];
+                            a.b = b; a.g = g; a.c = c; a.nc = t.nc; a.bs = t.bs;
+                            a.in_parts = am.pqkv; a.n_parts = t.s_qkv; a.part_stride = d.Bm * d.nqkv; a.in_ld = d.nqkv;
+                            a.qn_gain = wm.qn[l]; a.kn_gain = wm.kn[l];
+                            a.out = am.attp;
+                            int wg = order[oi % n_wg]; ++oi;
+                            Instr raw; memcpy(&raw, &a, sizeof raw);
+                            lists[wg].push_back(raw); ++n_tasks;
+                            load[wg] += (double)d.Tm / t.nc * d.d * 4.0 / kChunkBytes * 0.5 + 8.0;
+                        }
+            }
+            // ---- combine: one task per (sequence, q head)
+            {
+                std::vector<int> order = by_load();
+                int oi = 0;
+                for (int b = 0; b < d.Bm; ++b)
+                    for (int h = 0; h < d.nq; ++h) {
+                        InstrAtt a{};
+                        a.op = OP_COMB; a.ref_seq = l * 8 + ST_COMB; a.layer = l;
+                        uint32_t ca = c_att[b * d.nkv + h / d.G];
+                        a.wait_ctr[0] = ca; a.wait_cnt[0] = ctr_signals[ca]; a.wait_ctr[1] = kNone;
+                        a.sig_ctr = c_comb; ++ctr_signals[c_comb];
+                        a.b = b; a.nc = t.nc; a.out = am.attp; a.h0 = h; a.nh = 1; a.o_out = am.o; a.o_ld = d.qd;
+                        int wg = order[oi % n_wg]; ++oi;
+                        Instr raw; memcpy(&raw, &a, sizeof raw);
+                        lists[wg].push_back(raw); ++n_tasks;
+                        load[wg] += 4.0;
+                    }
+            }
+            // ---- O projection (residual add deferred to the consumer's prologue)
+            Instr o{};
+            o.op = OP_GEMV; o.flags = fl; o.ref_seq = l * 8 + ST_O; o.layer = l;
+            o.w_chunk = wm.o[l]; o.kbt = d.kb_qd; o.S = t.s_o; o.nkb = ceil_div(d.kb_qd, t.s_o);
+            o.n_rows = d.H; o.k_len = d.qd; o.pro = PRO_PLAIN;
+            o.in_parts = am.o; o.n_parts = 1; o.part_stride = 0; o.in_ld = d.qd;
+            o.out = am.po; o.out_split_stride = d.Bm * d.H; o.out_ld = d.H; o.bias = kNone;
+            if (!emit_gemv(o, d.rb_o, c_comb, c_o)) return false;
+
+            // ---- gate/up projection: prologue = residual + O partials -> RMSNorm
+            Instr gu{};
+            gu.op = OP_GEMV; gu.flags = fl; gu.ref_seq = l * 8 + ST_GU; gu.layer = l;
+            gu.w_chunk = wm.gu[l]; gu.kbt = d.kb_h; gu.S = t.s_gu; gu.nkb = ceil_div(d.kb_h, t.s_gu);
+            gu.n_rows = d.ngu; gu.k_len = d.H; gu.pro = PRO_RESID_NORM;
+            gu.in_base = am.xa; gu.in_parts = am.po; gu.n_parts = t.s_o; gu.part_stride = d.Bm * d.H; gu.in_ld = d.H;
+            gu.xs_out = am.xb; gu.gain = wm.g_mlp[l];
+            gu.out = am.gu; gu.out_split_stride = d.Bm * d.ngu; gu.out_ld = d.ngu; gu.bias = kNone;
+            if (!emit_gemv(gu, d.rb_gu, c_o, c_gu)) return false;
+
+            // ---- down projection: prologue = silu(gate) * up
+            Instr dn{};
+            dn.op = OP_GEMV; dn.flags = fl; dn.ref_seq = l * 8 + ST_DOWN; dn.layer = l;
+            dn.w_chunk = wm.down[l]; dn.kbt = d.kb_i; dn.S = t.s_d; dn.nkb = ceil_div(d.kb_i, t.s_d);
+            dn.n_rows = d.H; dn.k_len = d.I; dn.pro = PRO_SILU;
+            dn.in_parts = am.gu; dn.n_parts = t.s_gu; dn.part_stride = d.Bm * d.ngu; dn.in_ld = d.ngu;
+            dn.out = am.pd; dn.out_split_stride = d.Bm * d.H; dn.out_ld = d.H; dn.bias = kNone;
+            if (!emit_gemv(dn, d.rb_d, c_gu, c_d)) return false;
+            prev_done = c_d;
+        }
+        // ---- final norm + LM head
+        Instr h{};
+        h.op = OP_GEMV; h.flags = (t.mfma ? F_MFMA : 0u) | F_LOGITS; h.ref_seq = d.L * 8 + ST_HEAD; h.layer = d.L;
+        h.w_chunk = wm.head; h.kbt = d.kb_h; h.S = 1; h.nkb = d.kb_h;
+        h.n_rows = d.V; h.k_len = d.H; h.pro = PRO_RESID_NORM;
+        h.in_base = am.xb; h.in_parts = am.pd; h.n_parts = t.s_d; h.part_stride = d.Bm * d.H; h.in_ld = d.H;
+        h.xs_out = am.xa; h.gain = wm.g_final;
+        h.out = 0; h.out_split_stride = 0; h.out_ld = d.V; h.bias = kNone;
+        if (!emit_gemv(h, d.rb_v, prev_done, kNone)) return false;
+        // the LM head never stores a residual slice
+        for (auto &lst : lists)
+            for (auto &I : lst)
+                if (I.op == OP_GEMV && (I.flags & F_LOGITS)) { I.xs_lo = 0; I.xs_hi = 0; }
+        max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d));
+        return true;
+    }
+};
+
+// A split must leave every unit at least one k block; ragged last units are fine.
+static bool split_ok(int kbt, int s) { return s >= 1 && s <= kbt && ceil_div(kbt, s) * (s - 1) < kbt; }
+
+// ---------------------------------------------------------------- replay (shared by simulator and verifier)
+// Walks the per-workgroup lists as the kernel does: a task may start when all the counters it
+// waits on have received their signals.  visit(wg, idx, instr) is called in a valid execution
+// order.  Returns false on deadlock (some list cannot finish).
+template <class F>
+static bool replay(const mk_schedule *s, F &&visit, std::string *why)
+{
+    const int n_wg = s->n_wg, mi = s->max_instr;
+    std::vector<int> pc(n_wg, 0);
+    std::vector<uint32_t> got(s->n_counters, 0);
+    const Instr *all = (const Instr *)s->instr.data();
+    bool progress = true;
+    size_t remaining = 0;
+    for (int w = 0; w < n_wg; ++w)
+        for (int i = 0; i < mi && all[(size_t)w * mi + i].op != OP_END; ++i) ++remaining;
+    while (remaining && progress) {
+        progress = false;
+        for (int w = 0; w < n_wg; ++w) {
+            while (pc[w] < mi) {
+                const Instr &I = all[(size_t)w * mi + pc[w]];
+                if (I.op == OP_END) break;
+                bool ready = true;
+                for (int k = 0; k < 2; ++k)
+                    if (I.wait_ctr[k] != kNone) {
+                        if (I.wait_ctr[k] >= (uint32_t)s->n_counters) { if (why) *why = "wait on a counter that does not exist"; return false; }
+                        if (got[I.wait_ctr[k]] < I.wait_cnt[k]) ready = false;
+                    }
+                if (!ready) break;
+                visit(w, pc[w], I);
+                if (I.sig_ctr != kNone) {
+                    if (I.sig_ctr >= (uint32_t)s->n_counters) { if (why) *why = "signal to a counter that does not exist"; return false; }
+                    ++got[I.sig_ctr];
+                }
+                ++pc[w]; --remaining; progress = true;
+            }
+        }
+    }
+    if (remaining) {
+        if (why) {
+            char buf[160];
+            for (int w = 0; w < n_wg; ++w) {
+                const Instr &I = all[(size_t)w * mi + pc[w]];
+                if (pc[w] < mi && I.op != OP_END) {
+                    snprintf(buf, sizeof buf, "deadlock: workgroup %d stuck at instruction %d (ref_seq %u) waiting on counter %u",
+                             w, pc[w], I.ref_seq, I.wait_ctr[0]);
+                    *why = buf;
+                    break;
+                }
+            }
+        }
+        return false;
+    }
+    return true;
+}
+
+static uint32_t task_chunks(const Instr &I)
+{
+    uint32_t c0 = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb, ue = I.u0 + I.nu;
+    uint32_t c1 = (ue / I.S) * I.kbt + (ue % I.S) * I.nkb;
+    return c1 - c0;
+}
+
+// Pipeline cost model (Sec. 4.2.2 Step 3-4).  Per workgroup two timelines: the weight stream
+// (HBM -> registers / LDS pages) and the consumer.  Without an LDS ring only the first
+// prefetch window of a task overlaps its dependency wait; with a ring the stream runs ahead of
+// the consumer by up to the ring capacity (page states: Locked while loading, Ready once
+// landed, Empty again when consumed).
+static SimResult simulate(const mk_schedule *s)
+{
+    const double bw_chip = 8.0e6 * 0.70;                         // bytes per microsecond the chip sustains
+    const double bw_wg = bw_chip / s->n_wg;
+    const double sync_us = 1.8, pro_us_per_kfloat = 0.06, task_us = 0.35, sig_us = 0.6;
+    const double ring_bytes = (double)s->tl.ring_pages * s->tl.page_bytes;
+    const double window = ring_bytes > 0 ? ring_bytes : (double)(kPrefetch * kWaves * kChunkBytes);
+    std::vector<double> t_cons(s->n_wg, 0.0), t_load(s->n_wg, 0.0), busy(s->n_wg, 0.0);
+    std::vector<double> ctr_done(s->n_counters, 0.0);
+    const Dims &d = s->dm;
+    replay(s, [&](int w, int, const Instr &I) {
+        double dep = 0.0;
+        for (int k = 0; k < 2; ++k)
+            if (I.wait_ctr[k] != kNone) dep = std::max(dep, ctr_done[I.wait_ctr[k]] + sync_us);
+        double bytes = 0.0, pro = 0.0;
+        if (I.op == OP_GEMV) {
+            bytes = (double)task_chunks(I) * kChunkBytes;
+            if (!(I.flags & F_SKIP_PRO)) {
+                double fl = (I.pro == PRO_EMBED_NORM || I.pro == PRO_RESID_NORM)
+                                ? (double)d.H * (1 + I.n_parts) : (double)I.xs_hi * kChunkK * I.n_parts * (I.pro == PRO_SILU ? 2 : 1);
+                pro = 0.25 + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
+            }
+        } else if (I.op == OP_ATT) {
+            bytes = (double)d.Tm / s->tl.nc * d.d * 4.0;
+            pro = 0.5;
+        } else {
+            pro = 0.3 + s->tl.nc * 0.01;
+        }
+        // weight stream: may start once the ring has room, i.e. `window` bytes ahead of the consumer
+        double lead = std::min(bytes, window);
+        double load_start = std::max(t_load[w], t_cons[w] - lead / bw_wg);   // earliest the stream can begin this task
+        load_start = std::max(load_start, 0.0);
+        double start = std::max(t_cons[w], dep);
+        // bytes beyond the window can only stream while the consumer drains
+        double stream_end = std::max(load_start + lead / bw_wg, start + pro) + (bytes - lead) / bw_wg;
+        double end = std::max(start + pro, stream_end) + task_us + (I.sig_ctr != kNone ? sig_us : 0.0);
+        busy[w] += bytes / bw_wg;
+        t_load[w] = stream_end;
+        t_cons[w] = end;
+        if (I.sig_ctr != kNone) ctr_done[I.sig_ctr] = std::max(ctr_done[I.sig_ctr], end);
+    }, nullptr);
+    SimResult r;
+    r.makespan_us = *std::max_element(t_cons.begin(), t_cons.end());
+    double b = std::accumulate(busy.begin(), busy.end(), 0.0);
+    r.duty = r.makespan_us > 0 ? b / (r.makespan_us * s->n_wg) : 0.0;
+    return r;
+}
+
+// ---------------------------------------------------------------- assemble a schedule object from a tiling
+static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_schedule *s)
+{
+    s->cfg = cfg; s->dm = d; s->tl = t;
+    plan_weights(cfg, d, s->wm);
+    plan_act(d, t, s->am);
+    Builder b(cfg, d, t, s->wm, s->am);
+    if (!b.build()) return MK_EINFEASIBLE;
+    s->n_wg = cfg.n_workgroups;
+    size_t mx = 0;
+    for (auto &l : b.lists) mx = std::max(mx, l.size());
+    s->max_instr = (int)mx + 1;
+    s->n_counters = (int)b.ctr_signals.size();
+    s->n_tasks = b.n_tasks;
+    s->instr.assign((size_t)s->n_wg * s->max_instr * kInstrDwords, 0u);
+    std::vector<uint32_t> seqs;
+    for (int w = 0; w < s->n_wg; ++w) {
+        memcpy(s->instr.data() + (size_t)w * s->max_instr * kInstrDwords, b.lists[w].data(), b.lists[w].size() * sizeof(Instr));
+        for (auto &I : b.lists[w]) seqs.push_back(I.ref_seq);
+    }
+    std::sort(seqs.begin(), seqs.end());
+    seqs.erase(std::unique(seqs.begin(), seqs.end()), seqs.end());
+    s->ref_seqs = seqs;
+    s->lds_red_bytes = b.lb.red_bytes;
+    s->lds_xs_off = kLdsRed + b.lb.red_bytes;
+    s->lds_total = (uint32_t)align_up(s->lds_xs_off + b.max_xs_bytes, 256);
+    if (s->lds_total + (uint64_t)t.ring_pages * t.page_bytes > (uint64_t)kLdsMax) return MK_EINFEASIBLE;
+    // workspace layout
+    Layout &L = s->lay;
+    uint64_t off = 0;
+    L.weights = off; off = align_up(off + s->wm.n_chunks * kChunkBytes, 4096);
+    L.vecs = off; off = align_up(off + s->wm.n_vec * 2, 4096);
+    L.rope = off; off = align_up(off + (uint64_t)d.Tm * d.d * 4, 4096);
+    L.act = off; off = align_up(off + s->am.n_floats * 4, 4096);
+    L.counters = off; off = align_up(off + (uint64_t)s->n_counters * kCounterStride * 4, 4096);
+    L.instr = off; off = align_up(off + s->instr.size() * 4, 4096);
+    L.err = off; off = align_up(off + 64, 4096);
+    L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 32 : 0), 4096);
+    L.total = off;
+    s->sim = simulate(s);
+    return MK_OK;
+}
+
+int build_schedule(const mk_config *cfg_in, mk_schedule **out)
+{
+    if (!cfg_in || !out) { set_error("null argument"); return MK_EINVAL; }
+    mk_config cfg = *cfg_in;
+    Dims d;
+    int rc = derive_dims(cfg, d);
+    if (rc) return rc;
+    const int mfma = cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
+    if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
+    if (cfg.ring_kb > 0) { set_error("mk_config: ring_kb > 0 is not available in this build"); return MK_EINVAL; }
+
+    auto cands = [](int fixed, int kbt, std::initializer_list<int> opts) {
+        std::vector<int> v;
+        if (fixed > 0) { v.push_back(fixed); return v; }
+        for (int o : opts) if (split_ok(kbt, o)) v.push_back(o);
+        if (v.empty()) v.push_back(1);
+        return v;
+    };
+    std::vector<int> c_qkv = cands(cfg.split_qkv, d.kb_h, {1, 2, 4});
+    std::vector<int> c_o = cands(cfg.split_o, d.kb_qd, {1, 2, 4, 8});
+    std::vector<int> c_gu = cands(cfg.split_gateup, d.kb_h, {1, 2, 4});
+    std::vector<int> c_d = cands(cfg.split_down, d.kb_i, {1, 2, 4, 8, 16});
+    std::vector<int> c_nc;
+    if (cfg.attn_chunks > 0) c_nc.push_back(cfg.attn_chunks);
+    else {
+        for (int nc = 1; nc <= 256; nc *= 2) {
+            if ((int64_t)d.Bm * d.nkv * nc > 2 * (int64_t)cfg.n_workgroups && nc > 1) break;
+            c_nc.push_back(nc);
+        }
+    }
+    for (int v : {cfg.split_qkv, cfg.split_o, cfg.split_gateup, cfg.split_down})
+        if (v < 0) { set_error("mk_config: negative split"); return MK_EINVAL; }
+    if ((cfg.split_qkv > 0 && !split_ok(d.kb_h, cfg.split_qkv)) || (cfg.split_o > 0 && !split_ok(d.kb_qd, cfg.split_o)) ||
+        (cfg.split_gateup > 0 && !split_ok(d.kb_h, cfg.split_gateup)) || (cfg.split_down > 0 && !split_ok(d.kb_i, cfg.split_down))) {
+        set_error("mk_config: a fixed split leaves an empty unit");
+        return MK_EINVAL;
+    }
+
+    // coordinate descent over the tiling parameters, each candidate scored by the simulator
+    Tiling best{};
+    best.s_qkv = c_qkv[0]; best.s_o = c_o[0]; best.s_gu = c_gu[0]; best.s_d = c_d[c_d.size() / 2];
+    best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
+    best.ring_pages = 0; best.page_bytes = 16 * 1024; best.n_stage = 1;
+    int tried = 0, pruned = 0;
+    double best_ms = -1, best_duty = 0;
+    auto eval = [&](const Tiling &t, double &ms, double &duty) {
+        mk_schedule tmp{};
+        ++tried;
+        int r = assemble(cfg, d, t, &tmp);
+        if (r != MK_OK) { ++pruned; return false; }
+        ms = tmp.sim.makespan_us; duty = tmp.sim.duty;
+        return true;
+    };
+    struct Dim { int Tiling::*field; std::vector<int> *vals; };
+    Dim dimsv[] = {{&Tiling::s_qkv, &c_qkv}, {&Tiling::s_o, &c_o}, {&Tiling::s_gu, &c_gu}, {&Tiling::s_d, &c_d}, {&Tiling::nc, &c_nc}};
+    {
+        double ms, du;
+        if (eval(best, ms, du)) { best_ms = ms; best_duty = du; }
+    }
+    for (int round = 0; round < 2; ++round)
+        for (auto &dm : dimsv) {
+            if (dm.vals->size() < 2) continue;
+            for (int v : *dm.vals) {
+                Tiling t = best;
+                t.*(dm.field) = v;
+                if (t.*(dm.field) == best.*(dm.field) && best_ms >= 0) continue;
+                double ms, du;
+                if (!eval(t, ms, du)) continue;
+                if (best_ms < 0 || ms < best_ms - 1e-9 || (std::fabs(ms - best_ms) <= 1e-9 && du > best_duty)) {
+                    best = t; best_ms = ms; best_duty = du;
+                }
+            }
+        }
+    if (best_ms < 0) { set_error("no tiling candidate fits the LDS budget"); return MK_EINFEASIBLE; }
+
+    mk_schedule *s = new mk_schedule{};
+    rc = assemble(cfg, d, best, s);
+    if (rc != MK_OK) { delete s; set_error("assembling the chosen candidate failed"); return rc; }
+    s->cand_tried = tried; s->cand_pruned = pruned;
+    rc = verify_schedule(s);
+    if (rc != MK_OK) { delete s; return rc; }
+    *out = s;
+    return MK_OK;
+}
+
+// ---------------------------------------------------------------- verifier
+namespace {
+struct Access { uint32_t lo, hi; bool write; };
+
+// Memory footprint of one task on the activation region, derived from the instruction alone.
+void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &out)
+{
+    const Dims &d = s->dm;
+    out.clear();
+    auto rd = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), false}); };
+    auto wr = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), true}); };
+    if (I.op == OP_GEMV) {
+        if (!(I.flags & F_SKIP_PRO)) {
+            for (int b = 0; b < d.Bm; ++b) {
+                if (I.pro == PRO_RESID_NORM) {
+                    rd(I.in_base + (uint64_t)b * I.in_ld, d.H);
+                    for (uint32_t p = 0; p < I.n_parts; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld, d.H);
+                } else if (I.pro == PRO_PLAIN || I.pro == PRO_SILU) {
+                    uint64_t k0 = (uint64_t)I.xs_lo * kChunkK, k1 = std::min<uint64_t>(k0 + (uint64_t)I.xs_hi * kChunkK, I.k_len);
+                    if (k1 > k0) {
+                        uint64_t lo = k0, n = k1 - k0;
+                        if (I.pro == PRO_SILU) { lo = (k0 / 16) * 32; n = (k1 + 15) / 16 * 32 - lo; }
+                        for (uint32_t p = 0; p < I.n_parts; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld + lo, n);
+                    }
+                }
+                if ((I.pro == PRO_RESID_NORM || I.pro == PRO_EMBED_NORM) && I.xs_hi > I.xs_lo)
+                    wr(I.xs_out + (uint64_t)b * I.in_ld + I.xs_lo, I.xs_hi - I.xs_lo);
+            }
+        }
+        if (!(I.flags & F_LOGITS)) {
+            for (uint32_t u = I.u0; u < I.u0 + I.nu; ++u)
+                for (int b = 0; b < d.Bm; ++b)
+                    wr(I.out + (uint64_t)(u % I.S) * I.out_split_stride + (uint64_t)b * I.out_ld + (uint64_t)(u / I.S) * 16, 16);
+        }
+    } else if (I.op == OP_ATT) {
+        const InstrAtt &A = *(const InstrAtt *)&I;
+        for (uint32_t p = 0; p < A.n_parts; ++p) {
+            uint64_t base = A.in_parts + (uint64_t)p * A.part_stride + (uint64_t)A.b * A.in_ld;
+            rd(base + (uint64_t)A.g * d.G * d.d, (uint64_t)d.G * d.d);
+            rd(base + d.qd + (uint64_t)A.g * d.d, d.d);
+            rd(base + d.qd + d.kvd + (uint64_t)A.g * d.d, d.d);
+        }
+        for (int h = 0; h < d.G; ++h)
+            wr(A.out + (((uint64_t)A.b * d.nq + A.g * d.G + h) * A.nc + A.c) * (d.d + 2), d.d + 2);
+    } else if (I.op == OP_COMB) {
+        const InstrAtt &A = *(const InstrAtt *)&I;
+        for (uint32_t h = A.h0; h < A.h0 + A.nh; ++h) {
+            rd(A.out + (((uint64_t)A.b * d.nq + h) * A.nc) * (d.d + 2), (uint64_t)A.nc * (d.d + 2));
+            wr(A.o_out + (uint64_t)A.b * A.o_ld + (uint64_t)h * d.d, d.d);
+        }
+    }
+}
+}  // namespace
+
+int verify_schedule(const mk_schedule *s)
+{
+    if (!s) { set_error("null schedule"); return MK_EINVAL; }
+    char buf[256];
+    auto fail = [&](const std::string &m) { set_error("schedule verification failed: " + m); return MK_ESCHED; };
+    const int n_wg = s->n_wg, mi = s->max_instr;
+    const Dims &d = s->dm;
+    const Instr *all = (const Instr *)s->instr.data();
+    if (n_wg < 1 || mi < 1 || (int)s->instr.size() != n_wg * mi * kInstrDwords) return fail("malformed instruction array");
+    if (mi > 65535) return fail("instruction list too long");
+
+    // (1) every list ends with END and holds known opcodes; counters: wait target == signals per step
+    std::vector<uint32_t> signals(s->n_counters, 0);
+    std::vector<int> cnt(n_wg, 0);
+    for (int w = 0; w < n_wg; ++w) {
+        int i = 0;
+        for (; i < mi; ++i) {
+            const Instr &I = all[(size_t)w * mi + i];
+            if (I.op == OP_END) break;
+            if (I.op != OP_GEMV && I.op != OP_ATT && I.op != OP_COMB) return fail("unknown opcode");
+            if (I.sig_ctr != kNone) {
+                if (I.sig_ctr >= (uint32_t)s->n_counters) return fail("signal to a counter that does not exist");
+                ++signals[I.sig_ctr];
+            }
+        }
+        if (i == mi) return fail("instruction list without END");
+        cnt[w] = i;
+    }
+    for (int w = 0; w < n_wg; ++w)
+        for (int i = 0; i < cnt[w]; ++i) {
+            const Instr &I = all[(size_t)w * mi + i];
+            for (int k = 0; k < 2; ++k)
+                if (I.wait_ctr[k] != kNone) {
+                    if (I.wait_ctr[k] >= (uint32_t)s->n_counters) return fail("wait on a counter that does not exist");
+                    if (I.wait_cnt[k] != signals[I.wait_ctr[k]]) {
+                        snprintf(buf, sizeof buf, "workgroup %d instruction %d waits for %u signals of counter %u, which receives %u",
+                                 w, i, I.wait_cnt[k], I.wait_ctr[k], signals[I.wait_ctr[k]]);
+                        return fail(buf);
+                    }
+                }
+        }
+
+    // (2) every tile of every operator exactly once
+    {
+        std::map<uint32_t, std::vector<std::pair<uint32_t, uint32_t>>> units;   // ref_seq -> [u0, u1)
+        std::map<uint32_t, std::vector<uint32_t>> keys;
+        for (int w = 0; w < n_wg; ++w)
+            for (int i = 0; i < cnt[w]; ++i) {
+                const Instr &I = all[(size_t)w * mi + i];
+                if (I.op == OP_GEMV) {
+                    if (I.nu == 0 || I.S == 0 || I.nkb == 0) return fail("empty GEMV task");
+                    units[I.ref_seq].push_back({I.u0, I.u0 + I.nu});
+                } else {
+                    const InstrAtt &A = *(const InstrAtt *)&I;
+                    keys[I.ref_seq].push_back(I.op == OP_ATT ? (A.b * d.nkv + A.g) * A.nc + A.c : A.b * d.nq + A.h0);
+                }
+            }
+        for (int l = 0; l <= d.L; ++l) {
+            struct { uint32_t st; uint32_t total; } g[] = {
+                {ST_QKV, (uint32_t)d.rb_qkv * s->tl.s_qkv}, {ST_O, (uint32_t)d.rb_o * s->tl.s_o},
+                {ST_GU, (uint32_t)d.rb_gu * s->tl.s_gu}, {ST_DOWN, (uint32_t)d.rb_d * s->tl.s_d}, {ST_HEAD, (uint32_t)d.rb_v}};
+            for (auto &e : g) {
+                if ((l == d.L) != (e.st == ST_HEAD)) continue;
+                auto &v = units[l * 8 + e.st];
+                std::sort(v.begin(), v.end());
+                uint32_t at = 0;
+                for (auto &r : v) {
+                    if (r.first != at) { snprintf(buf, sizeof buf, "operator %u of layer %d: unit %u missing or duplicated", e.st, l, at); return fail(buf); }
+                    at = r.second;
+                }
+                if (at != e.total) { snprintf(buf, sizeof buf, "operator %u of layer %d covers %u of %u units", e.st, l, at, e.total); return fail(buf); }
+            }
+            if (l < d.L) {
+                struct { uint32_t st; uint32_t total; } k2[] = {{ST_ATT, (uint32_t)(d.Bm * d.nkv * s->tl.nc)}, {ST_COMB, (uint32_t)(d.Bm * d.nq)}};
+                for (auto &e : k2) {
+                    auto &v = keys[l * 8 + e.st];
+                    std::sort(v.begin(), v.end());
+                    if (v.size() != e.total) { snprintf(buf, sizeof buf, "operator %u of layer %d has %zu of %u tasks", e.st, l, v.size(), e.total); return fail(buf); }
+                    for (uint32_t i = 0; i < e.total; ++i) if (v[i] != i) return fail("attention task missing or duplicated");
+                }
+            }
+        }
+    }
+
+    // (3) replay with blocking waits: terminates, and yields happens-before vector clocks.
+    //     vc[task][w] = number of leading instructions of workgroup w that happen before the task starts.
+    std::vector<size_t> first(n_wg + 1, 0);
+    for (int w = 0; w < n_wg; ++w) first[w + 1] = first[w] + cnt[w];
+    const size_t n_tasks = first[n_wg];
+    std::vector<uint16_t> vc(n_tasks * n_wg, 0);
+    std::vector<uint16_t> cvc((size_t)s->n_counters * n_wg, 0);
+    std::string why;
+    bool ok = replay(s, [&](int w, int i, const Instr &I) {
+        uint16_t *me = vc.data() + (first[w] + i) * n_wg;
+        if (i > 0) memcpy(me, vc.data() + (first[w] + i - 1) * n_wg, sizeof(uint16_t) * n_wg);
+        me[w] = (uint16_t)i;
+        for (int k = 0; k < 2; ++k)
+            if (I.wait_ctr[k] != kNone) {
+                const uint16_t *c = cvc.data() + (size_t)I.wait_ctr[k] * n_wg;
+                for (int x = 0; x < n_wg; ++x) me[x] = std::max(me[x], c[x]);
+            }
+        if (I.sig_ctr != kNone) {
+            uint16_t *c = cvc.data() + (size_t)I.sig_ctr * n_wg;
+            for (int x = 0; x < n_wg; ++x) c[x] = std::max(c[x], me[x]);
+            c[w] = std::max<uint16_t>(c[w], (uint16_t)(i + 1));
+        }
+    }, &why);
+    if (!ok) return fail(why.empty() ? "replay did not terminate" : why);
+    auto hb = [&](uint32_t a, uint32_t b) {   // task ids: does a happen before b?
+        int wa = (int)(std::upper_bound(first.begin(), first.end(), (size_t)a) - first.begin()) - 1;
+        int ia = (int)(a - first[wa]);
+        int wb = (int)(std::upper_bound(first.begin(), first.end(), (size_t)b) - first.begin()) - 1;
+        int ib = (int)(b - first[wb]);
+        if (wa == wb) return ia < ib;
+        return vc[(size_t)b * n_wg + wa] >= (uint16_t)(ia + 1);
+    };
+
+    // (4) walk the tasks in topological (operator) order with a last-writers table: every
+    //     read-after-write, write-after-read and write-after-write pair must be ordered.
+    std::vector<uint32_t> order(n_tasks);
+    std::iota(order.begin(), order.end(), 0u);
+    auto instr_of = [&](uint32_t t) -> const Instr & {
+        int w = (int)(std::upper_bound(first.begin(), first.end(), (size_t)t) - first.begin()) - 1;
+        return all[(size_t)w * mi + (t - first[w])];
+    };
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return instr_of(a).ref_seq < instr_of(b).ref_seq; });
+    // F_SKIP_PRO is only legal directly after a GEMV of the same operator instance with the same staged input
+    for (int w = 0; w < n_wg; ++w)
+        for (int i = 0; i < cnt[w]; ++i) {
+            const Instr &I = all[(size_t)w * mi + i];
+            if (I.op == OP_GEMV && (I.flags & F_SKIP_PRO)) {
+                if (i == 0) return fail("first instruction skips its prologue");
+                const Instr &Pv = all[(size_t)w * mi + i - 1];
+                bool same = Pv.op == OP_GEMV && Pv.ref_seq == I.ref_seq && Pv.pro == I.pro;
+                if (same && (I.pro == PRO_PLAIN || I.pro == PRO_SILU)) same = Pv.xs_lo == I.xs_lo && Pv.xs_hi == I.xs_hi;
+                if (!same) return fail("prologue skipped although LDS does not hold this task's input");
+            }
+        }
+    const uint32_t BK = 256;                                   // floats per bucket
+    const size_t n_b = (s->am.n_floats + BK - 1) / BK + 1;
+    struct Rec { uint32_t lo, hi, task; };
+    std::vector<std::vector<Rec>> reads(n_b);
+    std::map<uint32_t, Rec> writers;                           // lo -> non-overlapping last-writer intervals
+    std::vector<Access> acc;
+    for (uint32_t t : order) {
+        const Instr &I = instr_of(t);
+        decode_accesses(s, I, acc);
+        for (const Access &a : acc) {
+            if (a.hi > s->am.n_floats) return fail("task touches memory outside the activation region");
+            if (!a.write) {
+                // RAW: the whole range must have been written earlier in this step, by tasks ordered before us
+                uint32_t at = a.lo;
+                auto it = writers.upper_bound(a.lo);
+                if (it != writers.begin()) --it;
+                for (; it != writers.end() && it->second.lo < a.hi; ++it) {
+                    const Rec &r = it->second;
+                    if (r.hi <= a.lo) continue;
+                    if (r.lo > at) break;
+                    if (!hb(r.task, t)) {
+                        snprintf(buf, sizeof buf, "read-after-write not ordered: task ref_seq %u reads [%u,%u) written by ref_seq %u",
+                                 I.ref_seq, a.lo, a.hi, instr_of(r.task).ref_seq);
+                        return fail(buf);
+                    }
+                    at = std::max(at, r.hi);
+                }
+                if (at < a.hi) {
+                    snprintf(buf, sizeof buf, "task ref_seq %u reads [%u,%u) that no earlier task of the step wrote (from %u)", I.ref_seq, a.lo, a.hi, at);
+                    return fail(buf);
+                }
+                for (size_t bk = a.lo / BK; bk <= (a.hi - 1) / BK; ++bk) reads[bk].push_back({a.lo, a.hi, t});
+            } else {
+                for (size_t bk = a.lo / BK; bk <= (a.hi - 1) / BK; ++bk)
+                    for (const Rec &r : reads[bk])
+                        if (r.lo < a.hi && a.lo < r.hi && r.task != t && !hb(r.task, t)) {
+                            snprintf(buf, sizeof buf, "write-after-read not ordered: ref_seq %u overwrites [%u,%u) still read by ref_seq %u",
+                                     I.ref_seq, a.lo, a.hi, instr_of(r.task).ref_seq);
+                            return fail(buf);
+                        }
+                // WAW against the last writers, then replace them
+                auto it = writers.upper_bound(a.lo);
+                if (it != writers.begin()) --it;
+                std::vector<Rec> keep;
+                while (it != writers.end() && it->second.lo < a.hi) {
+                    Rec r = it->second;
+                    if (r.hi <= a.lo) { ++it; continue; }
+                    if (r.task != t && !hb(r.task, t)) {
+                        snprintf(buf, sizeof buf, "write-after-write not ordered on [%u,%u): ref_seq %u vs %u", a.lo, a.hi, I.ref_seq, instr_of(r.task).ref_seq);
+                        return fail(buf);
+                    }
+                    if (r.lo < a.lo) keep.push_back({r.lo, a.lo, r.task});
+                    if (r.hi > a.hi) keep.push_back({a.hi, r.hi, r.task});
+                    it = writers.erase(it);
+                }
+                for (auto &k : keep) writers[k.lo] = k;
+                writers[a.lo] = {a.lo, a.hi, t};
+            }
+        }
+    }
+    return MK_OK;
+}
+
+// ---------------------------------------------------------------- serialisation
+namespace {
+struct BlobHeader {
+    uint32_t magic, version;
+    mk_config cfg;
+    Tiling tl;
+    int32_t n_wg, max_instr, n_counters, n_tasks;
+    uint32_t lds_red_bytes, lds_xs_off, lds_total;
+    double sim_makespan, sim_duty;
+    int32_t cand_tried, cand_pruned;
+    uint64_t n_instr_words;
+};
+constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
+constexpr uint32_t kVersion = 1;
+}  // namespace
+
+int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)
+{
+    if (!s || !bytes) { set_error("null argument"); return MK_EINVAL; }
+    size_t need = sizeof(BlobHeader) + s->instr.size() * 4;
+    if (!buf) { *bytes = need; return MK_OK; }
+    if (*bytes < need) { *bytes = need; set_error("dump buffer too small"); return MK_ENOMEM; }
+    BlobHeader h{};
+    h.magic = kMagic; h.version = kVersion; h.cfg = s->cfg; h.tl = s->tl;
+    h.n_wg = s->n_wg; h.max_instr = s->max_instr; h.n_counters = s->n_counters; h.n_tasks = s->n_tasks;
+    h.lds_red_bytes = s->lds_red_bytes; h.lds_xs_off = s->lds_xs_off; h.lds_total = s->lds_total;
+    h.sim_makespan = s->sim.makespan_us; h.sim_duty = s->sim.duty;
+    h.cand_tried = s->cand_tried; h.cand_pruned = s->cand_pruned;
+    h.n_instr_words = s->instr.size();
+    memcpy(buf, &h, sizeof h);
+    memcpy((char *)buf + sizeof h, s->instr.data(), s->instr.size() * 4);
+    *bytes = need;
+    return MK_OK;
+}
+
+int load_schedule(const void *buf, size_t bytes, mk_schedule **out)
+{
+    if (!buf || !out || bytes < sizeof(BlobHeader)) { set_error("blob too small"); return MK_EINVAL; }
+    BlobHeader h;
+    memcpy(&h, buf, sizeof h);
+    if (h.magic != kMagic || h.version != kVersion) { set_error("not a schedule blob of this version"); return MK_EINVAL; }
+    if (bytes != sizeof h + h.n_instr_words * 4 || h.n_wg < 1 || h.max_instr < 1 ||
+        h.n_instr_words != (uint64_t)h.n_wg * h.max_instr * kInstrDwords) { set_error("truncated or inconsistent schedule blob"); return MK_EINVAL; }
+    Dims d;
+    mk_config cfg = h.cfg;
+    if (cfg.n_workgroups != h.n_wg) { set_error("schedule blob: workgroup count mismatch"); return MK_EINVAL; }
+    int rc = derive_dims(cfg, d);
+    if (rc) return rc;
+    // rebuild the memory maps from the stored tiling, then take the stored instruction lists
+    mk_schedule *s = new mk_schedule{};
+    rc = assemble(cfg, d, h.tl, s);
+    if (rc != MK_OK) { delete s; set_error("schedule blob: stored tiling does not assemble"); return rc; }
+    if (s->max_instr != h.max_instr || s->n_counters != h.n_counters) { delete s; set_error("schedule blob: layout mismatch"); return MK_EINVAL; }
+    memcpy(s->instr.data(), (const char *)buf + sizeof h, h.n_instr_words * 4);
+    s->cand_tried = h.cand_tried; s->cand_pruned = h.cand_pruned;
+    rc = verify_schedule(s);
+    if (rc != MK_OK) { delete s; return rc; }
+    *out = s;
+    return MK_OK;
+}
+
+}  // namespace mk

@@ -1,0 +1,83 @@
+// Host-side schedule object and the offline synthesis entry points
+// (paper Sec. 3 Phase I; Sec. 4.1.1; Sec. 4.2.2 Steps 1-4).  No HIP types.
+#pragma once
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/mk.h"
+#include "mk_isa.h"
+
+namespace mk {
+
+struct Dims {
+    int L, H, nq, nkv, d, I, V, Bm, Tm, G;
+    int qd, kvd, nqkv;       // fused QKV rows
+    int ipad;                // intermediate padded to 16
+    int ngu;                 // fused gate/up rows = 2 * ipad
+    int kb_h, kb_qd, kb_i;   // k blocks (32) of hidden, nq*d, intermediate (padded)
+    int rb_qkv, rb_o, rb_gu, rb_d, rb_v;   // row blocks (16)
+};
+
+struct Tiling {              // the searched parameters (Sec. 4.2.2 Step 3, "tiling parameter space")
+    int s_qkv, s_o, s_gu, s_d;   // K splits
+    int nc;                      // attention chunk tasks per (sequence, kv head)
+    int bs;                      // positions per attention block
+    int mfma;                    // 0 VALU, 1 MFMA
+    int ring_pages, page_bytes, n_stage;  // Eq. 1-2 outcome (0 pages: weights go straight to registers)
+};
+
+struct WeightMap {           // chunk / element offsets inside the workspace
+    std::vector<uint32_t> qkv, o, gu, down;   // first chunk per layer
+    uint32_t embed, head;
+    std::vector<uint32_t> g_attn, g_mlp, bias, qn, kn;  // bf16 element offsets per layer (kNone if absent)
+    uint32_t g_final;
+    uint64_t n_chunks, n_vec;
+};
+
+struct ActMap {              // float offsets inside the activation region
+    uint32_t xa, xb, pqkv, attp, o, po, gu, pd;
+    uint64_t n_floats;
+};
+
+struct SimResult {
+    double makespan_us, duty;
+};
+
+}  // namespace mk
+
+struct mk_schedule {
+    mk_config cfg;
+    mk::Dims dm;
+    mk::Tiling tl;
+    mk::WeightMap wm;
+    mk::ActMap am;
+    mk::Layout lay;
+    uint32_t lds_red_bytes, lds_xs_off, lds_total;
+    int n_wg, max_instr, n_counters, n_tasks;
+    std::vector<uint32_t> instr;          // [n_wg][max_instr][32]
+    std::vector<uint32_t> ref_seqs;       // distinct operator-instance ranks in topological order
+    mk::SimResult sim;
+    int cand_tried, cand_pruned;
+    // ---- run-time binding (filled by mk_bind_workspace / mk_load_weights)
+    char *ws;
+    size_t ws_bytes;
+    int device;
+    bool bound, loaded;
+    uint32_t epoch;
+    void *ev0, *ev1;
+    bool ev_valid;
+};
+
+namespace mk {
+void set_error(const std::string &msg);
+int build_schedule(const mk_config *cfg, mk_schedule **out);   // n_workgroups must be > 0 here
+int verify_schedule(const mk_schedule *s);
+int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes);
+int load_schedule(const void *buf, size_t bytes, mk_schedule **out);
+int64_t pages_available(int64_t smem_max, int64_t n_stage, int64_t instr_buf, int64_t semaphores,
+                        int64_t scratch, int64_t page_size);
+int64_t pipeline_stages(int64_t pages_total, int64_t pages_weight, int64_t pages_scale, int64_t pages_act,
+                        int64_t pages_per_stage);
+}  // namespace mk

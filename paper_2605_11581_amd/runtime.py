@@ -1,0 +1,62 @@
+"""Convenience wrapper: allocates the workspace with torch, uploads host weights, steps.
+
+Only memory management and call sequencing live here; all arithmetic is in libmk.so."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as mk
+
+
+def _dev_bits(a: np.ndarray, device) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
+
+
+class Decoder:
+    def __init__(self, model: Dict, device: str = "cuda:0", schedule_blob: Optional[bytes] = None, **opts):
+        self.device = torch.device(device)
+        self.model = dict(model)
+        if schedule_blob is not None:
+            self.h = mk.mk_schedule_load(schedule_blob)
+        else:
+            self.h = mk.mk_build_schedule(mk.make_config(model, device_id=self.device.index or 0, **opts))
+        self.stats = mk.mk_get_stats(self.h)
+        self.workspace = torch.empty(mk.mk_workspace_bytes(self.h), dtype=torch.uint8, device=self.device)
+        mk.mk_bind_workspace(self.h, self.workspace)
+
+    def load_weights(self, w: Dict) -> None:
+        """``w``: numpy uint16 bf16 bit patterns (per-layer entries are lists); staged layer by layer."""
+        dev: Dict = {}
+        for k, v in w.items():
+            if v is None:
+                dev[k] = None
+            elif isinstance(v, (list, tuple)):
+                dev[k] = [_dev_bits(a, self.device) for a in v]
+            else:
+                dev[k] = _dev_bits(v, self.device)
+        mk.mk_load_weights(self.h, dev)
+        torch.cuda.synchronize(self.device)   # the staged copies may be freed now
+
+    def new_kv(self, host: Optional[np.ndarray] = None) -> torch.Tensor:
+        m = self.model
+        shape = (m["n_layers"], 2, m["max_batch"], m["n_kv_heads"], m["max_context"], m["head_dim"])
+        if host is None:
+            return torch.zeros(shape, dtype=torch.int16, device=self.device)
+        assert host.shape == shape
+        return _dev_bits(host, self.device)
+
+    def step(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor, logits: torch.Tensor,
+             per_op: bool = False) -> None:
+        fn = mk.mk_decode_step_per_op if per_op else mk.mk_decode_step
+        fn(self.h, tokens, positions, kv, logits, int(tokens.numel()))
+
+    def check(self) -> None:
+        mk.mk_check(self.h)
+
+    def close(self) -> None:
+        if self.h is not None:
+            mk.mk_destroy(self.h)
+            self.h = None
