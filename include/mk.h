@@ -94,6 +94,8 @@ typedef struct mk_stats {
     double sim_makespan_us;          /* cost-model prediction for one step             */
     double sim_duty_cycle;           /* sum of busy time / (workgroups * makespan)     */
     int32_t candidates_tried, candidates_pruned;
+    int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head;  /* rows per 1 KB weight chunk, per matrix */
+    int32_t reserved;
 } mk_stats;
 
 /* Phase I (host only, touches no GPU unless n_workgroups == 0): build the
@@ -142,8 +144,9 @@ size_t mk_workspace_bytes(const mk_schedule *s);
 int mk_bind_workspace(mk_schedule *s, void *dev_workspace, size_t bytes, void *stream);
 
 /* Offline weight reorder (cf. Sec. 4.3.2 "weight reorder"): copy every matrix
- * into the workspace in the tile-major order the kernel streams (16 rows x 32
- * k per 1 KB chunk, lane-major).  Asynchronous on `stream`; the caller's
+ * into the workspace in the tile-major order the kernel streams (1 KB chunks of
+ * R rows x 512/R consecutive k, lane-major; R is chosen per matrix by the
+ * schedule search).  Asynchronous on `stream`; the caller's
  * buffers may be freed once the stream has been synchronised. */
 int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream);
 
@@ -176,6 +179,11 @@ int mk_check(mk_schedule *s, void *stream);
  * events recorded on the launch stream around the launch(es).  Synchronises
  * on the closing event. */
 int mk_last_step_ms(mk_schedule *s, float *ms);
+
+/* Change the run-time flags of a handle (only MK_F_TIMING may be toggled after
+ * the schedule was built; MK_F_TRACE is fixed at build time because it sizes
+ * the workspace). */
+int mk_set_flags(mk_schedule *s, uint32_t flags);
 
 /* Copy the per-task trace (MK_F_TRACE) to host: records of 4 x uint64
  * {wg<<32|instr, t_begin, t_dep_ready, t_end} in device wall-clock ticks.

@@ -50,13 +50,14 @@ class mk_stats(C.Structure):
                                          "lds_bytes", "ring_pages", "page_bytes", "n_stage")] + [
         ("_pad", C.c_int32), ("weight_bytes_per_step", C.c_int64), ("workspace_bytes", C.c_int64),
         ("sim_makespan_us", C.c_double), ("sim_duty_cycle", C.c_double),
-        ("candidates_tried", C.c_int32), ("candidates_pruned", C.c_int32)]
+        ("candidates_tried", C.c_int32), ("candidates_pruned", C.c_int32)] + [
+        (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "reserved")]
 
 
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",
            "mk_get_config", "mk_instr_count", "mk_instr_get", "mk_instr_set", "mk_pages_available",
            "mk_pipeline_stages", "mk_workspace_bytes", "mk_bind_workspace", "mk_load_weights", "mk_decode_step",
-           "mk_decode_step_per_op", "mk_check", "mk_last_step_ms", "mk_read_trace", "mk_destroy", "mk_last_error")
+           "mk_decode_step_per_op", "mk_check", "mk_last_step_ms", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
 
 _lib = None
 
@@ -96,6 +97,7 @@ def lib():
             getattr(L, n).argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.mk_check.argtypes = [H, C.c_void_p]
         L.mk_last_step_ms.argtypes = [H, C.POINTER(C.c_float)]
+        L.mk_set_flags.argtypes = [H, C.c_uint32]
         L.mk_read_trace.argtypes = [H, C.c_void_p, C.POINTER(C.c_size_t), C.c_void_p]
         L.mk_destroy.argtypes = [H]
         L.mk_destroy.restype = None
@@ -150,7 +152,7 @@ def mk_schedule_load(blob: bytes) -> C.c_void_p:
 def mk_get_stats(h) -> Dict:
     st = mk_stats()
     _chk(lib().mk_get_stats(h, C.byref(st)))
-    return {f[0]: getattr(st, f[0]) for f in mk_stats._fields_ if f[0] != "_pad"}
+    return {f[0]: getattr(st, f[0]) for f in mk_stats._fields_ if f[0] not in ("_pad", "reserved")}
 
 
 def mk_get_config(h) -> mk_config:
@@ -243,6 +245,10 @@ def mk_last_step_ms(h) -> float:
     ms = C.c_float(0)
     _chk(lib().mk_last_step_ms(h, C.byref(ms)))
     return float(ms.value)
+
+
+def mk_set_flags(h, flags: int) -> None:
+    _chk(lib().mk_set_flags(h, flags))
 
 
 def mk_read_trace(h, stream=None) -> np.ndarray:

@@ -40,11 +40,12 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
     P.batch = batch; P.max_batch = s->dm.Bm; P.max_context = s->dm.Tm;
     P.n_layers = s->dm.L; P.hidden = s->dm.H; P.n_q_heads = s->dm.nq; P.n_kv_heads = s->dm.nkv;
-    P.head_dim = s->dm.d; P.inter_pad = s->dm.ipad; P.vocab = s->dm.V;
+    P.head_dim = s->dm.d; P.inter_pad = s->gm.ipad; P.vocab = s->dm.V;
     P.qk_norm = s->cfg.qk_norm; P.rms_eps = s->cfg.rms_eps;
     P.epoch = s->epoch; P.spin_limit = s->cfg.spin_limit ? s->cfg.spin_limit : (1u << 20);
     P.max_instr = (uint32_t)s->max_instr; P.flags = s->cfg.flags;
-    P.embed_chunk = s->wm.embed; P.only_seq = mk::kNone;
+    P.embed_chunk = s->wm.embed; P.embed_kbt = (uint32_t)s->gm.head.kbt; P.embed_rlog = (uint32_t)s->gm.head.rlog;
+    P.only_seq = mk::kNone; P.act_bytes = (uint32_t)(s->am.n_floats * 4);
     return P;
 }
 
@@ -132,8 +133,11 @@ int mk_get_stats(const mk_schedule *s, mk_stats *o)
     o->attn_chunks = s->tl.nc; o->use_mfma = s->tl.mfma;
     o->lds_bytes = (int32_t)s->lds_total; o->ring_pages = s->tl.ring_pages; o->page_bytes = s->tl.page_bytes; o->n_stage = s->tl.n_stage;
     const mk::Dims &d = s->dm;
-    int64_t per_layer = (int64_t)d.rb_qkv * d.kb_h + (int64_t)d.rb_o * d.kb_qd + (int64_t)d.rb_gu * d.kb_h + (int64_t)d.rb_d * d.kb_i;
-    o->weight_bytes_per_step = (per_layer * d.L + (int64_t)d.rb_v * d.kb_h) * mk::kChunkBytes;
+    const mk::Geom &g = s->gm;
+    auto chunks = [](const mk::MatGeom &m) { return (int64_t)m.groups * m.kbt; };
+    int64_t per_layer = chunks(g.qkv) + chunks(g.o) + chunks(g.gu) + chunks(g.down);
+    o->weight_bytes_per_step = (per_layer * d.L + chunks(g.head)) * mk::kChunkBytes;
+    o->rows_qkv = g.qkv.R; o->rows_o = g.o.R; o->rows_gateup = g.gu.R; o->rows_down = g.down.R; o->rows_head = g.head.R;
     o->workspace_bytes = (int64_t)s->lay.total;
     o->sim_makespan_us = s->sim.makespan_us; o->sim_duty_cycle = s->sim.duty;
     o->candidates_tried = s->cand_tried; o->candidates_pruned = s->cand_pruned;
@@ -224,14 +228,14 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     return MK_OK;
 }
 
-static int repack(const void *src, int n_rows, int n_cols, char *ws, uint64_t wbase, uint32_t chunk0, uint32_t kbt,
-                  uint32_t rb0, uint32_t rb_stride, uint32_t n_rb, hipStream_t st)
+static int repack(const void *src, int n_rows, int n_cols, mk_schedule *s, uint32_t chunk0, const mk::MatGeom &m,
+                  uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups, hipStream_t st)
 {
     if (!src) { mk::set_error("mk_load_weights: a required matrix pointer is NULL"); return MK_EINVAL; }
-    size_t total = (size_t)n_rb * kbt * 64;
-    mk::u32x4 *dst = (mk::u32x4 *)(ws + wbase) + (size_t)chunk0 * 64;
+    size_t total = (size_t)n_groups * m.kbt * 64;
+    mk::u32x4 *dst = (mk::u32x4 *)(s->ws + s->lay.weights) + (size_t)chunk0 * 64;
     hipLaunchKernelGGL(mk_repack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t *)src, n_rows,
-                       n_cols, dst, kbt, rb0, rb_stride, n_rb);
+                       n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups);
     HIP_TRY(hipGetLastError());
     return MK_OK;
 }
@@ -253,7 +257,7 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
     const mk::Dims &d = s->dm;
     const mk::WeightMap &m = s->wm;
     char *ws = s->ws;
-    const uint64_t wb = s->lay.weights, vb = s->lay.vecs;
+    const uint64_t vb = s->lay.vecs;
     if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up || !w->w_down) {
         mk::set_error("mk_load_weights: a per-layer pointer table is NULL");
         return MK_EINVAL;
@@ -262,14 +266,18 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
     if (s->cfg.qk_norm && (!w->q_norm || !w->k_norm)) { mk::set_error("mk_load_weights: qk_norm set but a gain table is NULL"); return MK_EINVAL; }
     int rc;
 #define TRY(x) do { rc = (x); if (rc) return rc; } while (0)
+    const mk::Geom &g = s->gm;
     for (int l = 0; l < d.L; ++l) {
-        TRY(repack(w->wq[l], d.qd, d.H, ws, wb, m.qkv[l], d.kb_h, 0, 1, d.qd / 16, st));
-        TRY(repack(w->wk[l], d.kvd, d.H, ws, wb, m.qkv[l], d.kb_h, d.qd / 16, 1, d.kvd / 16, st));
-        TRY(repack(w->wv[l], d.kvd, d.H, ws, wb, m.qkv[l], d.kb_h, (d.qd + d.kvd) / 16, 1, d.kvd / 16, st));
-        TRY(repack(w->wo[l], d.H, d.qd, ws, wb, m.o[l], d.kb_qd, 0, 1, d.rb_o, st));
-        TRY(repack(w->w_gate[l], d.I, d.H, ws, wb, m.gu[l], d.kb_h, 0, 2, d.ipad / 16, st));
-        TRY(repack(w->w_up[l], d.I, d.H, ws, wb, m.gu[l], d.kb_h, 1, 2, d.ipad / 16, st));
-        TRY(repack(w->w_down[l], d.H, d.I, ws, wb, m.down[l], d.kb_i, 0, 1, d.rb_d, st));
+        const uint32_t R = (uint32_t)g.qkv.R;
+        TRY(repack(w->wq[l], d.qd, d.H, s, m.qkv[l], g.qkv, R, 0, 0, d.qd / R, st));
+        TRY(repack(w->wk[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, d.qd / R, d.kvd / R, st));
+        TRY(repack(w->wv[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, (d.qd + d.kvd) / R, d.kvd / R, st));
+        TRY(repack(w->wo[l], d.H, d.qd, s, m.o[l], g.o, (uint32_t)g.o.R, 0, 0, (uint32_t)g.o.groups, st));
+        // gate rows fill the lower half of every row group, up rows the upper half
+        const uint32_t half = (uint32_t)g.gu.R / 2;
+        TRY(repack(w->w_gate[l], d.I, d.H, s, m.gu[l], g.gu, half, 0, 0, (uint32_t)g.gu.groups, st));
+        TRY(repack(w->w_up[l], d.I, d.H, s, m.gu[l], g.gu, half, half, 0, (uint32_t)g.gu.groups, st));
+        TRY(repack(w->w_down[l], d.H, d.I, s, m.down[l], g.down, (uint32_t)g.down.R, 0, 0, (uint32_t)g.down.groups, st));
         TRY(copy_vec(w->attn_norm[l], d.H, ws, vb, m.g_attn[l], st));
         TRY(copy_vec(w->mlp_norm[l], d.H, ws, vb, m.g_mlp[l], st));
         if (s->cfg.qkv_bias) {
@@ -282,8 +290,8 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
             TRY(copy_vec(w->k_norm[l], d.d, ws, vb, m.kn[l], st));
         }
     }
-    TRY(repack(w->embed, d.V, d.H, ws, wb, m.embed, d.kb_h, 0, 1, d.rb_v, st));
-    if (!s->cfg.tie_embeddings) TRY(repack(w->lm_head, d.V, d.H, ws, wb, m.head, d.kb_h, 0, 1, d.rb_v, st));
+    TRY(repack(w->embed, d.V, d.H, s, m.embed, g.head, (uint32_t)g.head.R, 0, 0, (uint32_t)g.head.groups, st));
+    if (!s->cfg.tie_embeddings) TRY(repack(w->lm_head, d.V, d.H, s, m.head, g.head, (uint32_t)g.head.R, 0, 0, (uint32_t)g.head.groups, st));
     TRY(copy_vec(w->final_norm, d.H, ws, vb, m.g_final, st));
 #undef TRY
     s->loaded = true;
@@ -303,7 +311,7 @@ int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positio
     s->epoch += 1;
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
-    const bool timing = (s->cfg.flags & 2u) != 0;
+    const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());
@@ -319,7 +327,7 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     hipStream_t st = (hipStream_t)stream;
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
-    const bool timing = (s->cfg.flags & 2u) != 0;
+    const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     for (uint32_t seq : s->ref_seqs) {
         P.only_seq = seq;
@@ -354,9 +362,17 @@ int mk_check(mk_schedule *s, void *stream)
 int mk_last_step_ms(mk_schedule *s, float *ms)
 {
     if (!s || !ms || !s->ev_valid) { mk::set_error("no timed step"); return MK_ESTATE; }
-    if (!(s->cfg.flags & 2u)) { mk::set_error("step timing needs flag bit 1 (value 2) in mk_config.flags"); return MK_ESTATE; }
+    if (!(s->cfg.flags & MK_F_TIMING)) { mk::set_error("step timing needs flag bit 1 (value 2) in mk_config.flags"); return MK_ESTATE; }
     HIP_TRY(hipEventSynchronize((hipEvent_t)s->ev1));
     HIP_TRY(hipEventElapsedTime(ms, (hipEvent_t)s->ev0, (hipEvent_t)s->ev1));
+    return MK_OK;
+}
+
+int mk_set_flags(mk_schedule *s, uint32_t flags)
+{
+    if (!s) { mk::set_error("null schedule"); return MK_EINVAL; }
+    if ((flags ^ s->cfg.flags) & ~(uint32_t)MK_F_TIMING) { mk::set_error("only MK_F_TIMING can change after the build"); return MK_EINVAL; }
+    s->cfg.flags = flags;
     return MK_OK;
 }
 

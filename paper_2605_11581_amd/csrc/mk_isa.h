@@ -9,19 +9,22 @@
 #pragma once
 #include <stdint.h>
 
+#ifndef __HIPCC__
+#define __host__
+#define __device__
+#endif
+
 namespace mk {
 
 constexpr int kWgThreads = 256;        // 4 wavefronts of 64
 constexpr int kWaves = kWgThreads / 64;
 constexpr int kChunkBytes = 1024;      // one wavefront-wide 128-bit load: 16 rows x 32 k of bf16
-constexpr int kChunkRows = 16;
-constexpr int kChunkK = 32;
 constexpr int kInstrDwords = 32;
 constexpr uint32_t kNone = 0xffffffffu;
 constexpr int kMaxBatch = 8;
 constexpr int kMaxGroup = 8;           // q heads per kv head
 constexpr int kCounterStride = 32;     // dwords between counters (one 128-byte line each)
-constexpr int kPrefetch = 8;           // 128-bit weight loads a lane keeps in flight (direct-load path)
+constexpr int kPrefetch = 16;          // 128-bit weight loads a lane keeps in flight (direct-load path)
 
 // LDS map of a workgroup:
 //   [0, 256)    current instruction
@@ -44,11 +47,17 @@ enum Pro : uint32_t {
 };
 
 enum Flags : uint32_t {
-    F_SKIP_PRO = 1u,   // LDS already holds this task's input vector (same operator, previous task)
-    F_MFMA = 2u,       // matrix-core GEMV/thin GEMM instead of VALU FMA
-    F_LOGITS = 4u,     // output goes to the caller's logits buffer
-    F_NO_WAIT_FENCE = 8u
+    F_SKIP_PRO = 1u,    // LDS already holds this task's input vector (same operator, previous task)
+    F_MFMA = 2u,        // matrix-core GEMV/thin GEMM instead of VALU FMA
+    F_LOGITS = 4u,      // output goes to the caller's logits buffer
+    F_ADD_RESID = 8u,   // epilogue adds the residual row (needs S == 1): out = resid + W x
+    F_SILU_EPI = 16u    // epilogue of the fused gate/up matrix (needs S == 1): out = silu(gate) * up
 };
+
+// Weight chunk geometry.  A chunk is one wavefront-wide 128-bit load (1 KB): R rows x (512 / R)
+// consecutive k of bf16, lane = ksub * R + r holding W[row0 + r][k0 + 8 ksub .. + 8].  R is a
+// per-matrix tiling parameter (16 for the matrix-core path); rlog = log2 R.
+__host__ __device__ inline uint32_t chunk_k(uint32_t rlog) { return 512u >> rlog; }
 
 struct Instr {                 // 32 dwords
     uint32_t op;               // 0
@@ -58,21 +67,22 @@ struct Instr {                 // 32 dwords
     uint32_t wait_ctr[2];      // 4,5   counter index or kNone
     uint32_t wait_cnt[2];      // 6,7   signals per step the counter receives
     uint32_t sig_ctr;          // 8     counter to signal once the outputs are stored (kNone: none)
-    // ---- GEMV: units u0 .. u0+nu of a matrix; unit u = (row block u / S, split u % S)
+    // ---- GEMV: units u0 .. u0+nu of a matrix; unit u = (row group u / S of R rows, K split u % S)
     uint32_t w_chunk;          // 9   first 1 KB chunk of the matrix inside the weight region
-    uint32_t kbt;              // 10  k blocks per row block
-    uint32_t nkb;              // 11  k blocks per unit (last split of a row block may be shorter)
-    uint32_t S;                // 12  splits per row block
+    uint32_t kbt;              // 10  chunks per row group (whole K)
+    uint32_t nkb;              // 11  chunks per unit (last split of a row group may be shorter)
+    uint32_t S;                // 12  K splits per row group
     uint32_t u0;               // 13
     uint32_t nu;               // 14
     uint32_t n_rows;           // 15  valid output rows of the matrix
-    uint32_t pro;              // 16
-    uint32_t in_base;          // 17  float offset: residual base (RESID) / unused
-    uint32_t in_parts;         // 18  float offset of partial 0 (PRO_SILU: gate rows; up rows follow at +in_aux)
-    uint32_t n_parts;          // 19
+    uint32_t cfg;              // 16  pro [0:3] | rlog [4:7] | producer rlog (PRO_SILU) [8:11] | n_parts [16:23]
+    uint32_t in_base;          // 17  float offset of the residual base (norm prologues)
+    uint32_t in_parts;         // 18  float offset of partial 0 / of the plain input vector
+    uint32_t resid;            // 19  F_ADD_RESID: float offset of the residual rows added in the epilogue
     uint32_t part_stride;      // 20  floats between partials
     uint32_t in_ld;            // 21  floats between sequences (batch rows) of the input
-    uint32_t xs_lo, xs_hi;     // 22,23 slice of the new residual this task stores
+    uint32_t xs_lo, xs_hi;     // 22,23 norm prologues: slice of the new residual this task stores;
+                               //       plain prologues: first staged chunk and number of staged chunks
     uint32_t xs_out;           // 24  float offset of the residual store buffer
     uint32_t gain;             // 25  bf16 element offset of the norm gain in the vector region
     uint32_t out;              // 26  float offset of output partial 0
@@ -80,8 +90,16 @@ struct Instr {                 // 32 dwords
     uint32_t out_ld;           // 28  floats between sequences of the output
     uint32_t bias;             // 29  bf16 element offset of the bias or kNone
     uint32_t k_len;            // 30  true K (input elements beyond it are zero)
-    uint32_t in_aux;           // 31  PRO_SILU: float distance from gate rows to up rows; EMBED: unused
+    uint32_t spare;            // 31
 };
+__host__ __device__ inline uint32_t instr_pro(const Instr &I) { return I.cfg & 15u; }
+__host__ __device__ inline uint32_t instr_rlog(const Instr &I) { return (I.cfg >> 4) & 15u; }
+__host__ __device__ inline uint32_t instr_prod_rlog(const Instr &I) { return (I.cfg >> 8) & 15u; }
+__host__ __device__ inline uint32_t instr_nparts(const Instr &I) { return (I.cfg >> 16) & 255u; }
+__host__ __device__ inline uint32_t make_cfg(uint32_t pro, uint32_t rlog, uint32_t prod_rlog, uint32_t n_parts)
+{
+    return pro | (rlog << 4) | (prod_rlog << 8) | (n_parts << 16);
+}
 
 // ATT / COMB view of the same 32 dwords (fields 0..8 identical).
 struct InstrAtt {
@@ -114,7 +132,7 @@ struct Layout {
     uint64_t counters;   // uint32, one per 128-byte line
     uint64_t instr;      // Instr[n_wg][max_instr]
     uint64_t err;        // uint32[8] sticky error flags
-    uint64_t trace;      // uint64[n_wg][max_instr][4]
+    uint64_t trace;      // uint64[n_wg][max_instr][4]: task begin, dependencies met, prologue done, end
     uint64_t total;
 };
 
@@ -134,7 +152,9 @@ struct Params {
     uint32_t max_instr;
     uint32_t flags;
     uint32_t embed_chunk; // first chunk of the (repacked) embedding matrix
+    uint32_t embed_kbt, embed_rlog;
     uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
+    uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
 };
 
 }  // namespace mk

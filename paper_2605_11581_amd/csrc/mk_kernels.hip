@@ -42,10 +42,47 @@ __device__ __forceinline__ uint16_t f_to_bf(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Activations, partial sums and counters cross workgroups (and XCDs, whose L2 caches are not
+// coherent with each other) inside one launch.  They are moved with agent-scope relaxed
+// atomics -- write-through stores and cache-bypassing loads (the sc1 bit) -- so that no
+// L2-wide write-back / invalidate is ever needed; weights and the KV history are read-only
+// during a launch and use ordinary (nontemporal) loads.
+__device__ __forceinline__ float ld_act(const float *p)
+{
+    typedef const __attribute__((address_space(1))) uint32_t *gptr;
+    return __uint_as_float(__hip_atomic_load((gptr)(uintptr_t)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void st_act(float *p, float v)
+{
+    typedef __attribute__((address_space(1))) uint32_t *gptr;
+    __hip_atomic_store((gptr)(uintptr_t)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Cross-lane sums inside a 16-lane row with DPP (no LDS crossbar traffic).  Every step pairs
+// lanes symmetrically, so all lanes of the group end with bit-identical sums.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_sum8(float v)    // over aligned groups of 8 lanes
+{
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    return v;
+}
+__device__ __forceinline__ float row_sum16(float v)   // over a 16-lane row
+{
+    v = row_sum8(v);
+    v = dpp_add<0x140>(v);   // row_mirror
     return v;
 }
 
@@ -62,10 +99,8 @@ __device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t targe
 {
     uint32_t it = 0;
     while ((int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-        __builtin_amdgcn_s_sleep(1);
         if (++it > limit) return false;
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // later loads see the producers' stores
     return true;
 }
 
@@ -73,24 +108,46 @@ __device__ __forceinline__ int clamp_i(int v, int lo, int hi) { return v < lo ? 
 
 __device__ __forceinline__ int token_of(const Params &P, int b)
 {
-    int t = P.tokens[b];
+    int t = (int)rfl((uint32_t)P.tokens[b]);
     if (t < 0 || t >= P.vocab) { set_err(P, 1, 1u); t = clamp_i(t, 0, P.vocab - 1); }
     return t;
 }
 __device__ __forceinline__ int position_of(const Params &P, int b)
 {
-    int p = P.positions[b];
+    int p = (int)rfl((uint32_t)P.positions[b]);
     if (p < 0 || p >= P.max_context) { set_err(P, 1, 2u); p = clamp_i(p, 0, P.max_context - 1); }
     return p;
 }
 
-// Element (row, k) of a tile-major matrix whose first chunk is `chunk0`.
-__device__ __forceinline__ float tile_elem(const char *wbase, uint32_t chunk0, uint32_t kbt, int row, int k)
+// Element (row, k) of a tile-major matrix whose first chunk is `chunk0` (R = 1 << rlog rows per chunk).
+__device__ __forceinline__ float tile_elem(const char *wbase, uint32_t chunk0, uint32_t kbt, uint32_t rlog, int row, int k)
 {
-    size_t chunk = (size_t)chunk0 + (size_t)(row >> 4) * kbt + (size_t)(k >> 5);
-    int slot = ((k & 31) >> 3) * 16 + (row & 15);
+    const uint32_t R = 1u << rlog, ck = chunk_k(rlog);
+    size_t chunk = (size_t)chunk0 + (size_t)((uint32_t)row >> rlog) * kbt + (size_t)((uint32_t)k / ck);
+    uint32_t slot = (((uint32_t)k % ck) >> 3) * R + ((uint32_t)row & (R - 1));
     const uint16_t *p = (const uint16_t *)(wbase + chunk * kChunkBytes + slot * 16) + (k & 7);
     return bf_to_f(*p);
+}
+
+// 128-bit cache-bypassing (sc1) accesses to the activation region through a buffer descriptor;
+// the compiler tracks their completion, so several can be in flight per lane.
+struct ActBuf {
+    __amdgpu_buffer_rsrc_t r;
+};
+__device__ __forceinline__ ActBuf act_buf(const Params &P)
+{
+    ActBuf a;
+    a.r = __builtin_amdgcn_make_buffer_rsrc((void *)(P.ws + P.lay.act), 0, (int)P.act_bytes, 0x00020000);
+    return a;
+}
+constexpr int kAuxSc1 = 16;
+__device__ __forceinline__ f32x4 ld_act4(const ActBuf &a, uint32_t float_off)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(a.r, (int)(float_off * 4u), 0, kAuxSc1));
+}
+__device__ __forceinline__ void st_act4(const ActBuf &a, uint32_t float_off, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), a.r, (int)(float_off * 4u), 0, kAuxSc1);
 }
 
 // ---------------------------------------------------------------- GEMV task
@@ -99,59 +156,89 @@ __device__ __forceinline__ float tile_elem(const char *wbase, uint32_t chunk0, u
 //   MFMA path: bf16 planes [col][k], col = b * nterm + term, x = sum of its nterm bf16 terms;
 //              plane stride = k_stage * 2 + 16 bytes (bank skew)
 template <bool MFMA>
-__device__ __forceinline__ void store_x(char *xs, int b, int i, float y, int nterm, uint32_t plane_stride)
+__device__ __forceinline__ void store_x4(char *xs, int b, int i, f32x4 y, int nterm, uint32_t plane_stride)
 {
     if (!MFMA) {
-        ((float *)xs)[i] = y;
+        *(f32x4 *)(xs + (size_t)i * 4) = y;
     } else {
-        float r = y;
+        f32x4 r = y;
         for (int t = 0; t < nterm; ++t) {
-            uint16_t h = f_to_bf(r);
-            *(uint16_t *)(xs + (size_t)(b * nterm + t) * plane_stride + (size_t)i * 2) = h;
-            r -= bf_to_f(h);
+            uint16_t h0 = f_to_bf(r.x), h1 = f_to_bf(r.y), h2 = f_to_bf(r.z), h3 = f_to_bf(r.w);
+            uint2 pk;
+            pk.x = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            pk.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
+            *(uint2 *)(xs + (size_t)(b * nterm + t) * plane_stride + (size_t)i * 2) = pk;
+            r.x -= bf_to_f(h0); r.y -= bf_to_f(h1); r.z -= bf_to_f(h2); r.w -= bf_to_f(h3);
         }
     }
 }
 
 __device__ __forceinline__ int nterm_of(int batch) { return batch <= 5 ? 3 : 2; }
 
+constexpr int kQuadsPerThread = 4;   // hidden <= 4 * 4 * 256
+
 template <bool MFMA>
-__device__ void gemv_prologue(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, int batch)
+__device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, int batch)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     char *xs = lds + lp.xs_off;
     float *misc = (float *)(lds + kLdsMisc);
-    const float *act = (const float *)(P.ws + P.lay.act);
-    float *actw = (float *)(P.ws + P.lay.act);
+    const ActBuf ab = act_buf(P);
     const int nterm = nterm_of(batch);
-    const uint32_t pro = I.pro;
+    const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
 
     if (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM) {
-        const int H = P.hidden;
+        const int H = P.hidden, nq4 = H >> 2;
         const uint32_t plane_stride = (uint32_t)H * 2u + 16u;
         const uint16_t *gain = (const uint16_t *)(P.ws + P.lay.vecs) + I.gain;
-        const uint32_t kbtH = (uint32_t)H >> 5;
         for (int b = 0; b < batch; ++b) {
-            float v[16];
-            float ss = 0.f;
-            int tok = 0;
-            if (pro == PRO_EMBED_NORM) tok = token_of(P, b);
+            f32x4 v[kQuadsPerThread];
+            if (pro == PRO_EMBED_NORM) {
+                const int tok = token_of(P, b);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                int i = tid + j * kWgThreads;
-                float x = 0.f;
-                if (i < H) {
-                    if (pro == PRO_EMBED_NORM) {
-                        x = tile_elem(P.ws + P.lay.weights, P.embed_chunk, kbtH, tok, i);
-                    } else {
-                        x = act[I.in_base + (size_t)b * I.in_ld + i];
-                        for (uint32_t s = 0; s < I.n_parts; ++s)
-                            x += act[I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld + i];
+                for (int j = 0; j < kQuadsPerThread; ++j) {
+                    const int q = tid + j * kWgThreads;
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (q < nq4) {
+                        x.x = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, 4 * q);
+                        x.y = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, 4 * q + 1);
+                        x.z = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, 4 * q + 2);
+                        x.w = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, 4 * q + 3);
                     }
-                    if ((uint32_t)i >= I.xs_lo && (uint32_t)i < I.xs_hi) actw[I.xs_out + (size_t)b * I.in_ld + i] = x;
+                    v[j] = x;
                 }
-                v[j] = x;
-                ss += x * x;
+            } else {
+                const uint32_t row = I.in_base + (uint32_t)b * I.in_ld;
+#pragma unroll
+                for (int j = 0; j < kQuadsPerThread; ++j) {
+                    const int q = tid + j * kWgThreads;
+                    v[j] = ld_act4(ab, q < nq4 ? row + 4u * q : 0xfffffff0u);   // out of range reads return 0
+                }
+                // partial sums of the producer, four partials (x four quads) in flight at a time, added in order
+                for (uint32_t s0 = 0; s0 < n_parts; s0 += 4) {
+                    f32x4 t[4][kQuadsPerThread];
+#pragma unroll
+                    for (int ds = 0; ds < 4; ++ds) {
+                        const uint32_t prow = I.in_parts + (s0 + ds) * I.part_stride + (uint32_t)b * I.in_ld;
+#pragma unroll
+                        for (int j = 0; j < kQuadsPerThread; ++j) {
+                            const int q = tid + j * kWgThreads;
+                            t[ds][j] = ld_act4(ab, (q < nq4 && s0 + ds < n_parts) ? prow + 4u * q : 0xfffffff0u);
+                        }
+                    }
+#pragma unroll
+                    for (int ds = 0; ds < 4; ++ds)
+#pragma unroll
+                        for (int j = 0; j < kQuadsPerThread; ++j) v[j] += t[ds][j];
+                }
+            }
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < kQuadsPerThread; ++j) {
+                const int q = tid + j * kWgThreads;
+                if (q < nq4 && (uint32_t)(4 * q) >= I.xs_lo && (uint32_t)(4 * q) < I.xs_hi)
+                    st_act4(ab, I.xs_out + (uint32_t)b * I.in_ld + 4u * q, v[j]);
+                ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
             }
             ss = wave_sum(ss);
             float *slot = misc + (b & 1) * 8;
@@ -160,51 +247,75 @@ __device__ void gemv_prologue(const Params &P, const Instr &I, char *lds, const 
             float tot = slot[0] + slot[1] + slot[2] + slot[3];
             float inv = 1.0f / sqrtf(tot / (float)H + P.rms_eps);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                int i = tid + j * kWgThreads;
-                if (i < H) store_x<MFMA>(xs, b, i, v[j] * inv * bf_to_f(gain[i]), nterm, plane_stride);
+            for (int j = 0; j < kQuadsPerThread; ++j) {
+                const int q = tid + j * kWgThreads;
+                if (q < nq4) {
+                    uint2 gw = *(const uint2 *)(gain + 4 * q);
+                    f32x4 y;
+                    y.x = v[j].x * inv * bf_lo(gw.x); y.y = v[j].y * inv * bf_hi(gw.x);
+                    y.z = v[j].z * inv * bf_lo(gw.y); y.w = v[j].w * inv * bf_hi(gw.y);
+                    store_x4<MFMA>(xs, b, 4 * q, y, nterm, plane_stride);
+                }
             }
         }
     } else {
-        // PLAIN / SILU: stage k blocks [xs_lo, xs_lo + xs_hi) of the input
-        const int k0 = (int)I.xs_lo * kChunkK, kn = (int)I.xs_hi * kChunkK;
+        // PLAIN / SILU: stage chunks [xs_lo, xs_lo + xs_hi) of the input (whole-K chunk indices)
+        const uint32_t ck = chunk_k(instr_rlog(I));
+        const int k0 = (int)(I.xs_lo * ck), kn = (int)(I.xs_hi * ck);
         const uint32_t plane_stride = (uint32_t)kn * 2u + 16u;
+        const uint32_t prl = instr_prod_rlog(I), PR = 1u << prl;
         for (int b = 0; b < batch; ++b) {
-            for (int i = tid; i < kn; i += kWgThreads) {
-                int k = k0 + i;
-                float y = 0.f;
-                if ((uint32_t)k < I.k_len) {
-                    if (pro == PRO_PLAIN) {
-                        for (uint32_t s = 0; s < I.n_parts; ++s)
-                            y += act[I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld + k];
-                    } else {
-                        size_t gi = (size_t)(k >> 4) * 32 + (k & 15);
-                        float gsum = 0.f, usum = 0.f;
-                        for (uint32_t s = 0; s < I.n_parts; ++s) {
-                            const float *pp = act + I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld;
-                            gsum += pp[gi];
-                            usum += pp[gi + 16];
+            const uint32_t brow = (uint32_t)b * I.in_ld;
+            for (int i0 = tid * 4; i0 < kn; i0 += kWgThreads * 4 * 2) {
+                // two quads per thread and iteration keep several loads in flight
+                f32x4 y[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int i = i0 + u * kWgThreads * 4;
+                    const uint32_t k = (uint32_t)(k0 + i);
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                    if (i < kn && k < I.k_len) {
+                        if (pro == PRO_PLAIN) {
+                            for (uint32_t s = 0; s < n_parts; ++s) acc += ld_act4(ab, I.in_parts + s * I.part_stride + brow + k);
+                        } else {
+                            // fused gate/up output: row group j holds PR/2 gate rows then PR/2 up rows (PR >= 8)
+                            const uint32_t half = PR >> 1;
+                            const uint32_t gi = (k / half) * PR + (k % half);
+                            f32x4 gs = {0.f, 0.f, 0.f, 0.f}, us = {0.f, 0.f, 0.f, 0.f};
+                            for (uint32_t s = 0; s < n_parts; ++s) {
+                                gs += ld_act4(ab, I.in_parts + s * I.part_stride + brow + gi);
+                                us += ld_act4(ab, I.in_parts + s * I.part_stride + brow + gi + half);
+                            }
+                            acc.x = gs.x / (1.0f + __expf(-gs.x)) * us.x; acc.y = gs.y / (1.0f + __expf(-gs.y)) * us.y;
+                            acc.z = gs.z / (1.0f + __expf(-gs.z)) * us.z; acc.w = gs.w / (1.0f + __expf(-gs.w)) * us.w;
                         }
-                        y = gsum / (1.0f + __expf(-gsum)) * usum;
+                        // elements at or beyond the true K are zero
+                        if (k + 1 >= I.k_len) acc.y = 0.f;
+                        if (k + 2 >= I.k_len) acc.z = 0.f;
+                        if (k + 3 >= I.k_len) acc.w = 0.f;
                     }
+                    y[u] = acc;
                 }
-                store_x<MFMA>(xs, b, i, y, nterm, plane_stride);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int i = i0 + u * kWgThreads * 4;
+                    if (i < kn) store_x4<MFMA>(xs, b, i, y[u], nterm, plane_stride);
+                }
             }
         }
     }
     __syncthreads();
 }
 
-// k blocks in unit u of a matrix with S splits of nkb blocks per row block (last split ragged)
+// chunks in unit u of a matrix with S splits of nkb chunks per row group (last split ragged)
 __device__ __forceinline__ uint32_t unit_nkb(uint32_t u, uint32_t S, uint32_t nkb, uint32_t kbt)
 {
     uint32_t s = u % S;
     return (s == S - 1) ? kbt - s * nkb : nkb;
 }
 
-
 struct GemvStream {
-    const u32x4 *wp;      // this lane's pointer to chunk 0 of the task
+    const __attribute__((address_space(1))) u32x4 *wp;   // this lane's pointer to chunk 0 of the task
     uint32_t total;       // chunks in the task
     u32x4 buf[kPrefetch];
 };
@@ -213,39 +324,43 @@ struct GemvStream {
 // previous operator produces, so this runs before the dependency wait.
 __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
     uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb;
     uint32_t ulast = I.u0 + I.nu;  // one past the last unit
     uint32_t end = (ulast / I.S) * I.kbt + (ulast % I.S) * I.nkb;
     st.total = end - first;
-    st.wp = (const u32x4 *)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
+    st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
+    const uint32_t last = st.total ? st.total - 1 : 0;
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) {
-        uint32_t idx = (uint32_t)wave + (uint32_t)j * kWaves;
-        if (idx < st.total) st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)idx * 64);
+        uint32_t idx = min((uint32_t)wave + (uint32_t)j * kWaves, last);
+        st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)idx * 64);
     }
 }
 
 template <bool MFMA>
-__device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, GemvStream &st, int batch)
+__device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, GemvStream &st, int batch)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ksub = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
+    const uint32_t rlog = instr_rlog(I), R = 1u << rlog, ck = chunk_k(rlog);
+    const int ksub = lane >> rlog;
     char *xs = lds + lp.xs_off;
     float *red = (float *)(lds + kLdsRed);
     const int nterm = nterm_of(batch);
     const int ncols = MFMA ? batch * nterm : 1;
     const uint32_t S = I.S, nkb = I.nkb, kbt = I.kbt, nu = I.nu, u0 = I.u0;
-    const bool normk = (I.pro == PRO_EMBED_NORM || I.pro == PRO_RESID_NORM);
+    const uint32_t pro = instr_pro(I);
+    const bool normk = (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM);
     const uint32_t x_kb0 = normk ? 0u : I.xs_lo;
-    const uint32_t k_stage = normk ? (uint32_t)P.hidden : I.xs_hi * kChunkK;
+    const uint32_t k_stage = normk ? (uint32_t)P.hidden : I.xs_hi * ck;
     const uint32_t plane_stride = k_stage * 2u + 16u;
-    const uint32_t red_per_wave = nu * 16u * (uint32_t)(MFMA ? batch : 1);
+    const uint32_t outs_per_unit = R * (uint32_t)(MFMA ? batch : 1);
+    const uint32_t red_per_wave = nu * outs_per_unit;
 
-    // running position of this wave inside the task: unit ul, k block kbi within the unit
+    // running position of this wave inside the task: unit ul, chunk kbi within the unit
     uint32_t ul = 0, kbi = (uint32_t)wave;
     uint32_t cur_n = unit_nkb(u0, S, nkb, kbt);
-    uint32_t cur_kb0 = (u0 % S) * nkb;  // first k block of the current unit inside its row block
+    uint32_t cur_kb0 = (u0 % S) * nkb;  // first chunk of the current unit inside its row group
 
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     f32x4 cacc = {0.f, 0.f, 0.f, 0.f};
@@ -253,9 +368,16 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
     auto flush = [&]() {
         if (!MFMA) {
             float v = (a0 + a1) + (a2 + a3);
+            // sum the 64 / R lanes that share a row
+            // lanes sharing a row differ in the lane bits >= rlog: in-row bits by DPP, the two row bits by permute
+            // (row rotations by 8, 4, 2, 1 sum the lanes of a 16-lane row that are congruent modulo R)
+            if (R <= 8) v = dpp_add<0x128>(v);
+            if (R <= 4) v = dpp_add<0x124>(v);
+            if (R <= 2) v = dpp_add<0x122>(v);
+            if (R <= 1) v = dpp_add<0x121>(v);
             v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
-            if (lane < 16) red[wave * red_per_wave + ul * 16 + lane] = v;
+            if ((uint32_t)lane < R) red[wave * red_per_wave + ul * R + lane] = v;
             a0 = a1 = a2 = a3 = 0.f;
         } else {
             // cacc[j] = C[row 4*ksub + j][col lane & 15]; sum the nterm columns of each sequence
@@ -283,10 +405,10 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
             cur_n = unit_nkb(u0 + ul, S, nkb, kbt);
             cur_kb0 = ((u0 + ul) % S) * nkb;
         }
-        const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;  // k block inside the staged vector
+        const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;  // chunk inside the staged vector
         if (!MFMA) {
-            const float4 *xp = (const float4 *)(xs + ((size_t)kb_rel * kChunkK + ksub * 8) * 4);
-            float4 x0 = xp[0], x1 = xp[1];
+            const f32x4 *xp = (const f32x4 *)(xs + ((size_t)kb_rel * ck + ksub * 8) * 4);
+            f32x4 x0 = xp[0], x1 = xp[1];
             a0 += bf_lo(w.x) * x0.x; a1 += bf_hi(w.x) * x0.y;
             a2 += bf_lo(w.y) * x0.z; a3 += bf_hi(w.y) * x0.w;
             a0 += bf_lo(w.z) * x1.x; a1 += bf_hi(w.z) * x1.y;
@@ -295,7 +417,7 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
             const int col = lane & 15;
             u32x4 xb = {0u, 0u, 0u, 0u};
             if (col < ncols)
-                xb = *(const u32x4 *)(xs + (size_t)col * plane_stride + ((size_t)kb_rel * kChunkK + ksub * 8) * 2);
+                xb = *(const u32x4 *)(xs + (size_t)col * plane_stride + ((size_t)kb_rel * ck + ksub * 8) * 2);
             bf16x8 av = __builtin_bit_cast(bf16x8, w);
             bf16x8 bv = __builtin_bit_cast(bf16x8, xb);
             cacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, cacc, 0, 0, 0);
@@ -304,15 +426,17 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
     };
 
     const uint32_t total = st.total;
-    for (uint32_t base = 0; base < total; base += kPrefetch * kWaves) {
+    if (total) {
+        const uint32_t last = total - 1;
+        for (uint32_t base = 0; base < total; base += kPrefetch * kWaves) {
 #pragma unroll
-        for (int j = 0; j < kPrefetch; ++j) {
-            uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
-            if (idx < total) {
-                u32x4 w = st.buf[j];
-                uint32_t nidx = idx + kPrefetch * kWaves;
-                if (nidx < total) st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
-                consume(w);
+            for (int j = 0; j < kPrefetch; ++j) {
+                const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+                if (idx < total) consume(st.buf[j]);
+                // refill the slot: always a load (clamped to the task's last chunk), so the slot's
+                // registers are written by exactly one instruction and nothing waits on it here
+                const uint32_t nidx = min(idx + kPrefetch * kWaves, last);
+                st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
             }
         }
     }
@@ -323,26 +447,44 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
     }
     __syncthreads();
 
-    // cross-wave sum in fixed wave order, bias, store
-    const uint32_t nout = red_per_wave;
+    // cross-wave sum in fixed wave order, then the epilogue
+    const ActBuf ab = act_buf(P);
     float *actw = (float *)(P.ws + P.lay.act);
-    for (uint32_t t = tid; t < nout; t += kWgThreads) {
+    const uint32_t nb = (uint32_t)(MFMA ? batch : 1);
+    auto rsum = [&](uint32_t t) {
         float v = red[t];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) v += red[w * red_per_wave + t];
-        uint32_t r = t & 15u, ub = t >> 4;
-        uint32_t b = MFMA ? ub % (uint32_t)batch : 0u;
-        uint32_t uu = u0 + (MFMA ? ub / (uint32_t)batch : ub);
-        uint32_t rb = uu / S, s = uu % S;
-        uint32_t row = rb * 16u + r;
-        if (I.bias != kNone && s == 0 && row < I.n_rows)
-            v += bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
-        if (I.flags & F_LOGITS) {
-            if (row < I.n_rows) P.logits[(size_t)b * P.vocab + row] = v;
-        } else {
-            actw[I.out + (size_t)s * I.out_split_stride + (size_t)b * I.out_ld + row] = v;
+        return v;
+    };
+    if (I.flags & F_SILU_EPI) {
+        // row group = R/2 gate rows then R/2 up rows; out[group * R/2 + r] = silu(gate) * up
+        const uint32_t half = R >> 1, nout = nu * nb * half;
+        for (uint32_t t = tid; t < nout; t += kWgThreads) {
+            uint32_t r = t % half, ub = t / half;
+            float g = rsum(ub * R + r), u = rsum(ub * R + half + r);
+            uint32_t b = ub % nb, uu = u0 + ub / nb;
+            uint32_t row = uu * half + r;     // S == 1: unit index == row group
+            st_act(actw + I.out + (size_t)b * I.out_ld + row, g / (1.0f + __expf(-g)) * u);
+        }
+    } else {
+        for (uint32_t t = tid; t < red_per_wave; t += kWgThreads) {
+            float v = rsum(t);
+            uint32_t r = t & (R - 1), ub = t >> rlog;
+            uint32_t b = ub % nb, uu = u0 + ub / nb;
+            uint32_t rg = uu / S, s = uu % S;
+            uint32_t row = rg * R + r;
+            if (I.bias != kNone && s == 0 && row < I.n_rows)
+                v += bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
+            if (I.flags & F_LOGITS) {
+                if (row < I.n_rows) P.logits[(size_t)b * P.vocab + row] = v;
+            } else {
+                if (I.flags & F_ADD_RESID) v += ld_act(actw + I.resid + (size_t)b * I.out_ld + row);
+                st_act(actw + I.out + (size_t)s * I.out_split_stride + (size_t)b * I.out_ld + row, v);
+            }
         }
     }
+    (void)ab;
 }
 
 // ---------------------------------------------------------------- attention task
@@ -351,9 +493,22 @@ __device__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsP
 // q heads of the group are processed against each K/V row read once.  The
 // task that owns the block of the current position also rotates/rounds the
 // new k and v, appends them to the cache and attends to them from LDS.
+//
+// The K/V history does not depend on this step's QKV projection, so the first
+// loads of the task are issued before the dependency wait (paper Sec. 4.2.3,
+// Fig. 4: history KV loads leave the critical path).
 struct AttState {
     float m[kMaxGroup], l[kMaxGroup];
     float acc[kMaxGroup][8];
+};
+
+constexpr int kAttPrefetch = 6;   // K and V 128-bit loads in flight per lane
+constexpr int kPartStride = 4;    // partial rows are [acc[D], m, l, pad, pad] so that they stay 16-byte aligned
+
+struct AttStream {
+    const __attribute__((address_space(1))) u32x4 *kp, *vp;   // this lane's K / V row base (position 0, own 8-dim slice)
+    int p, npos, sub;
+    u32x4 kbuf[kAttPrefetch], vbuf[kAttPrefetch];
 };
 
 __device__ __forceinline__ float safe_exp_diff(float a, float M)
@@ -361,16 +516,55 @@ __device__ __forceinline__ float safe_exp_diff(float a, float M)
     return (a == -INFINITY) ? 0.f : __expf(a - M);
 }
 
+// position (in the cache) of flattened index idx of task c
+__device__ __forceinline__ int att_pos(int idx, int bs, int nc, int c)
+{
+    int blk = idx / bs;
+    return (c + blk * nc) * bs + (idx - blk * bs);
+}
+
 template <int D>
-__device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const LdsPlan &lp)
+__device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, AttStream &st)
+{
+    constexpr int LPP = D / 8, PPW = 64 / LPP;
+    typedef const __attribute__((address_space(1))) u32x4 *gp;
+    const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
+    const int b = (int)I.b, g = (int)I.g;
+    st.npos = 0; st.p = 0; st.sub = lane / LPP;
+    if (b >= P.batch) return;
+    const int p = position_of(P, b);
+    const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
+    const int nblk_all = (p + bs - 1) / bs;                       // blocks containing positions < p
+    const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
+    st.p = p; st.npos = my_blocks * bs;
+    const size_t head_elems = (size_t)P.max_context * D;
+    const uint16_t *Kc = P.kv + ((((size_t)I.layer * 2 + 0) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
+    const uint16_t *Vc = P.kv + ((((size_t)I.layer * 2 + 1) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
+    st.kp = (gp)(uintptr_t)Kc + (lane % LPP);
+    st.vp = (gp)(uintptr_t)Vc + (lane % LPP);
+#pragma unroll
+    for (int j = 0; j < kAttPrefetch; ++j) {
+        const int grp = (wave + j * kWaves) * PPW;
+        // clamped to a valid row: rows at or beyond p are masked when consumed
+        int t = att_pos(grp + st.sub, bs, nc, c);
+        t = t < P.max_context ? t : P.max_context - 1;
+        if (grp < st.npos) {
+            st.kbuf[j] = __builtin_nontemporal_load(st.kp + (size_t)t * LPP);
+            st.vbuf[j] = __builtin_nontemporal_load(st.vp + (size_t)t * LPP);
+        }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, const LdsPlan &lp, AttStream &as)
 {
     constexpr int LPP = D / 8;       // lanes per position (16 B each)
     constexpr int PPW = 64 / LPP;    // positions per wavefront load
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     const int b = (int)I.b, g = (int)I.g;
     if (b >= P.batch) return;
     const int G = P.n_q_heads / P.n_kv_heads;
-    const int p = position_of(P, b);
+    const int p = as.p;
     const int qd = P.n_q_heads * D, kvd = P.n_kv_heads * D;
     const float *act = (const float *)(P.ws + P.lay.act);
     const uint16_t *vecs = (const uint16_t *)(P.ws + P.lay.vecs);
@@ -379,7 +573,7 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
     // LDS scratch inside the xs region
     float *sq = (float *)(lds + lp.xs_off);              // [G][D] rotated, pre-scaled q
     float *snew = sq + kMaxGroup * D;                    // [2][D] new k (rotated, bf16-rounded) and v
-    float *smerge = snew + 2 * D;                        // [kWaves][G][D + 2]
+    float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][D + 2]
     const int jb_new = p / (int)I.bs;
     const bool owner = (jb_new % (int)I.nc) == (int)I.c;
 
@@ -397,8 +591,9 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
         if (i < D / 2) {
             for (uint32_t s = 0; s < I.n_parts; ++s) {
                 const float *pp = act + I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld + row0;
-                a += pp[i];
-                c2 += pp[i + D / 2];
+                float u0 = ld_act(pp + i), u1 = ld_act(pp + i + D / 2);
+                a += u0;
+                c2 += u1;
             }
         }
         if (rot) {
@@ -437,13 +632,13 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
     __syncthreads();
 
     // ---- main loop over this task's history positions (t < p)
-    const int sub = lane / LPP, dl = lane % LPP;   // position inside the load, 8-dim slice
+    const int sub = as.sub, dl = lane % LPP;   // position inside the load, 8-dim slice
     float qr[kMaxGroup][8];
 #pragma unroll
     for (int h = 0; h < kMaxGroup; ++h)
         if (h < G) {
-            const float4 *qp = (const float4 *)(sq + h * D + dl * 8);
-            float4 q0 = qp[0], q1 = qp[1];
+            const f32x4 *qp = (const f32x4 *)(sq + h * D + dl * 8);
+            f32x4 q0 = qp[0], q1 = qp[1];
             qr[h][0] = q0.x; qr[h][1] = q0.y; qr[h][2] = q0.z; qr[h][3] = q0.w;
             qr[h][4] = q1.x; qr[h][5] = q1.y; qr[h][6] = q1.z; qr[h][7] = q1.w;
         }
@@ -454,14 +649,8 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
 #pragma unroll
         for (int j = 0; j < 8; ++j) st.acc[h][j] = 0.f;
     }
-    const size_t head_elems = (size_t)P.max_context * D;
-    const uint16_t *Kc = P.kv + ((((size_t)I.layer * 2 + 0) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
-    const uint16_t *Vc = P.kv + ((((size_t)I.layer * 2 + 1) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
-    // number of this task's blocks that start before p
-    const int nblk_all = (p + bs - 1) / bs;                       // blocks containing positions < p
-    const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
-    const int npos = my_blocks * bs;                              // flattened (some may be >= p)
+    const int npos = as.npos;
 
     auto step = [&](const u32x4 &kw, const u32x4 &vw, bool valid) {
         float kf[8] = {bf_lo(kw.x), bf_hi(kw.x), bf_lo(kw.y), bf_hi(kw.y), bf_lo(kw.z), bf_hi(kw.z), bf_lo(kw.w), bf_hi(kw.w)};
@@ -472,8 +661,7 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
                 float s = 0.f;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) s += qr[h][j] * kf[j];
-#pragma unroll
-                for (int o = LPP / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+                s = (LPP == 16) ? row_sum16(s) : row_sum8(s);
                 if (valid) {
                     float mn = fmaxf(st.m[h], s);
                     float sc = safe_exp_diff(st.m[h], mn);
@@ -486,17 +674,22 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
             }
     };
 
-    for (int grp = wave * PPW; grp < npos; grp += kWaves * PPW) {
-        int idx = grp + sub;
-        int blk = idx / bs;
-        int t = (c + blk * nc) * bs + (idx - blk * bs);
-        bool valid = t < p;
-        u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
-        if (valid) {
-            kw = __builtin_nontemporal_load((const u32x4 *)(Kc + (size_t)t * D) + dl);
-            vw = __builtin_nontemporal_load((const u32x4 *)(Vc + (size_t)t * D) + dl);
+    for (int base = 0; base * PPW < npos; base += kAttPrefetch * kWaves) {
+#pragma unroll
+        for (int j = 0; j < kAttPrefetch; ++j) {
+            const int grp = (base + wave + j * kWaves) * PPW;
+            if (grp < npos) {
+                const int t = att_pos(grp + sub, bs, nc, c);
+                step(as.kbuf[j], as.vbuf[j], t < p);
+            }
+            const int ngrp = grp + kAttPrefetch * kWaves * PPW;
+            if (ngrp < npos) {
+                int t = att_pos(ngrp + sub, bs, nc, c);
+                t = t < P.max_context ? t : P.max_context - 1;
+                as.kbuf[j] = __builtin_nontemporal_load(as.kp + (size_t)t * LPP);
+                as.vbuf[j] = __builtin_nontemporal_load(as.vp + (size_t)t * LPP);
+            }
         }
-        step(kw, vw, valid);
     }
     // the new position, from LDS, by the first position slot of wave 0 of the owner task
     if (owner && wave == 0) {
@@ -513,188 +706,250 @@ __device__ void att_task(const Params &P, const InstrAtt &I, char *lds, const Ld
         step(kw, vw, sub == 0);
     }
 
-    // ---- merge the PPW position slots of the wave (butterfly over lane bits >= LPP)
-#pragma unroll
-    for (int o = LPP; o < 64; o <<= 1) {
-#pragma unroll
-        for (int h = 0; h < kMaxGroup; ++h)
-            if (h < G) {
-                float mo = __shfl_xor(st.m[h], o, 64), lo = __shfl_xor(st.l[h], o, 64);
-                float M = fmaxf(st.m[h], mo);
-                float fa = safe_exp_diff(st.m[h], M), fb = safe_exp_diff(mo, M);
-                st.l[h] = st.l[h] * fa + lo * fb;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    float ao = __shfl_xor(st.acc[h][j], o, 64);
-                    st.acc[h][j] = st.acc[h][j] * fa + ao * fb;
-                }
-                st.m[h] = M;
-            }
-    }
-    if (sub == 0) {
+    // ---- every (wave, position slot) leaves its running state in LDS; merged below in fixed order
+    constexpr int NSLOT = kWaves * PPW;
+    {
+        const int slot = wave * PPW + sub;
 #pragma unroll
         for (int h = 0; h < kMaxGroup; ++h)
             if (h < G) {
-                float *dst = smerge + ((size_t)wave * G + h) * (D + 2);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) dst[dl * 8 + j] = st.acc[h][j];
+                float *dst = smerge + ((size_t)slot * G + h) * (D + 2);
+                f32x4 lo4 = {st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]};
+                f32x4 hi4 = {st.acc[h][4], st.acc[h][5], st.acc[h][6], st.acc[h][7]};
+                *(f32x4 *)(dst + dl * 8) = lo4;
+                *(f32x4 *)(dst + dl * 8 + 4) = hi4;
                 if (dl == 0) { dst[D] = st.m[h]; dst[D + 1] = st.l[h]; }
             }
     }
     __syncthreads();
 
-    // ---- merge the waves in fixed order and write the task's partial
     float *outp = (float *)(P.ws + P.lay.act) + I.out;
     for (int e = tid; e < G * D; e += kWgThreads) {
         int h = e / D, i = e % D;
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, smerge[((size_t)w * G + h) * (D + 2) + D]);
+        for (int w = 0; w < NSLOT; ++w) M = fmaxf(M, smerge[((size_t)w * G + h) * (D + 2) + D]);
         float L = 0.f, A = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < NSLOT; ++w) {
             const float *src = smerge + ((size_t)w * G + h) * (D + 2);
             float f = safe_exp_diff(src[D], M);
             L += src[D + 1] * f;
             A += src[i] * f;
         }
-        // partial layout [b][head][nc][D + 2]
-        float *dst = outp + ((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc) + I.c) * (D + 2);
-        dst[i] = A;
-        if (i == 0) { dst[D] = M; dst[D + 1] = L; }
+        // partial layout [b][head][nc][D + kPartStride]
+        float *dst = outp + ((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc) + I.c) * (D + kPartStride);
+        st_act(dst + i, A);
+        if (i == 0) { st_act(dst + D, M); st_act(dst + D + 1, L); }
     }
 }
 
-// Combine the nc flash-decode partials of q heads h0 .. h0+nh of sequence b.
-__device__ void comb_task(const Params &P, const InstrAtt &I)
+// Combine the nc flash-decode partials of q heads h0 .. h0+nh of sequence b: the partial rows
+// are copied to LDS with all their 128-bit loads in flight together, then reduced in fixed order.
+__device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, char *lds, const LdsPlan &lp)
 {
     const int b = (int)I.b;
     if (b >= P.batch) return;
-    const int D = P.head_dim, nc = (int)I.nc;
-    const float *part = (const float *)(P.ws + P.lay.act) + I.out;
+    const int D = P.head_dim, nc = (int)I.nc, RS = D + kPartStride;
+    const ActBuf ab = act_buf(P);
+    float *stage = (float *)(lds + lp.xs_off);
     float *o = (float *)(P.ws + P.lay.act) + I.o_out + (size_t)b * I.o_ld;
-    for (int e = threadIdx.x; e < (int)I.nh * D; e += kWgThreads) {
-        int h = (int)I.h0 + e / D, i = e % D;
-        const float *src = part + (((size_t)b * P.n_q_heads + h) * nc) * (D + 2);
-        float M = -INFINITY;
-        for (int c = 0; c < nc; ++c) M = fmaxf(M, src[(size_t)c * (D + 2) + D]);
-        float L = 0.f, A = 0.f;
-        for (int c = 0; c < nc; ++c) {
-            const float *s = src + (size_t)c * (D + 2);
-            float f = safe_exp_diff(s[D], M);
-            L += s[D + 1] * f;
-            A += s[i] * f;
+    for (int hh = 0; hh < (int)I.nh; ++hh) {
+        const int h = (int)I.h0 + hh;
+        const uint32_t src = I.out + (uint32_t)(((size_t)b * P.n_q_heads + h) * nc) * (uint32_t)RS;
+        const int nq4 = nc * RS / 4;
+        if (hh) __syncthreads();
+        for (int q0 = threadIdx.x; q0 < nq4; q0 += kWgThreads * 4) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * kWgThreads;
+                v[u] = ld_act4(ab, q < nq4 ? src + 4u * q : 0xfffffff0u);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * kWgThreads;
+                if (q < nq4) *(f32x4 *)(stage + 4 * q) = v[u];
+            }
         }
-        o[(size_t)h * D + i] = A / L;
+        __syncthreads();
+        for (int i = threadIdx.x; i < D; i += kWgThreads) {
+            float M = -INFINITY;
+            for (int c = 0; c < nc; ++c) M = fmaxf(M, stage[c * RS + D]);
+            float L = 0.f, A = 0.f;
+            for (int c = 0; c < nc; ++c) {
+                const float *s = stage + c * RS;
+                float f = safe_exp_diff(s[D], M);
+                L += s[D + 1] * f;
+                A += s[i] * f;
+            }
+            st_act(o + (size_t)h * D + i, A / L);
+        }
     }
 }
 
 // ---------------------------------------------------------------- interpreter
-template <bool PERSISTENT>
-__device__ void run_list(const Params &P, const LdsPlan lp)
+__device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, uint32_t *slot)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if (threadIdx.x < kInstrDwords) slot[threadIdx.x] = list[(size_t)pc * kInstrDwords + threadIdx.x];
+}
+
+// Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
+template <bool PERSISTENT>
+__device__ __forceinline__ void exec_instr(const Params &P, const LdsPlan &lp, char *lds, const Instr &I, uint32_t pc,
+                                           bool &dead)
+{
     const int tid = threadIdx.x;
-    const uint32_t wg = blockIdx.x;
-    const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)wg * P.max_instr * kInstrDwords;
-    uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);
     uint32_t *sflag = (uint32_t *)(lds + kLdsMisc + 128);
     const uint32_t *counters = (const uint32_t *)(P.ws + P.lay.counters);
-    uint64_t *trace = (uint64_t *)(P.ws + P.lay.trace);
-    bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
+    uint64_t t0 = 0, t1 = 0;
+    const bool tracing = PERSISTENT && (P.flags & 1u);
+    if (tracing && tid == 0) t0 = wall_clock64();
 
+    GemvStream st;
+    AttStream as;
+    if (I.op == OP_GEMV) gemv_issue(P, I, st);
+    else if (I.op == OP_ATT) {
+        if (P.head_dim == 128) att_issue<128>(P, *(const InstrAtt *)&I, as);
+        else att_issue<64>(P, *(const InstrAtt *)&I, as);
+    }
+
+    if (PERSISTENT) {
+        if (tid == 0) {
+            uint32_t ok = 1;
+            if (!dead) {
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    if (ok && I.wait_ctr[k] != kNone)
+                        ok = wait_counter(counters + (size_t)I.wait_ctr[k] * kCounterStride,
+                                          P.epoch * I.wait_cnt[k], P.spin_limit) ? 1u : 0u;
+            }
+            if (!ok) set_err(P, 0, 1u + pc);
+            sflag[0] = ok;
+        }
+        __syncthreads();
+        if (sflag[0] == 0) dead = true;
+    }
+    if (tracing && tid == 0) t1 = wall_clock64();
+
+    uint64_t t2 = 0;
+    if (I.op == OP_GEMV) {
+        if (I.flags & F_MFMA) {
+            if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
+            if (tracing && tid == 0) t2 = wall_clock64();
+            gemv_main<true>(P, I, lds, lp, st, P.batch);
+        } else {
+            if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
+            if (tracing && tid == 0) t2 = wall_clock64();
+            gemv_main<false>(P, I, lds, lp, st, 1);
+        }
+    } else if (I.op == OP_ATT) {
+        const InstrAtt &A = *(const InstrAtt *)&I;
+        if (P.head_dim == 128) att_task<128>(P, A, lds, lp, as);
+        else att_task<64>(P, A, lds, lp, as);
+    } else if (I.op == OP_COMB) {
+        comb_task(P, *(const InstrAtt *)&I, lds, lp);
+    }
+
+    if (PERSISTENT && I.sig_ctr != kNone) {
+        // each wave drains its write-through stores, the barrier collects all waves, then one
+        // thread publishes the task with the counter increment
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0)
+            __hip_atomic_fetch_add((uint32_t *)counters + (size_t)I.sig_ctr * kCounterStride, 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tracing && tid == 0) {
+        uint64_t *r = (uint64_t *)(P.ws + P.lay.trace) + ((size_t)blockIdx.x * P.max_instr + pc) * 4;
+        r[0] = t0; r[1] = t1; r[2] = t2 ? t2 : t1; r[3] = wall_clock64();
+    }
+}
+
+__device__ __forceinline__ void read_instr(const uint32_t *slot, Instr &I)
+{
+    uint32_t *dst = (uint32_t *)&I;
+#pragma unroll
+    for (int j = 0; j < kInstrDwords; ++j) dst[j] = rfl(slot[j]);
+}
+
+// Persistent walk of this workgroup's whole list; the next instruction is fetched while the
+// current one runs.
+__device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan lp)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
+    uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);   // two slots of 32 dwords
+    bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
+    fetch_instr(list, 0, sinstr);
     for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
         __syncthreads();
-        if (tid < kInstrDwords) sinstr[tid] = list[(size_t)pc * kInstrDwords + tid];
+        Instr I;
+        read_instr(sinstr + (pc & 1u) * kInstrDwords, I);
+        if (I.op == OP_END) break;
+        uint32_t nxt = 0;
+        const bool more = pc + 1 < P.max_instr;
+        if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
+        exec_instr<true>(P, lp, lds, I, pc, dead);
+        if (more && threadIdx.x < kInstrDwords) sinstr[((pc + 1) & 1u) * kInstrDwords + threadIdx.x] = nxt;
+    }
+}
+
+// One operator instance: the instructions of this workgroup whose ref_seq matches (they are
+// adjacent in the list), found with one parallel scan.
+__device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan lp)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
+    uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);
+    uint32_t *srange = (uint32_t *)(lds + kLdsMisc + 160);   // [0] first match, [1] match count
+    if (threadIdx.x == 0) { srange[0] = 0xffffffffu; srange[1] = 0u; }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < P.max_instr; i += kWgThreads) {
+        uint32_t op = list[(size_t)i * kInstrDwords], seq = list[(size_t)i * kInstrDwords + 2];
+        if (op != OP_END && seq == P.only_seq) { atomicMin(srange, i); atomicAdd(srange + 1, 1u); }
+    }
+    __syncthreads();
+    const uint32_t first = srange[0], n = srange[1];
+    bool dead = false;
+    for (uint32_t pc = first; pc < first + n && n; ++pc) {
+        __syncthreads();
+        fetch_instr(list, pc, sinstr);
         __syncthreads();
         Instr I;
-        {
-            uint32_t *dst = (uint32_t *)&I;
-#pragma unroll
-            for (int j = 0; j < kInstrDwords; ++j) dst[j] = rfl(sinstr[j]);
-        }
-        if (I.op == OP_END) break;
-        if (!PERSISTENT && I.ref_seq != P.only_seq) continue;
-        uint64_t t0 = 0, t1 = 0;
-        const bool tracing = PERSISTENT && (P.flags & 1u);
-        if (tracing && tid == 0) t0 = wall_clock64();
-
-        GemvStream st;
-        if (I.op == OP_GEMV) gemv_issue(P, I, st);
-
-        if (PERSISTENT) {
-            if (tid == 0) {
-                uint32_t ok = 1;
-                if (!dead) {
-#pragma unroll
-                    for (int k = 0; k < 2; ++k)
-                        if (ok && I.wait_ctr[k] != kNone)
-                            ok = wait_counter(counters + (size_t)I.wait_ctr[k] * kCounterStride,
-                                              P.epoch * I.wait_cnt[k], P.spin_limit) ? 1u : 0u;
-                }
-                if (!ok) set_err(P, 0, 1u + pc);
-                sflag[0] = ok;
-            }
-            __syncthreads();
-            if (sflag[0] == 0) dead = true;
-        }
-        if (tracing && tid == 0) t1 = wall_clock64();
-
-        if (I.op == OP_GEMV) {
-            if (I.flags & F_MFMA) {
-                if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
-                gemv_main<true>(P, I, lds, lp, st, P.batch);
-            } else {
-                if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
-                gemv_main<false>(P, I, lds, lp, st, 1);
-            }
-        } else if (I.op == OP_ATT) {
-            const InstrAtt &A = *(const InstrAtt *)&I;
-            if (P.head_dim == 128) att_task<128>(P, A, lds, lp);
-            else att_task<64>(P, A, lds, lp);
-        } else if (I.op == OP_COMB) {
-            comb_task(P, *(const InstrAtt *)&I);
-        }
-
-        if (PERSISTENT && I.sig_ctr != kNone) {
-            // every wave's stores have left the wave before the barrier; thread 0 then
-            // publishes them (agent-scope release) with the counter increment
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (tid == 0)
-                __hip_atomic_fetch_add((uint32_t *)counters + (size_t)I.sig_ctr * kCounterStride, 1u,
-                                       __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (tracing && tid == 0) {
-            uint64_t *r = trace + ((size_t)wg * P.max_instr + pc) * 4;
-            r[0] = ((uint64_t)wg << 32) | pc; r[1] = t0; r[2] = t1; r[3] = wall_clock64();
-        }
+        read_instr(sinstr, I);
+        exec_instr<false>(P, lp, lds, I, pc, dead);
     }
 }
 
 }  // namespace mk
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_list<true>(P, lp); }
+mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent(P, lp); }
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_list<false>(P, lp); }
+mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op(P, lp); }
 
-// Offline weight reorder: row-major bf16 [n_rows][n_cols] -> tile-major chunks.
-// Destination row block of source row block rb is rb0 + rb * rb_stride (so two
-// matrices can be interleaved block-wise); chunk (rb, kb) holds lane-major
-// 16 B: lane = ksub * 16 + r -> 8 elements W[rb*16 + r][kb*32 + ksub*8 + 0..7].
-extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int n_cols, mk::u32x4 *dst,
-                                            uint32_t kbt, uint32_t rb0, uint32_t rb_stride, uint32_t n_rb)
+// Offline weight reorder: row-major bf16 [n_rows][n_cols] -> tile-major chunks of R = 1 << rlog rows.
+// Source row i lands in row group g0 + i / rpu at row r_off + i % rpu of the group (rpu = R and
+// r_off = 0 for a plain matrix; rpu = R/2 with r_off 0 / R/2 interleaves the gate and up matrices).
+// Chunk (group, kb) holds lane-major 16 B: lane = ksub * R + r -> W[row][kb * 512/R + ksub*8 + 0..7].
+// Lanes whose r lies outside [r_off, r_off + rpu) belong to the other matrix and are left alone;
+// rows and columns beyond the source are written as zeros.
+extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int n_cols, mk::u32x4 *dst, uint32_t kbt,
+                                            uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups)
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t total = (size_t)n_rb * kbt * 64;
+    size_t total = (size_t)n_groups * kbt * 64;
     if (gid >= total) return;
+    const uint32_t R = 1u << rlog, ck = 512u >> rlog;
     uint32_t lane = (uint32_t)(gid & 63);
-    size_t ck = gid >> 6;
-    uint32_t kb = (uint32_t)(ck % kbt), rb = (uint32_t)(ck / kbt);
-    int row = (int)(rb * 16 + (lane & 15));
-    int k0 = (int)(kb * 32 + (lane >> 4) * 8);
+    size_t c = gid >> 6;
+    uint32_t kb = (uint32_t)(c % kbt), grp = (uint32_t)(c / kbt);
+    uint32_t r = lane & (R - 1), ksub = lane >> rlog;
+    if (r < r_off || r >= r_off + rpu) return;
+    long row = (long)grp * rpu + (r - r_off);
+    int k0 = (int)(kb * ck + ksub * 8);
     uint16_t e[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -704,7 +959,7 @@ extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int
     mk::u32x4 v;
     v.x = e[0] | ((uint32_t)e[1] << 16); v.y = e[2] | ((uint32_t)e[3] << 16);
     v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[((size_t)(rb0 + rb * rb_stride) * kbt + kb) * 64 + lane] = v;
+    dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v;
 }
 
 extern "C" __global__ void mk_copy_u16_kernel(const uint16_t *src, uint16_t *dst, size_t n)

@@ -29,6 +29,7 @@ const char *last_error_text() { return g_err.c_str(); }
 
 constexpr int64_t kLdsMax = 160 * 1024;   // LDS per CU on CDNA4
 constexpr int kMaxHidden = 16 * kWgThreads;
+constexpr int kPartPad = 4;   // attention partial rows: [acc[d], m, l, pad, pad]
 
 int64_t pages_available(int64_t smem_max, int64_t n_stage, int64_t instr_buf, int64_t semaphores,
                         int64_t scratch, int64_t page_size)
@@ -70,46 +71,63 @@ static int derive_dims(const mk_config &c, Dims &d)
     d.L = c.n_layers; d.H = c.hidden; d.nq = c.n_q_heads; d.nkv = c.n_kv_heads; d.d = c.head_dim;
     d.I = c.intermediate; d.V = c.vocab; d.Bm = c.max_batch; d.Tm = c.max_context; d.G = d.nq / d.nkv;
     d.qd = d.nq * d.d; d.kvd = d.nkv * d.d; d.nqkv = d.qd + 2 * d.kvd;
-    d.ipad = ceil_div(d.I, 16) * 16; d.ngu = 2 * d.ipad;
-    d.kb_h = d.H / 32; d.kb_qd = d.qd / 32; d.kb_i = ceil_div(d.I, 32);
-    d.rb_qkv = d.nqkv / 16; d.rb_o = d.H / 16; d.rb_gu = d.ngu / 16; d.rb_d = d.H / 16; d.rb_v = ceil_div(d.V, 16);
     return MK_OK;
 }
 
+static MatGeom mat_geom(int rlog, int n_rows, int k_len)
+{
+    MatGeom g;
+    g.rlog = rlog; g.R = 1 << rlog; g.ck = 512 >> rlog;
+    g.groups = ceil_div(n_rows, g.R); g.kbt = ceil_div(k_len, g.ck);
+    g.n_rows = n_rows; g.k_len = k_len;
+    return g;
+}
+
+static void derive_geom(const Dims &d, const Tiling &t, Geom &g)
+{
+    g.qkv = mat_geom(t.r_qkv, d.nqkv, d.H);
+    g.o = mat_geom(t.r_o, d.H, d.qd);
+    const int half = (1 << t.r_gu) / 2;
+    g.ipad = ceil_div(d.I, std::max(half, 4)) * std::max(half, 4);
+    g.gu = mat_geom(t.r_gu, 2 * g.ipad, d.H);
+    g.down = mat_geom(t.r_d, d.H, d.I);
+    g.head = mat_geom(t.r_head, d.V, d.H);
+}
+
 // ---------------------------------------------------------------- memory maps
-static void plan_weights(const mk_config &c, const Dims &d, WeightMap &w)
+static void plan_weights(const mk_config &c, const Dims &d, const Geom &g, WeightMap &w)
 {
     uint64_t ch = 0, ve = 0;
-    auto take = [&](uint64_t n) { uint64_t at = ch; ch += n; return (uint32_t)at; };
+    auto take = [&](const MatGeom &m) { uint64_t at = ch; ch += (uint64_t)m.groups * m.kbt; return (uint32_t)at; };
     auto takev = [&](uint64_t n) { uint64_t at = ve; ve += (n + 7) / 8 * 8; return (uint32_t)at; };
     w.qkv.resize(d.L); w.o.resize(d.L); w.gu.resize(d.L); w.down.resize(d.L);
     w.g_attn.resize(d.L); w.g_mlp.resize(d.L); w.bias.assign(d.L, kNone); w.qn.assign(d.L, kNone); w.kn.assign(d.L, kNone);
     for (int l = 0; l < d.L; ++l) {
-        w.qkv[l] = take((uint64_t)d.rb_qkv * d.kb_h);
-        w.o[l] = take((uint64_t)d.rb_o * d.kb_qd);
-        w.gu[l] = take((uint64_t)d.rb_gu * d.kb_h);
-        w.down[l] = take((uint64_t)d.rb_d * d.kb_i);
+        w.qkv[l] = take(g.qkv);
+        w.o[l] = take(g.o);
+        w.gu[l] = take(g.gu);
+        w.down[l] = take(g.down);
         w.g_attn[l] = takev(d.H); w.g_mlp[l] = takev(d.H);
         if (c.qkv_bias) w.bias[l] = takev(d.nqkv);
         if (c.qk_norm) { w.qn[l] = takev(d.d); w.kn[l] = takev(d.d); }
     }
-    w.embed = take((uint64_t)d.rb_v * d.kb_h);
-    w.head = c.tie_embeddings ? w.embed : take((uint64_t)d.rb_v * d.kb_h);
+    w.embed = take(g.head);
+    w.head = c.tie_embeddings ? w.embed : take(g.head);
     w.g_final = takev(d.H);
     w.n_chunks = ch; w.n_vec = ve;
 }
 
-static void plan_act(const Dims &d, const Tiling &t, ActMap &a)
+static void plan_act(const Dims &d, const Geom &g, const Tiling &t, ActMap &a)
 {
     uint64_t f = 0;
     auto take = [&](uint64_t n) { uint64_t at = f; f += (n + 63) / 64 * 64; return (uint32_t)at; };
     a.xa = take((uint64_t)d.Bm * d.H);
     a.xb = take((uint64_t)d.Bm * d.H);
     a.pqkv = take((uint64_t)t.s_qkv * d.Bm * d.nqkv);
-    a.attp = take((uint64_t)d.Bm * d.nq * t.nc * (d.d + 2));
+    a.attp = take((uint64_t)d.Bm * d.nq * t.nc * (d.d + kPartPad));
     a.o = take((uint64_t)d.Bm * d.qd);
     a.po = take((uint64_t)t.s_o * d.Bm * d.H);
-    a.gu = take((uint64_t)t.s_gu * d.Bm * d.ngu);
+    a.gu = take((uint64_t)t.s_gu * d.Bm * 2 * g.ipad);
     a.pd = take((uint64_t)t.s_d * d.Bm * d.H);
     a.n_floats = f;
 }
@@ -118,14 +136,14 @@ static uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- LDS budget (Eq. 1-2)
 struct LdsBudget {
-    int cap_units;        // units per GEMV task the cross-wave reduction area can hold
+    int cap_outs;         // outputs (rows x sequences) per GEMV task the cross-wave reduction area can hold
     uint32_t red_bytes;
     uint32_t xs_cap;      // bytes left for the staged input vector
 };
 
 static uint32_t att_scratch_bytes(const Dims &d)
 {
-    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * d.G * (d.d + 2)) * 4u;
+    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 2)) * 4u;   // q, new k/v, per-slot merge
 }
 
 static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
@@ -134,15 +152,20 @@ static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
     return t.mfma ? (uint32_t)(d.Bm * nterm) * ((uint32_t)d.H * 2u + 16u) : (uint32_t)d.H * 4u;
 }
 
+// Eq. 1: what is left of the 160 KB after the per-stage fixed areas (instruction buffer,
+// semaphores/flags, reduction scratch) is available as pages; Eq. 2: the pages not pinned by the
+// staged activations give the depth of the weight ring.  With ring_pages == 0 weights stream
+// straight into registers and the whole remainder is available to activations.
 static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
 {
-    int cols = t.mfma ? d.Bm : 1;
-    b.cap_units = std::max(1, 64 / cols);
-    b.red_bytes = (uint32_t)(kWaves * b.cap_units * 16 * cols * 4);
-    int64_t fixed = kLdsRed + b.red_bytes;                       // instruction buffer + semaphores + scratch
-    int64_t ring = (int64_t)t.ring_pages * t.page_bytes;
-    int64_t left = kLdsMax - fixed - ring;
-    int64_t need = std::max<int64_t>(att_scratch_bytes(d), norm_stage_bytes(d, t));
+    b.cap_outs = 1024;
+    b.red_bytes = (uint32_t)(kWaves * b.cap_outs * 4);
+    const int64_t fixed = kLdsRed + b.red_bytes;
+    const int64_t pages_total = pages_available(kLdsMax, 1, kLdsMisc - kLdsInstr, kLdsRed - kLdsMisc, b.red_bytes, t.page_bytes);
+    const int64_t need = std::max<int64_t>(att_scratch_bytes(d), norm_stage_bytes(d, t));
+    const int64_t pages_act = (need + t.page_bytes - 1) / t.page_bytes;
+    if (t.ring_pages > 0 && pipeline_stages(pages_total, t.ring_pages, 0, pages_act, 1) < 1) return false;
+    const int64_t left = kLdsMax - fixed - (int64_t)t.ring_pages * t.page_bytes;
     if (left < need) return false;
     b.xs_cap = (uint32_t)left;
     return true;
@@ -153,6 +176,7 @@ struct Builder {
     const mk_config &cfg;
     const Dims &d;
     const Tiling &t;
+    const Geom &g;
     const WeightMap &wm;
     const ActMap &am;
     LdsBudget lb;
@@ -163,8 +187,8 @@ struct Builder {
     uint32_t max_xs_bytes = 0;
     int n_tasks = 0;
 
-    Builder(const mk_config &c, const Dims &dd, const Tiling &tt, const WeightMap &w, const ActMap &a)
-        : cfg(c), d(dd), t(tt), wm(w), am(a), n_wg(c.n_workgroups), lists(c.n_workgroups), load(c.n_workgroups, 0.0) {}
+    Builder(const mk_config &c, const Dims &dd, const Tiling &tt, const Geom &gg, const WeightMap &w, const ActMap &a)
+        : cfg(c), d(dd), t(tt), g(gg), wm(w), am(a), n_wg(c.n_workgroups), lists(c.n_workgroups), load(c.n_workgroups, 0.0) {}
 
     uint32_t new_counter() { ctr_signals.push_back(0); return (uint32_t)ctr_signals.size() - 1; }
 
@@ -177,20 +201,24 @@ struct Builder {
         return o;
     }
 
-    uint32_t stage_bytes(uint32_t nkblocks) const
+    uint32_t stage_bytes(uint32_t k_elems) const
     {
         int nterm = d.Bm <= 5 ? 3 : 2;
-        return t.mfma ? (uint32_t)(d.Bm * nterm) * (nkblocks * kChunkK * 2u + 16u) : nkblocks * kChunkK * 4u;
+        return t.mfma ? (uint32_t)(d.Bm * nterm) * (k_elems * 2u + 16u) : k_elems * 4u;
     }
 
     // Partition the units of one GEMV operator instance over the workgroups and emit its tasks.
-    // `proto` carries everything except u0/nu/xs range/flags/signal.  Returns false if a task cannot fit LDS.
-    bool emit_gemv(Instr proto, int nrb, uint32_t wait_ctr, uint32_t sig_ctr)
+    // `proto` carries everything except u0/nu/staged range/skip flag/signal.  Returns false if a task cannot fit LDS.
+    bool emit_gemv(Instr proto, const MatGeom &m, uint32_t wait_ctr, uint32_t sig_ctr)
     {
         const uint32_t S = proto.S, kbt = proto.kbt, nkb = proto.nkb;
-        const uint32_t U = (uint32_t)nrb * S;
+        const uint32_t U = (uint32_t)m.groups * S;
         const int parts = (int)std::min<uint32_t>((uint32_t)n_wg, U);
-        const bool normk = proto.pro == PRO_EMBED_NORM || proto.pro == PRO_RESID_NORM;
+        const uint32_t pro = instr_pro(proto);
+        const bool normk = pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM;
+        const bool store_slice = normk && proto.xs_out != kNone;
+        const int cols = t.mfma ? d.Bm : 1;
+        const uint32_t cap_units = std::max<uint32_t>(1, (uint32_t)lb.cap_outs / (uint32_t)(m.R * cols));
         std::vector<int> order = by_load();
         uint32_t base = U / parts, rem = U % parts, u = 0;
         for (int pi = 0; pi < parts; ++pi) {
@@ -202,11 +230,11 @@ struct Builder {
             while (u < u_end) {
                 // grow the task unit by unit while the reduction area and the staged input fit
                 uint32_t nu = 0, klo = 0, khi = 0;
-                while (u + nu < u_end && (int)nu < lb.cap_units) {
+                while (u + nu < u_end && nu < cap_units) {
                     uint32_t uu = u + nu, s = uu % S;
                     uint32_t lo = s * nkb, hi = (s == S - 1) ? kbt : lo + nkb;
                     uint32_t nlo = nu ? std::min(klo, lo) : lo, nhi = nu ? std::max(khi, hi) : hi;
-                    if (!normk && stage_bytes(nhi - nlo) > lb.xs_cap) break;
+                    if (!normk && stage_bytes((nhi - nlo) * m.ck) > lb.xs_cap) break;
                     klo = nlo; khi = nhi; ++nu;
                 }
                 if (nu == 0) return false;
@@ -217,16 +245,20 @@ struct Builder {
                 I.wait_cnt[1] = 0;
                 I.sig_ctr = kNone;
                 if (normk) {
-                    // the first task of each participant stores its slice of the new residual
-                    I.xs_lo = first ? (uint32_t)((uint64_t)d.H * pi / parts) : 0;
-                    I.xs_hi = first ? (uint32_t)((uint64_t)d.H * (pi + 1) / parts) : 0;
+                    // the first task of each participant stores its 4-aligned slice of the new residual
+                    I.xs_lo = I.xs_hi = 0;
+                    if (first && store_slice) {
+                        I.xs_lo = 4u * (uint32_t)((uint64_t)(d.H / 4) * pi / parts);
+                        I.xs_hi = 4u * (uint32_t)((uint64_t)(d.H / 4) * (pi + 1) / parts);
+                    }
+                    if (!store_slice) I.xs_out = 0;
                     if (!first) I.flags |= F_SKIP_PRO;
                     max_xs_bytes = std::max(max_xs_bytes, norm_stage_bytes(d, t));
                 } else {
                     I.xs_lo = klo; I.xs_hi = khi - klo;
                     if (!first && prev_lo == I.xs_lo && prev_n == I.xs_hi) I.flags |= F_SKIP_PRO;
                     prev_lo = I.xs_lo; prev_n = I.xs_hi;
-                    max_xs_bytes = std::max(max_xs_bytes, stage_bytes(khi - klo));
+                    max_xs_bytes = std::max(max_xs_bytes, stage_bytes((khi - klo) * m.ck));
                 }
                 if (u + nu == u_end) { I.sig_ctr = sig_ctr; if (sig_ctr != kNone) ++ctr_signals[sig_ctr]; }
                 lists[wg].push_back(I);
@@ -240,40 +272,55 @@ struct Builder {
         return true;
     }
 
+    Instr gemv_proto(uint32_t stage, int l, const MatGeom &m, uint32_t w_chunk, int S, uint32_t pro, uint32_t n_parts,
+                     uint32_t prod_rlog) const
+    {
+        Instr I{};
+        I.op = OP_GEMV; I.flags = t.mfma ? F_MFMA : 0u; I.ref_seq = (uint32_t)l * 8 + stage; I.layer = (uint32_t)l;
+        I.w_chunk = w_chunk; I.kbt = (uint32_t)m.kbt; I.S = (uint32_t)S; I.nkb = (uint32_t)ceil_div(m.kbt, S);
+        I.n_rows = (uint32_t)m.n_rows; I.k_len = (uint32_t)m.k_len;
+        I.cfg = make_cfg(pro, (uint32_t)m.rlog, prod_rlog, n_parts);
+        I.bias = kNone; I.xs_out = kNone;
+        return I;
+    }
+
     bool build()
     {
         if (!lds_budget(d, t, lb)) return false;
-        const uint32_t fl = t.mfma ? F_MFMA : 0u;
-        uint32_t prev_done = kNone;   // counter of the operator producing the residual partials of the layer below
+        // The residual stream lives in xa / xb.  `res` is the buffer holding the current residual,
+        // `parts` the K-split partial sums still to be added to it (summed in the next prologue).
+        uint32_t res = am.xa, parts_off = 0, parts_n = 0;
+        uint32_t prev_done = kNone;
+        auto other = [&](uint32_t b) { return b == am.xa ? am.xb : am.xa; };
         for (int l = 0; l < d.L; ++l) {
             const uint32_t c_qkv = new_counter(), c_comb = new_counter(), c_o = new_counter(), c_gu = new_counter(),
                            c_d = new_counter();
             std::vector<uint32_t> c_att(d.Bm * d.nkv);
             for (auto &c : c_att) c = new_counter();
 
-            // ---- QKV projection: prologue = (embedding | residual + down partials) -> RMSNorm
-            Instr q{};
-            q.op = OP_GEMV; q.flags = fl; q.ref_seq = l * 8 + ST_QKV; q.layer = l;
-            q.w_chunk = wm.qkv[l]; q.kbt = d.kb_h; q.S = t.s_qkv; q.nkb = ceil_div(d.kb_h, t.s_qkv);
-            q.n_rows = d.nqkv; q.k_len = d.H;
-            q.pro = l == 0 ? PRO_EMBED_NORM : PRO_RESID_NORM;
-            q.in_base = am.xb; q.in_parts = am.pd; q.n_parts = l == 0 ? 0 : t.s_d; q.part_stride = d.Bm * d.H; q.in_ld = d.H;
-            q.xs_out = am.xa; q.gain = wm.g_attn[l];
-            q.out = am.pqkv; q.out_split_stride = d.Bm * d.nqkv; q.out_ld = d.nqkv; q.bias = wm.bias[l];
-            if (!emit_gemv(q, d.rb_qkv, prev_done, c_qkv)) return false;
-
+            // ---- QKV projection: prologue = (embedding | residual + pending partials) -> RMSNorm
+            {
+                Instr q = gemv_proto(ST_QKV, l, g.qkv, wm.qkv[l], t.s_qkv, l == 0 ? PRO_EMBED_NORM : PRO_RESID_NORM, parts_n, 0);
+                q.in_base = res; q.in_parts = parts_off; q.part_stride = d.Bm * d.H; q.in_ld = d.H;
+                if (l == 0) { q.xs_out = am.xa; res = am.xa; }
+                else if (parts_n) { q.xs_out = other(res); res = other(res); }
+                parts_n = 0;
+                q.gain = wm.g_attn[l];
+                q.out = am.pqkv; q.out_split_stride = d.Bm * d.nqkv; q.out_ld = d.nqkv; q.bias = wm.bias[l];
+                if (!emit_gemv(q, g.qkv, prev_done, c_qkv)) return false;
+            }
             // ---- attention partials: one task per (sequence, kv head, chunk)
             {
                 std::vector<int> order = by_load();
                 int oi = 0;
                 for (int b = 0; b < d.Bm; ++b)
-                    for (int g = 0; g < d.nkv; ++g)
+                    for (int gh = 0; gh < d.nkv; ++gh)
                         for (int c = 0; c < t.nc; ++c) {
                             InstrAtt a{};
                             a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l;
                             a.wait_ctr[0] = c_qkv; a.wait_cnt[0] = ctr_signals[c_qkv]; a.wait_ctr[1] = kNone;
-                            a.sig_ctr = c_att[b * d.nkv + g]; ++ctr_signals[a.sig_ctr];
-                            a.b = b; a.g = g; a.c = c; a.nc = t.nc; a.bs = t.bs;
+                            a.sig_ctr = c_att[b * d.nkv + gh]; ++ctr_signals[a.sig_ctr];
+                            a.b = b; a.g = gh; a.c = c; a.nc = t.nc; a.bs = t.bs;
                             a.in_parts = am.pqkv; a.n_parts = t.s_qkv; a.part_stride = d.Bm * d.nqkv; a.in_ld = d.nqkv;
                             a.qn_gain = wm.qn[l]; a.kn_gain = wm.kn[l];
                             a.out = am.attp;
@@ -301,54 +348,53 @@ struct Builder {
                         load[wg] += 4.0;
                     }
             }
-            // ---- O projection (residual add deferred to the consumer's prologue)
-            Instr o{};
-            o.op = OP_GEMV; o.flags = fl; o.ref_seq = l * 8 + ST_O; o.layer = l;
-            o.w_chunk = wm.o[l]; o.kbt = d.kb_qd; o.S = t.s_o; o.nkb = ceil_div(d.kb_qd, t.s_o);
-            o.n_rows = d.H; o.k_len = d.qd; o.pro = PRO_PLAIN;
-            o.in_parts = am.o; o.n_parts = 1; o.part_stride = 0; o.in_ld = d.qd;
-            o.out = am.po; o.out_split_stride = d.Bm * d.H; o.out_ld = d.H; o.bias = kNone;
-            if (!emit_gemv(o, d.rb_o, c_comb, c_o)) return false;
-
-            // ---- gate/up projection: prologue = residual + O partials -> RMSNorm
-            Instr gu{};
-            gu.op = OP_GEMV; gu.flags = fl; gu.ref_seq = l * 8 + ST_GU; gu.layer = l;
-            gu.w_chunk = wm.gu[l]; gu.kbt = d.kb_h; gu.S = t.s_gu; gu.nkb = ceil_div(d.kb_h, t.s_gu);
-            gu.n_rows = d.ngu; gu.k_len = d.H; gu.pro = PRO_RESID_NORM;
-            gu.in_base = am.xa; gu.in_parts = am.po; gu.n_parts = t.s_o; gu.part_stride = d.Bm * d.H; gu.in_ld = d.H;
-            gu.xs_out = am.xb; gu.gain = wm.g_mlp[l];
-            gu.out = am.gu; gu.out_split_stride = d.Bm * d.ngu; gu.out_ld = d.ngu; gu.bias = kNone;
-            if (!emit_gemv(gu, d.rb_gu, c_o, c_gu)) return false;
-
-            // ---- down projection: prologue = silu(gate) * up
-            Instr dn{};
-            dn.op = OP_GEMV; dn.flags = fl; dn.ref_seq = l * 8 + ST_DOWN; dn.layer = l;
-            dn.w_chunk = wm.down[l]; dn.kbt = d.kb_i; dn.S = t.s_d; dn.nkb = ceil_div(d.kb_i, t.s_d);
-            dn.n_rows = d.H; dn.k_len = d.I; dn.pro = PRO_SILU;
-            dn.in_parts = am.gu; dn.n_parts = t.s_gu; dn.part_stride = d.Bm * d.ngu; dn.in_ld = d.ngu;
-            dn.out = am.pd; dn.out_split_stride = d.Bm * d.H; dn.out_ld = d.H; dn.bias = kNone;
-            if (!emit_gemv(dn, d.rb_d, c_gu, c_d)) return false;
+            // ---- O projection; unsplit: the epilogue adds the residual, split: partials for the next prologue
+            {
+                Instr o = gemv_proto(ST_O, l, g.o, wm.o[l], t.s_o, PRO_PLAIN, 1, 0);
+                o.in_parts = am.o; o.part_stride = 0; o.in_ld = d.qd;
+                o.out_ld = d.H;
+                if (t.s_o == 1) { o.flags |= F_ADD_RESID; o.resid = res; o.out = other(res); res = other(res); }
+                else { o.out = am.po; o.out_split_stride = d.Bm * d.H; parts_off = am.po; parts_n = t.s_o; }
+                if (!emit_gemv(o, g.o, c_comb, c_o)) return false;
+            }
+            // ---- gate/up projection: prologue = residual (+ O partials) -> RMSNorm; unsplit: SiLU * up in the epilogue
+            {
+                Instr gu = gemv_proto(ST_GU, l, g.gu, wm.gu[l], t.s_gu, PRO_RESID_NORM, parts_n, 0);
+                gu.in_base = res; gu.in_parts = parts_off; gu.part_stride = d.Bm * d.H; gu.in_ld = d.H;
+                if (parts_n) { gu.xs_out = other(res); res = other(res); }
+                parts_n = 0;
+                gu.gain = wm.g_mlp[l];
+                gu.out = am.gu;
+                if (t.s_gu == 1) { gu.flags |= F_SILU_EPI; gu.out_ld = g.ipad; }
+                else { gu.out_split_stride = d.Bm * 2 * g.ipad; gu.out_ld = 2 * g.ipad; }
+                if (!emit_gemv(gu, g.gu, c_o, c_gu)) return false;
+            }
+            // ---- down projection
+            {
+                const bool fused = t.s_gu == 1;
+                Instr dn = gemv_proto(ST_DOWN, l, g.down, wm.down[l], t.s_d, fused ? PRO_PLAIN : PRO_SILU,
+                                      fused ? 1 : t.s_gu, (uint32_t)g.gu.rlog);
+                dn.in_parts = am.gu; dn.part_stride = fused ? 0 : d.Bm * 2 * g.ipad; dn.in_ld = fused ? g.ipad : 2 * g.ipad;
+                dn.out_ld = d.H;
+                if (t.s_d == 1) { dn.flags |= F_ADD_RESID; dn.resid = res; dn.out = other(res); res = other(res); }
+                else { dn.out = am.pd; dn.out_split_stride = d.Bm * d.H; parts_off = am.pd; parts_n = t.s_d; }
+                if (!emit_gemv(dn, g.down, c_gu, c_d)) return false;
+            }
             prev_done = c_d;
         }
-        // ---- final norm + LM head
-        Instr h{};
-        h.op = OP_GEMV; h.flags = (t.mfma ? F_MFMA : 0u) | F_LOGITS; h.ref_seq = d.L * 8 + ST_HEAD; h.layer = d.L;
-        h.w_chunk = wm.head; h.kbt = d.kb_h; h.S = 1; h.nkb = d.kb_h;
-        h.n_rows = d.V; h.k_len = d.H; h.pro = PRO_RESID_NORM;
-        h.in_base = am.xb; h.in_parts = am.pd; h.n_parts = t.s_d; h.part_stride = d.Bm * d.H; h.in_ld = d.H;
-        h.xs_out = am.xa; h.gain = wm.g_final;
-        h.out = 0; h.out_split_stride = 0; h.out_ld = d.V; h.bias = kNone;
-        if (!emit_gemv(h, d.rb_v, prev_done, kNone)) return false;
-        // the LM head never stores a residual slice
-        for (auto &lst : lists)
-            for (auto &I : lst)
-                if (I.op == OP_GEMV && (I.flags & F_LOGITS)) { I.xs_lo = 0; I.xs_hi = 0; }
+        // ---- final norm + LM head (never stores a residual slice)
+        Instr h = gemv_proto(ST_HEAD, d.L, g.head, wm.head, 1, PRO_RESID_NORM, parts_n, 0);
+        h.flags |= F_LOGITS;
+        h.in_base = res; h.in_parts = parts_off; h.part_stride = d.Bm * d.H; h.in_ld = d.H;
+        h.gain = wm.g_final; h.out_ld = d.V;
+        if (!emit_gemv(h, g.head, prev_done, kNone)) return false;
         max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d));
+        max_xs_bytes = std::max(max_xs_bytes, (uint32_t)(t.nc * (d.d + kPartPad) * 4));
         return true;
     }
 };
 
-// A split must leave every unit at least one k block; ragged last units are fine.
+// A split must leave every unit at least one chunk; ragged last units are fine.
 static bool split_ok(int kbt, int s) { return s >= 1 && s <= kbt && ceil_div(kbt, s) * (s - 1) < kbt; }
 
 // ---------------------------------------------------------------- replay (shared by simulator and verifier)
@@ -422,7 +468,7 @@ static SimResult simulate(const mk_schedule *s)
 {
     const double bw_chip = 8.0e6 * 0.70;                         // bytes per microsecond the chip sustains
     const double bw_wg = bw_chip / s->n_wg;
-    const double sync_us = 1.8, pro_us_per_kfloat = 0.06, task_us = 0.35, sig_us = 0.6;
+    const double sync_us = 1.8, pro_us_per_kfloat = 0.02, task_us = 0.6, sig_us = 0.8;
     const double ring_bytes = (double)s->tl.ring_pages * s->tl.page_bytes;
     const double window = ring_bytes > 0 ? ring_bytes : (double)(kPrefetch * kWaves * kChunkBytes);
     std::vector<double> t_cons(s->n_wg, 0.0), t_load(s->n_wg, 0.0), busy(s->n_wg, 0.0);
@@ -436,10 +482,14 @@ static SimResult simulate(const mk_schedule *s)
         if (I.op == OP_GEMV) {
             bytes = (double)task_chunks(I) * kChunkBytes;
             if (!(I.flags & F_SKIP_PRO)) {
-                double fl = (I.pro == PRO_EMBED_NORM || I.pro == PRO_RESID_NORM)
-                                ? (double)d.H * (1 + I.n_parts) : (double)I.xs_hi * kChunkK * I.n_parts * (I.pro == PRO_SILU ? 2 : 1);
-                pro = 0.25 + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
+                const uint32_t pr = instr_pro(I), np = instr_nparts(I);
+                const bool normk = pr == PRO_EMBED_NORM || pr == PRO_RESID_NORM;
+                double fl = normk ? (double)d.H * (1 + np) : (double)I.xs_hi * chunk_k(instr_rlog(I)) * np * (pr == PRO_SILU ? 2 : 1);
+                // one memory round trip per four partials in flight, plus the bytes themselves
+                pro = 0.8 + 0.8 * ((np + 3) / 4) + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
             }
+            // units are flushed through a cross-lane reduction: small R means more flushes per byte
+            pro += 0.004 * I.nu;
         } else if (I.op == OP_ATT) {
             bytes = (double)d.Tm / s->tl.nc * d.d * 4.0;
             pro = 0.5;
@@ -470,9 +520,10 @@ static SimResult simulate(const mk_schedule *s)
 static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_schedule *s)
 {
     s->cfg = cfg; s->dm = d; s->tl = t;
-    plan_weights(cfg, d, s->wm);
-    plan_act(d, t, s->am);
-    Builder b(cfg, d, t, s->wm, s->am);
+    derive_geom(d, t, s->gm);
+    plan_weights(cfg, d, s->gm, s->wm);
+    plan_act(d, s->gm, t, s->am);
+    Builder b(cfg, d, t, s->gm, s->wm, s->am);
     if (!b.build()) return MK_EINFEASIBLE;
     s->n_wg = cfg.n_workgroups;
     size_t mx = 0;
@@ -520,57 +571,64 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
     if (cfg.ring_kb > 0) { set_error("mk_config: ring_kb > 0 is not available in this build"); return MK_EINVAL; }
 
-    auto cands = [](int fixed, int kbt, std::initializer_list<int> opts) {
-        std::vector<int> v;
-        if (fixed > 0) { v.push_back(fixed); return v; }
-        for (int o : opts) if (split_ok(kbt, o)) v.push_back(o);
-        if (v.empty()) v.push_back(1);
-        return v;
+    for (int v : {cfg.split_qkv, cfg.split_o, cfg.split_gateup, cfg.split_down, cfg.attn_chunks})
+        if (v < 0) { set_error("mk_config: negative split / chunk count"); return MK_EINVAL; }
+    auto opt = [](int fixed, std::initializer_list<int> opts) {
+        return fixed > 0 ? std::vector<int>{fixed} : std::vector<int>(opts);
     };
-    std::vector<int> c_qkv = cands(cfg.split_qkv, d.kb_h, {1, 2, 4});
-    std::vector<int> c_o = cands(cfg.split_o, d.kb_qd, {1, 2, 4, 8});
-    std::vector<int> c_gu = cands(cfg.split_gateup, d.kb_h, {1, 2, 4});
-    std::vector<int> c_d = cands(cfg.split_down, d.kb_i, {1, 2, 4, 8, 16});
+    std::vector<int> c_sqkv = opt(cfg.split_qkv, {1, 2}), c_so = opt(cfg.split_o, {1, 2, 4}),
+                     c_sgu = opt(cfg.split_gateup, {1, 2}), c_sd = opt(cfg.split_down, {1, 2, 4, 8});
+    // rows per weight chunk: the matrix-core path needs 16; the VALU path may trade rows for K
+    std::vector<int> c_r = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2, 1};
+    std::vector<int> c_rgu = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2};
     std::vector<int> c_nc;
     if (cfg.attn_chunks > 0) c_nc.push_back(cfg.attn_chunks);
-    else {
-        for (int nc = 1; nc <= 256; nc *= 2) {
+    else
+        for (int nc = 1; nc <= 64; nc *= 2) {
             if ((int64_t)d.Bm * d.nkv * nc > 2 * (int64_t)cfg.n_workgroups && nc > 1) break;
             c_nc.push_back(nc);
         }
-    }
-    for (int v : {cfg.split_qkv, cfg.split_o, cfg.split_gateup, cfg.split_down})
-        if (v < 0) { set_error("mk_config: negative split"); return MK_EINVAL; }
-    if ((cfg.split_qkv > 0 && !split_ok(d.kb_h, cfg.split_qkv)) || (cfg.split_o > 0 && !split_ok(d.kb_qd, cfg.split_o)) ||
-        (cfg.split_gateup > 0 && !split_ok(d.kb_h, cfg.split_gateup)) || (cfg.split_down > 0 && !split_ok(d.kb_i, cfg.split_down))) {
-        set_error("mk_config: a fixed split leaves an empty unit");
-        return MK_EINVAL;
-    }
+
+    // A candidate is admissible when every K split leaves no empty unit, the norm-prologue
+    // operators have K a whole number of chunks, and the split gate/up path keeps 128-bit rows.
+    auto admissible = [&](const Tiling &t) {
+        Geom g;
+        derive_geom(d, t, g);
+        if (d.H % g.qkv.ck || d.H % g.gu.ck || d.H % g.head.ck) return false;
+        if (d.nqkv % g.qkv.R || d.qd % g.qkv.R || d.kvd % g.qkv.R) return false;
+        if (!split_ok(g.qkv.kbt, t.s_qkv) || !split_ok(g.o.kbt, t.s_o) || !split_ok(g.gu.kbt, t.s_gu) || !split_ok(g.down.kbt, t.s_d)) return false;
+        if (t.s_gu > 1 && g.gu.R < 8) return false;
+        return true;
+    };
 
     // coordinate descent over the tiling parameters, each candidate scored by the simulator
     Tiling best{};
-    best.s_qkv = c_qkv[0]; best.s_o = c_o[0]; best.s_gu = c_gu[0]; best.s_d = c_d[c_d.size() / 2];
+    best.s_qkv = c_sqkv[0]; best.s_o = c_so[0]; best.s_gu = c_sgu[0]; best.s_d = c_sd[0];
+    best.r_qkv = best.r_o = best.r_gu = best.r_d = best.r_head = 4;
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.ring_pages = 0; best.page_bytes = 16 * 1024; best.n_stage = 1;
     int tried = 0, pruned = 0;
     double best_ms = -1, best_duty = 0;
     auto eval = [&](const Tiling &t, double &ms, double &duty) {
-        mk_schedule tmp{};
         ++tried;
+        if (!admissible(t)) { ++pruned; return false; }
+        mk_schedule tmp{};
         int r = assemble(cfg, d, t, &tmp);
         if (r != MK_OK) { ++pruned; return false; }
         ms = tmp.sim.makespan_us; duty = tmp.sim.duty;
         return true;
     };
     struct Dim { int Tiling::*field; std::vector<int> *vals; };
-    Dim dimsv[] = {{&Tiling::s_qkv, &c_qkv}, {&Tiling::s_o, &c_o}, {&Tiling::s_gu, &c_gu}, {&Tiling::s_d, &c_d}, {&Tiling::nc, &c_nc}};
+    Dim dimsv[] = {{&Tiling::r_qkv, &c_r}, {&Tiling::s_qkv, &c_sqkv}, {&Tiling::r_o, &c_r}, {&Tiling::s_o, &c_so},
+                   {&Tiling::r_gu, &c_rgu}, {&Tiling::s_gu, &c_sgu}, {&Tiling::r_d, &c_r}, {&Tiling::s_d, &c_sd},
+                   {&Tiling::nc, &c_nc}};
     {
         double ms, du;
         if (eval(best, ms, du)) { best_ms = ms; best_duty = du; }
     }
     for (int round = 0; round < 2; ++round)
         for (auto &dm : dimsv) {
-            if (dm.vals->size() < 2) continue;
+            if (dm.vals->size() < 2 && best_ms >= 0) continue;
             for (int v : *dm.vals) {
                 Tiling t = best;
                 t.*(dm.field) = v;
@@ -582,7 +640,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
                 }
             }
         }
-    if (best_ms < 0) { set_error("no tiling candidate fits the LDS budget"); return MK_EINFEASIBLE; }
+    if (best_ms < 0) { set_error("no tiling candidate is admissible and fits the LDS budget"); return MK_EINFEASIBLE; }
 
     mk_schedule *s = new mk_schedule{};
     rc = assemble(cfg, d, best, s);
@@ -606,27 +664,38 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
     auto rd = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), false}); };
     auto wr = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), true}); };
     if (I.op == OP_GEMV) {
+        const uint32_t pro = instr_pro(I), np = instr_nparts(I), rlog = instr_rlog(I), R = 1u << rlog, ck = chunk_k(rlog);
         if (!(I.flags & F_SKIP_PRO)) {
             for (int b = 0; b < d.Bm; ++b) {
-                if (I.pro == PRO_RESID_NORM) {
+                if (pro == PRO_RESID_NORM) {
                     rd(I.in_base + (uint64_t)b * I.in_ld, d.H);
-                    for (uint32_t p = 0; p < I.n_parts; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld, d.H);
-                } else if (I.pro == PRO_PLAIN || I.pro == PRO_SILU) {
-                    uint64_t k0 = (uint64_t)I.xs_lo * kChunkK, k1 = std::min<uint64_t>(k0 + (uint64_t)I.xs_hi * kChunkK, I.k_len);
+                    for (uint32_t p = 0; p < np; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld, d.H);
+                } else if (pro == PRO_PLAIN || pro == PRO_SILU) {
+                    uint64_t k0 = (uint64_t)I.xs_lo * ck, k1 = std::min<uint64_t>(k0 + (uint64_t)I.xs_hi * ck, I.k_len);
                     if (k1 > k0) {
-                        uint64_t lo = k0, n = k1 - k0;
-                        if (I.pro == PRO_SILU) { lo = (k0 / 16) * 32; n = (k1 + 15) / 16 * 32 - lo; }
-                        for (uint32_t p = 0; p < I.n_parts; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld + lo, n);
+                        uint64_t lo = k0, n = (k1 - k0 + 3) / 4 * 4;
+                        if (pro == PRO_SILU) {
+                            const uint64_t PR = 1ull << instr_prod_rlog(I), half = PR / 2;
+                            lo = (k0 / half) * PR; n = (k1 + half - 1) / half * PR - lo;
+                        }
+                        for (uint32_t p = 0; p < np; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld + lo, n);
                     }
                 }
-                if ((I.pro == PRO_RESID_NORM || I.pro == PRO_EMBED_NORM) && I.xs_hi > I.xs_lo)
+                if ((pro == PRO_RESID_NORM || pro == PRO_EMBED_NORM) && I.xs_hi > I.xs_lo)
                     wr(I.xs_out + (uint64_t)b * I.in_ld + I.xs_lo, I.xs_hi - I.xs_lo);
             }
         }
         if (!(I.flags & F_LOGITS)) {
             for (uint32_t u = I.u0; u < I.u0 + I.nu; ++u)
-                for (int b = 0; b < d.Bm; ++b)
-                    wr(I.out + (uint64_t)(u % I.S) * I.out_split_stride + (uint64_t)b * I.out_ld + (uint64_t)(u / I.S) * 16, 16);
+                for (int b = 0; b < d.Bm; ++b) {
+                    if (I.flags & F_SILU_EPI) {
+                        wr(I.out + (uint64_t)b * I.out_ld + (uint64_t)u * (R / 2), R / 2);
+                    } else {
+                        const uint64_t row0 = (uint64_t)(u / I.S) * R;
+                        if (I.flags & F_ADD_RESID) rd(I.resid + (uint64_t)b * I.out_ld + row0, R);
+                        wr(I.out + (uint64_t)(u % I.S) * I.out_split_stride + (uint64_t)b * I.out_ld + row0, R);
+                    }
+                }
         }
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
@@ -637,11 +706,11 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
             rd(base + d.qd + d.kvd + (uint64_t)A.g * d.d, d.d);
         }
         for (int h = 0; h < d.G; ++h)
-            wr(A.out + (((uint64_t)A.b * d.nq + A.g * d.G + h) * A.nc + A.c) * (d.d + 2), d.d + 2);
+            wr(A.out + (((uint64_t)A.b * d.nq + A.g * d.G + h) * A.nc + A.c) * (d.d + kPartPad), d.d + 2);
     } else if (I.op == OP_COMB) {
         const InstrAtt &A = *(const InstrAtt *)&I;
         for (uint32_t h = A.h0; h < A.h0 + A.nh; ++h) {
-            rd(A.out + (((uint64_t)A.b * d.nq + h) * A.nc) * (d.d + 2), (uint64_t)A.nc * (d.d + 2));
+            for (uint32_t c = 0; c < A.nc; ++c) rd(A.out + (((uint64_t)A.b * d.nq + h) * A.nc + c) * (d.d + kPartPad), d.d + 2);
             wr(A.o_out + (uint64_t)A.b * A.o_ld + (uint64_t)h * d.d, d.d);
         }
     }
@@ -656,7 +725,7 @@ int verify_schedule(const mk_schedule *s)
     const int n_wg = s->n_wg, mi = s->max_instr;
     const Dims &d = s->dm;
     const Instr *all = (const Instr *)s->instr.data();
-    if (n_wg < 1 || mi < 1 || (int)s->instr.size() != n_wg * mi * kInstrDwords) return fail("malformed instruction array");
+    if (n_wg < 1 || n_wg > 65535 || mi < 1 || (int)s->instr.size() != n_wg * mi * kInstrDwords) return fail("malformed instruction array");
     if (mi > 65535) return fail("instruction list too long");
 
     // (1) every list ends with END and holds known opcodes; counters: wait target == signals per step
@@ -706,9 +775,11 @@ int verify_schedule(const mk_schedule *s)
                 }
             }
         for (int l = 0; l <= d.L; ++l) {
+            const Geom &gm = s->gm;
             struct { uint32_t st; uint32_t total; } g[] = {
-                {ST_QKV, (uint32_t)d.rb_qkv * s->tl.s_qkv}, {ST_O, (uint32_t)d.rb_o * s->tl.s_o},
-                {ST_GU, (uint32_t)d.rb_gu * s->tl.s_gu}, {ST_DOWN, (uint32_t)d.rb_d * s->tl.s_d}, {ST_HEAD, (uint32_t)d.rb_v}};
+                {ST_QKV, (uint32_t)gm.qkv.groups * s->tl.s_qkv}, {ST_O, (uint32_t)gm.o.groups * s->tl.s_o},
+                {ST_GU, (uint32_t)gm.gu.groups * s->tl.s_gu}, {ST_DOWN, (uint32_t)gm.down.groups * s->tl.s_d},
+                {ST_HEAD, (uint32_t)gm.head.groups}};
             for (auto &e : g) {
                 if ((l == d.L) != (e.st == ST_HEAD)) continue;
                 auto &v = units[l * 8 + e.st];
@@ -756,23 +827,20 @@ int verify_schedule(const mk_schedule *s)
         }
     }, &why);
     if (!ok) return fail(why.empty() ? "replay did not terminate" : why);
+    std::vector<uint16_t> t_wg(n_tasks), t_idx(n_tasks);
+    for (int w = 0; w < n_wg; ++w)
+        for (int i = 0; i < cnt[w]; ++i) { t_wg[first[w] + i] = (uint16_t)w; t_idx[first[w] + i] = (uint16_t)i; }
     auto hb = [&](uint32_t a, uint32_t b) {   // task ids: does a happen before b?
-        int wa = (int)(std::upper_bound(first.begin(), first.end(), (size_t)a) - first.begin()) - 1;
-        int ia = (int)(a - first[wa]);
-        int wb = (int)(std::upper_bound(first.begin(), first.end(), (size_t)b) - first.begin()) - 1;
-        int ib = (int)(b - first[wb]);
-        if (wa == wb) return ia < ib;
-        return vc[(size_t)b * n_wg + wa] >= (uint16_t)(ia + 1);
+        const int wa = t_wg[a], wb = t_wg[b];
+        if (wa == wb) return t_idx[a] < t_idx[b];
+        return vc[(size_t)b * n_wg + wa] >= (uint16_t)(t_idx[a] + 1);
     };
 
     // (4) walk the tasks in topological (operator) order with a last-writers table: every
     //     read-after-write, write-after-read and write-after-write pair must be ordered.
     std::vector<uint32_t> order(n_tasks);
     std::iota(order.begin(), order.end(), 0u);
-    auto instr_of = [&](uint32_t t) -> const Instr & {
-        int w = (int)(std::upper_bound(first.begin(), first.end(), (size_t)t) - first.begin()) - 1;
-        return all[(size_t)w * mi + (t - first[w])];
-    };
+    auto instr_of = [&](uint32_t t) -> const Instr & { return all[(size_t)t_wg[t] * mi + t_idx[t]]; };
     std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return instr_of(a).ref_seq < instr_of(b).ref_seq; });
     // F_SKIP_PRO is only legal directly after a GEMV of the same operator instance with the same staged input
     for (int w = 0; w < n_wg; ++w)
@@ -781,8 +849,8 @@ int verify_schedule(const mk_schedule *s)
             if (I.op == OP_GEMV && (I.flags & F_SKIP_PRO)) {
                 if (i == 0) return fail("first instruction skips its prologue");
                 const Instr &Pv = all[(size_t)w * mi + i - 1];
-                bool same = Pv.op == OP_GEMV && Pv.ref_seq == I.ref_seq && Pv.pro == I.pro;
-                if (same && (I.pro == PRO_PLAIN || I.pro == PRO_SILU)) same = Pv.xs_lo == I.xs_lo && Pv.xs_hi == I.xs_hi;
+                bool same = Pv.op == OP_GEMV && Pv.ref_seq == I.ref_seq && Pv.cfg == I.cfg;
+                if (same && (instr_pro(I) == PRO_PLAIN || instr_pro(I) == PRO_SILU)) same = Pv.xs_lo == I.xs_lo && Pv.xs_hi == I.xs_hi;
                 if (!same) return fail("prologue skipped although LDS does not hold this task's input");
             }
         }
@@ -862,7 +930,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 1;
+constexpr uint32_t kVersion = 2;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)

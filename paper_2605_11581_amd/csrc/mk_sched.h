@@ -14,18 +14,27 @@ namespace mk {
 struct Dims {
     int L, H, nq, nkv, d, I, V, Bm, Tm, G;
     int qd, kvd, nqkv;       // fused QKV rows
-    int ipad;                // intermediate padded to 16
-    int ngu;                 // fused gate/up rows = 2 * ipad
-    int kb_h, kb_qd, kb_i;   // k blocks (32) of hidden, nq*d, intermediate (padded)
-    int rb_qkv, rb_o, rb_gu, rb_d, rb_v;   // row blocks (16)
 };
 
 struct Tiling {              // the searched parameters (Sec. 4.2.2 Step 3, "tiling parameter space")
     int s_qkv, s_o, s_gu, s_d;   // K splits
+    int r_qkv, r_o, r_gu, r_d, r_head;   // log2 of the rows per weight chunk, per matrix
     int nc;                      // attention chunk tasks per (sequence, kv head)
     int bs;                      // positions per attention block
     int mfma;                    // 0 VALU, 1 MFMA
     int ring_pages, page_bytes, n_stage;  // Eq. 1-2 outcome (0 pages: weights go straight to registers)
+};
+
+struct MatGeom {             // tile-major geometry of one matrix under a tiling
+    int rlog, R, ck;         // rows per chunk, k per chunk (512 / R)
+    int groups;              // row groups (of R rows)
+    int kbt;                 // chunks per row group
+    int n_rows, k_len;       // true output rows and K
+};
+
+struct Geom {
+    MatGeom qkv, o, gu, down, head;
+    int ipad;                // intermediate padded so that gate and up fill whole half groups
 };
 
 struct WeightMap {           // chunk / element offsets inside the workspace
@@ -37,7 +46,7 @@ struct WeightMap {           // chunk / element offsets inside the workspace
 };
 
 struct ActMap {              // float offsets inside the activation region
-    uint32_t xa, xb, pqkv, attp, o, po, gu, pd;
+    uint32_t xa, xb, pqkv, attp, o, po, gu, pd;   // gu holds silu(gate)*up when the gate/up epilogue is fused
     uint64_t n_floats;
 };
 
@@ -51,6 +60,7 @@ struct mk_schedule {
     mk_config cfg;
     mk::Dims dm;
     mk::Tiling tl;
+    mk::Geom gm;
     mk::WeightMap wm;
     mk::ActMap am;
     mk::Layout lay;
