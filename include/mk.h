@@ -62,6 +62,7 @@ typedef struct mk_config {
     int32_t ring_kb;         /* LDS weight-page ring in KB; 0 = no ring (direct loads), -1 = auto */
     int32_t split_qkv, split_o, split_gateup, split_down; /* K splits; 0 = search    */
     int32_t attn_chunks;     /* attention tasks per (sequence, KV head); 0 = search  */
+    int32_t chunk_rows;      /* rows per 1 KB weight chunk for every matrix (2,4,8,16); 0 = search per matrix */
     uint32_t spin_limit;     /* dependency-wait poll limit; 0 = library default      */
     uint32_t flags;          /* MK_F_*                                               */
 } mk_config;

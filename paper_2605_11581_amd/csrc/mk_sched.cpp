@@ -581,6 +581,11 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     // rows per weight chunk: the matrix-core path needs 16; the VALU path may trade rows for K
     std::vector<int> c_r = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2, 1};
     std::vector<int> c_rgu = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2};
+    if (cfg.chunk_rows) {
+        int rl = cfg.chunk_rows == 2 ? 1 : cfg.chunk_rows == 4 ? 2 : cfg.chunk_rows == 8 ? 3 : cfg.chunk_rows == 16 ? 4 : -1;
+        if (rl < 0 || (mfma && rl != 4)) { set_error("mk_config: chunk_rows must be 2, 4, 8 or 16 (16 on the matrix-core path)"); return MK_EINVAL; }
+        c_r = {rl}; c_rgu = {rl};
+    }
     std::vector<int> c_nc;
     if (cfg.attn_chunks > 0) c_nc.push_back(cfg.attn_chunks);
     else
@@ -604,7 +609,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     // coordinate descent over the tiling parameters, each candidate scored by the simulator
     Tiling best{};
     best.s_qkv = c_sqkv[0]; best.s_o = c_so[0]; best.s_gu = c_sgu[0]; best.s_d = c_sd[0];
-    best.r_qkv = best.r_o = best.r_gu = best.r_d = best.r_head = 4;
+    best.r_qkv = best.r_o = best.r_gu = best.r_d = c_r[0]; best.r_head = cfg.chunk_rows ? c_r[0] : 4;
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.ring_pages = 0; best.page_bytes = 16 * 1024; best.n_stage = 1;
     int tried = 0, pruned = 0;

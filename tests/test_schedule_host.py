@@ -1,0 +1,219 @@
+"""Host-side checks that need no GPU: the C ABI loads and exports what include/mk.h
+declares, the page-budget equations agree with the oracle and the paper's figures, and the
+offline scheduler / verifier / serialiser behave (including rejecting corrupted schedules)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_11581_amd import binding as mk, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+KNONE = 0xFFFFFFFF
+# dword indices of the instruction format (mk_isa.h)
+OP, FLAGS, REF_SEQ, WAIT_CTR0, WAIT_CNT0, SIG_CTR, U0, NU = 0, 1, 2, 4, 6, 8, 13, 14
+
+
+def build(name="c0_tiny", **opts):
+    cfg = synth.model_cfg(synth.CONFIGS[name])
+    opts.setdefault("n_workgroups", 256)
+    return mk.mk_build_schedule(mk.make_config(cfg, **opts))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mk.h")).read()
+    declared = set(re.findall(r"\b(mk_[a-z_0-9]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    lib = mk.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"libmk.so does not export {name}"
+    assert declared == set(mk.EXPORTS)
+
+
+def test_page_budget_equations_match_oracle_and_paper():
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        a = [int(x) for x in rng.integers(0, 300000, size=6)]
+        a[5] = max(a[5], 1)
+        assert mk.mk_pages_available(*a) == oracle.pages_available(*a)
+        b = [int(x) for x in rng.integers(0, 64, size=5)]
+        b[4] = max(b[4], 1)
+        assert mk.mk_pipeline_stages(*b) == oracle.pipeline_stages(*b)
+    # Sec. 4.3.2: 64 KB -> 32 KB per iteration is 4 -> 2 pages of 16 KB
+    assert mk.mk_pages_available(65536, 0, 0, 0, 0, 16384) == 4
+    assert mk.mk_pages_available(32768, 0, 0, 0, 0, 16384) == 2
+    # Sec. 1: 128 KB sustains 2 stages of a 4-page iteration; halving K (2 pages) restores 4
+    n = mk.mk_pages_available(128 * 1024, 1, 0, 0, 0, 16384)
+    assert mk.mk_pipeline_stages(n, 0, 0, 0, 4) == 2 and mk.mk_pipeline_stages(n, 0, 0, 0, 2) == 4
+
+
+@pytest.mark.parametrize("name", ["c0_tiny", "c1_0p5b", "c2_1p5b", "c3_4b"])
+def test_schedules_build_and_verify(name):
+    h = build(name)
+    mk.mk_schedule_verify(h)
+    st = mk.mk_get_stats(h)
+    full = synth.CONFIGS[name]
+    L, H, d = full["n_layers"], full["hidden"], full["head_dim"]
+    qd, kvd, I, V = full["n_q_heads"] * d, full["n_kv_heads"] * d, full["intermediate"], full["vocab"]
+    algorithmic = 2 * (L * (H * (qd + 2 * kvd) + qd * H + 3 * H * I) + V * H)
+    # the streamed (tile-padded) weights cover the algorithmic bytes with little padding
+    assert algorithmic <= st["weight_bytes_per_step"] <= algorithmic * 1.06
+    assert st["n_workgroups"] == 256 and st["lds_bytes"] <= 160 * 1024
+    assert st["sim_makespan_us"] > 0 and 0 < st["sim_duty_cycle"] <= 1
+    assert st["candidates_tried"] > st["candidates_pruned"] >= 0
+    mk.mk_destroy(h)
+
+
+def test_batched_schedule_uses_matrix_cores_and_fits_lds():
+    cfg = synth.model_cfg(synth.CONFIGS["c4_7b"], n_layers=2, vocab=4096)
+    h = mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=256))
+    st = mk.mk_get_stats(h)
+    assert st["use_mfma"] == 1 and st["rows_qkv"] == 16 and st["lds_bytes"] <= 160 * 1024
+    mk.mk_destroy(h)
+
+
+@pytest.mark.parametrize("n_wg", [1, 7, 64, 304])
+def test_other_grid_sizes(n_wg):
+    h = build("c0_tiny", n_workgroups=n_wg)
+    mk.mk_schedule_verify(h)
+    assert mk.mk_get_stats(h)["n_workgroups"] == n_wg
+    mk.mk_destroy(h)
+
+
+def test_fixed_tiling_overrides_are_honoured():
+    h = build("c0_tiny", split_qkv=2, split_o=2, split_gateup=2, split_down=2, attn_chunks=4)
+    st = mk.mk_get_stats(h)
+    assert (st["split_qkv"], st["split_o"], st["split_gateup"], st["split_down"], st["attn_chunks"]) == (2, 2, 2, 2, 4)
+    mk.mk_schedule_verify(h)
+    mk.mk_destroy(h)
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=8), dict(hidden=100), dict(max_batch=9), dict(max_batch=0),
+                                 dict(n_q_heads=3), dict(n_layers=0), dict(max_context=0),
+                                 dict(max_batch=2, use_mfma=0), dict(ring_kb=64), dict(split_down=10 ** 6)])
+def test_bad_configs_are_rejected(bad):
+    cfg = synth.model_cfg(synth.CONFIGS["c0_tiny"])
+    opts = {k: bad.pop(k) for k in list(bad) if k in ("use_mfma", "ring_kb", "split_down")}
+    cfg.update(bad)
+    with pytest.raises(mk.MkError) as e:
+        mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=64, **opts))
+    assert e.value.code in (mk.MK_EINVAL, mk.MK_EINFEASIBLE)
+
+
+def test_build_is_deterministic_and_roundtrips():
+    h1, h2 = build("c0_tiny"), build("c0_tiny")
+    b1, b2 = mk.mk_schedule_dump(h1), mk.mk_schedule_dump(h2)
+    assert b1 == b2
+    h3 = mk.mk_schedule_load(b1)
+    assert mk.mk_schedule_dump(h3) == b1
+    for wg in (0, 17, 255):
+        n = mk.mk_instr_count(h1, wg)
+        assert n == mk.mk_instr_count(h3, wg)
+        for i in range(n):
+            assert np.array_equal(mk.mk_instr_get(h1, wg, i), mk.mk_instr_get(h3, wg, i))
+    with pytest.raises(mk.MkError):
+        mk.mk_schedule_load(b1[:-8])
+    with pytest.raises(mk.MkError):
+        mk.mk_schedule_load(b"\0" * 64)
+    bad = bytearray(b1); bad[0] ^= 0xFF
+    with pytest.raises(mk.MkError):
+        mk.mk_schedule_load(bytes(bad))
+    for h in (h1, h2, h3):
+        mk.mk_destroy(h)
+
+
+def _first(h, wg, pred):
+    for i in range(mk.mk_instr_count(h, wg)):
+        w = mk.mk_instr_get(h, wg, i)
+        if pred(w):
+            return i, w
+    raise AssertionError("no such instruction")
+
+
+def _expect_rejected(h, needle=None):
+    with pytest.raises(mk.MkError) as e:
+        mk.mk_schedule_verify(h)
+    assert e.value.code == mk.MK_ESCHED
+    if needle:
+        assert needle in str(e.value), str(e.value)
+    mk.mk_destroy(h)
+
+
+def test_verifier_rejects_swapped_dependent_instructions():
+    h = build("c0_tiny", n_workgroups=4)
+    a, b = mk.mk_instr_get(h, 0, 0), mk.mk_instr_get(h, 0, 1)
+    assert a[REF_SEQ] != b[REF_SEQ]
+    mk.mk_instr_set(h, 0, 0, b); mk.mk_instr_set(h, 0, 1, a)
+    _expect_rejected(h)      # the later operator now blocks its own producer: deadlock
+
+
+def test_verifier_rejects_wrong_counter_target():
+    h = build("c0_tiny")
+    i, w = _first(h, 3, lambda w: w[WAIT_CTR0] != KNONE)
+    w[WAIT_CNT0] += 1
+    mk.mk_instr_set(h, 3, i, w)
+    _expect_rejected(h, "waits for")
+
+
+def test_verifier_rejects_dropped_wait():
+    h = build("c0_tiny")
+    i, w = _first(h, 5, lambda w: w[WAIT_CTR0] != KNONE and w[OP] == 1)
+    w[WAIT_CTR0] = KNONE
+    mk.mk_instr_set(h, 5, i, w)
+    _expect_rejected(h, "not ordered")
+
+
+def test_verifier_rejects_dropped_signal_and_bad_counter():
+    h = build("c0_tiny")
+    i, w = _first(h, 9, lambda w: w[SIG_CTR] != KNONE)
+    w[SIG_CTR] = KNONE
+    mk.mk_instr_set(h, 9, i, w)
+    _expect_rejected(h)
+    h = build("c0_tiny")
+    i, w = _first(h, 9, lambda w: w[SIG_CTR] != KNONE)
+    w[SIG_CTR] = 10 ** 6
+    mk.mk_instr_set(h, 9, i, w)
+    _expect_rejected(h, "does not exist")
+
+
+def test_verifier_rejects_missing_or_duplicated_tile():
+    h = build("c0_tiny")
+    i, w = _first(h, 11, lambda w: w[OP] == 1)
+    w[U0] += 1
+    mk.mk_instr_set(h, 11, i, w)
+    _expect_rejected(h, "unit")
+
+
+def test_verifier_rejects_list_without_end_and_unknown_opcode():
+    h = build("c0_tiny")
+    w = mk.mk_instr_get(h, 0, 0)
+    w[OP] = 77
+    mk.mk_instr_set(h, 0, 0, w)
+    _expect_rejected(h, "opcode")
+
+
+def test_weight_prefetch_is_independent_of_activations():
+    """Sec. 4.2.3 (asynchronous prefetching): weight tiles carry no activation dependency, so
+    every GEMV instruction names its weight chunks statically -- they are a pure function of the
+    instruction, identical from step to step."""
+    h = build("c2_1p5b")
+    seen = 0
+    for wg in (0, 100, 255):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if w[OP] == 1:
+                assert w[NU] >= 1 and w[9] < 2 ** 31      # w_chunk is a constant of the schedule
+                seen += 1
+    assert seen > 300
+    mk.mk_destroy(h)
+
+
+def test_no_oracle_in_product_path():
+    pkg = os.path.join(ROOT, "paper_2605_11581_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, f
