@@ -35,6 +35,18 @@ def algorithmic_bytes(cfg, batch: int, T: float) -> float:
     return weights + kv + 4.0 * batch * V
 
 
+def measured_traffic(config: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload (or None)."""
+    path = os.path.join(ROOT, "profiles", f"mk_megakernel_{config}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +56,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-op", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy (counter calibration)")
     ap.add_argument("--opt", action="append", default=[], help="schedule override key=value (e.g. split_down=4)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -81,6 +94,14 @@ def main() -> int:
     def run(first: int, n: int, per_op: bool = False):
         for i in range(first, first + n):
             dec.step(toks[i], poss[i], kv_d, logits, per_op=per_op)
+
+    if args.calib_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---- timed region: K steps back to back on one stream, one launch each
     run(0, warmup)
@@ -120,7 +141,7 @@ def main() -> int:
                                                           "split_down", "attn_chunks", "use_mfma", "lds_bytes")}},
         "hbm_gbs_whole_run": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config) if B == 1 else None,
                      "kernel": "mk_megakernel", "kernel_ms": round(kern_ms, 5), "algorithmic_bytes": int(bytes_launch)},
     }
 
