@@ -186,8 +186,9 @@ int mk_last_step_ms(mk_schedule *s, float *ms);
  * the workspace). */
 int mk_set_flags(mk_schedule *s, uint32_t flags);
 
-/* Copy the per-task trace (MK_F_TRACE) to host: records of 4 x uint64
- * {wg<<32|instr, t_begin, t_dep_ready, t_end} in device wall-clock ticks.
+/* Copy the per-task trace (MK_F_TRACE) to host: records of 8 x uint64, one per
+ * (workgroup, instruction): {t_begin, t_dependencies_met, t_prologue_done, t_end, 4 task-internal marks}
+ * in device wall-clock ticks (100 MHz).
  * *n_records in: capacity, out: records written. */
 int mk_read_trace(mk_schedule *s, uint64_t *host_out, size_t *n_records, void *stream);
 

@@ -254,7 +254,7 @@ def mk_set_flags(h, flags: int) -> None:
 def mk_read_trace(h, stream=None) -> np.ndarray:
     st = mk_get_stats(h)
     cap = st["n_workgroups"] * (st["max_instr_per_wg"] + 1)
-    out = np.zeros((cap, 4), dtype=np.uint64)
+    out = np.zeros((cap, 8), dtype=np.uint64)
     n = C.c_size_t(cap)
     _chk(lib().mk_read_trace(h, out.ctypes.data_as(C.c_void_p), C.byref(n), _stream(stream)))
     return out[: n.value]

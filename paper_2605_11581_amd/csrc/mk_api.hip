@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -32,6 +33,17 @@ int hip_fail(hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail(e_, #expr); \
     } while (0)
 
+// Tuning knobs read from the environment (development only; defaults are the shipped values).
+uint32_t dbg_knob(const char *name, uint32_t dflt, uint32_t lo, uint32_t hi)
+{
+    const char *v = getenv(name);
+    if (!v || !*v) return dflt;
+    long x = strtol(v, nullptr, 10);
+    if (x < (long)lo) x = lo;
+    if (x > (long)hi) x = hi;
+    return (uint32_t)x;
+}
+
 mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv,
                        float *logits, int batch)
 {
@@ -46,6 +58,9 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.max_instr = (uint32_t)s->max_instr; P.flags = s->cfg.flags;
     P.embed_chunk = s->wm.embed; P.embed_kbt = (uint32_t)s->gm.head.kbt; P.embed_rlog = (uint32_t)s->gm.head.rlog;
     P.only_seq = mk::kNone; P.act_bytes = (uint32_t)(s->am.n_floats * 4);
+    P.ctr_stride = dbg_knob("MK_DBG_CTR_STRIDE", mk::kCounterStride, 1, mk::kCounterStrideMax);
+    P.poll_sleep = dbg_knob("MK_DBG_POLL_SLEEP", 0, 0, 64);
+    P.dbg = dbg_knob("MK_DBG_UNSAFE_TIMING", 0, 0, 7);
     return P;
 }
 
@@ -69,7 +84,7 @@ int fill_u32(void *dst, uint32_t v, size_t n, hipStream_t st)
 
 int reset_sync_state(mk_schedule *s, hipStream_t st)
 {
-    int rc = fill_u32(s->ws + s->lay.counters, 0u, (size_t)s->n_counters * mk::kCounterStride, st);
+    int rc = fill_u32(s->ws + s->lay.counters, 0u, (size_t)s->n_counters * mk::kCounterStrideMax, st);
     if (rc) return rc;
     rc = fill_u32(s->ws + s->lay.err, 0u, 16, st);
     s->epoch = 0;
@@ -186,8 +201,16 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_x2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     int per_cu = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel, mk::kWgThreads, s->lds_total));
+    s->two_per_cu = !s->tl.ring_pages && s->n_wg > prop.multiProcessorCount;
+    if (s->two_per_cu)
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_x2, mk::kWgThreads, s->lds_total));
+    else if (s->tl.ring_pages)
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_ring, mk::kWgThreads + 64, s->lds_total));
+    else
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel, mk::kWgThreads, s->lds_total));
     if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
         char buf[200];
         snprintf(buf, sizeof buf, "the device keeps only %d x %d workgroups resident, the schedule needs %d", per_cu, prop.multiProcessorCount, s->n_wg);
@@ -215,7 +238,7 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     int rc = reset_sync_state(s, st);
     if (rc) return rc;
     if (s->cfg.flags & MK_F_TRACE) {
-        rc = fill_u32(s->ws + s->lay.trace, 0u, (size_t)s->n_wg * s->max_instr * 8, st);
+        rc = fill_u32(s->ws + s->lay.trace, 0u, (size_t)s->n_wg * s->max_instr * 16, st);
         if (rc) return rc;
     }
     if (!s->ev_valid) {
@@ -310,10 +333,15 @@ int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positio
     }
     s->epoch += 1;
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
-    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
-    hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    if (s->two_per_cu)
+        hipLaunchKernelGGL(mk_megakernel_x2, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    else if (s->tl.ring_pages)
+        hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads + 64), s->lds_total, st, P, lp);
+    else
+        hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
     return MK_OK;
@@ -326,7 +354,7 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
-    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off};
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, 0, 0};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     for (uint32_t seq : s->ref_seqs) {
@@ -383,7 +411,7 @@ int mk_read_trace(mk_schedule *s, uint64_t *host_out, size_t *n_records, void *s
     size_t have = (size_t)s->n_wg * s->max_instr;
     size_t n = *n_records < have ? *n_records : have;
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
-    HIP_TRY(hipMemcpy(host_out, s->ws + s->lay.trace, n * 32, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(host_out, s->ws + s->lay.trace, n * 64, hipMemcpyDeviceToHost));
     *n_records = n;
     return MK_OK;
 }

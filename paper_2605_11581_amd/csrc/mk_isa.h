@@ -23,7 +23,8 @@ constexpr int kInstrDwords = 32;
 constexpr uint32_t kNone = 0xffffffffu;
 constexpr int kMaxBatch = 8;
 constexpr int kMaxGroup = 8;           // q heads per kv head
-constexpr int kCounterStride = 32;     // dwords between counters (one 128-byte line each)
+constexpr int kCounterStride = 32;     // default dwords between counters (one 128-byte line each)
+constexpr int kCounterStrideMax = 1088; // the counter region is sized for strides up to this
 constexpr int kPrefetch = 16;          // 128-bit weight loads a lane keeps in flight (direct-load path)
 
 // LDS map of a workgroup:
@@ -132,7 +133,7 @@ struct Layout {
     uint64_t counters;   // uint32, one per 128-byte line
     uint64_t instr;      // Instr[n_wg][max_instr]
     uint64_t err;        // uint32[8] sticky error flags
-    uint64_t trace;      // uint64[n_wg][max_instr][4]: task begin, dependencies met, prologue done, end
+    uint64_t trace;      // uint64[n_wg][max_instr][8]: task begin, dependencies met, prologue done, end, 4 task-internal marks
     uint64_t total;
 };
 
@@ -155,6 +156,9 @@ struct Params {
     uint32_t embed_kbt, embed_rlog;
     uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
     uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
+    uint32_t ctr_stride;  // dwords between dependency counters
+    uint32_t poll_sleep;  // s_sleep units between two polls of a dependency counter
+    uint32_t dbg;         // timing experiments only: bit 0 skip dependency waits, bit 1 skip the store drain (results invalid)
 };
 
 }  // namespace mk

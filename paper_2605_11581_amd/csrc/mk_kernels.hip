@@ -25,7 +25,52 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct LdsPlan {
     uint32_t red_bytes;   // cross-wave reduction region
     uint32_t xs_off;      // byte offset of the staged-input region
+    uint32_t ring_off;    // byte offset of the weight-page ring (ring kernel only)
+    uint32_t ring_slots;  // 1 KB chunk slots in the ring (multiple of 4)
 };
+
+// Per-wave view of the workgroup: LDS plan plus the state of the consumer barrier.
+// In the ring kernel a fifth wave (the loader) streams weights into LDS pages and never
+// takes part in barriers, so the four consumer waves synchronise through an LDS counter
+// instead of s_barrier.
+struct Wg {
+    uint32_t red_bytes, xs_off, ring_off, ring_slots;
+    bool ring;
+    uint32_t bar_target;  // consumer barrier: arrivals expected so far
+    uint32_t chunk_n;     // ring: global index (in this workgroup's weight stream) of the next task's first chunk
+    uint32_t landed_c;    // ring: cached copy of the loader's published count
+    int npf;              // 128-bit weight loads a lane keeps in flight (direct-load path), <= kPrefetch
+};
+
+// LDS sync words of the ring kernel (inside the misc area)
+constexpr int kSyncLanded = kLdsMisc + 192;   // chunks the loader has published as landed
+constexpr int kSyncHw = kLdsMisc + 208;       // [4] per consumer wave: 1 + last chunk it has finished with (16-byte aligned)
+constexpr int kSyncBar = kLdsMisc + 224;      // consumer barrier counter
+constexpr uint32_t kLdsSpinLimit = 1u << 24;
+
+// LDS sync words are read through explicit local-address-space volatile pointers (a generic
+// volatile pointer would turn every poll into a flat load).
+typedef volatile __attribute__((address_space(3))) uint32_t *lds_vptr;
+__device__ __forceinline__ lds_vptr lds_word(char *lds, int byte_off)
+{
+    return (lds_vptr)((__attribute__((address_space(3))) char *)lds + byte_off);
+}
+
+__device__ __forceinline__ void wg_sync(Wg &wg, char *lds)
+{
+    if (!wg.ring) {
+        __syncthreads();
+        return;
+    }
+    lds_vptr bar = lds_word(lds, kSyncBar);
+    wg.bar_target += kWaves;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    uint32_t it = 0;
+    while ((int32_t)(*bar - wg.bar_target) < 0)
+        if (++it > kLdsSpinLimit) break;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ uint32_t rfl(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -95,11 +140,12 @@ __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
 // Poll a dependency counter until it has received `target` signals (wrap-safe).
 // Bounded: after `limit` polls the wait gives up and reports failure, so every
 // wave always reaches the end of its instruction list.
-__device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t target, uint32_t limit)
+__device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t target, uint32_t limit, uint32_t nap)
 {
     uint32_t it = 0;
     while ((int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
         if (++it > limit) return false;
+        for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(2);
     }
     return true;
 }
@@ -178,7 +224,7 @@ __device__ __forceinline__ int nterm_of(int batch) { return batch <= 5 ? 3 : 2; 
 constexpr int kQuadsPerThread = 4;   // hidden <= 4 * 4 * 256
 
 template <bool MFMA>
-__device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, int batch)
+__device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, char *lds, Wg &lp, int batch)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     char *xs = lds + lp.xs_off;
@@ -243,7 +289,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
             ss = wave_sum(ss);
             float *slot = misc + (b & 1) * 8;
             if (lane == 0) slot[wave] = ss;
-            __syncthreads();
+            wg_sync(lp, lds);
             float tot = slot[0] + slot[1] + slot[2] + slot[3];
             float inv = 1.0f / sqrtf(tot / (float)H + P.rms_eps);
 #pragma unroll
@@ -266,6 +312,30 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         const uint32_t prl = instr_prod_rlog(I), PR = 1u << prl;
         for (int b = 0; b < batch; ++b) {
             const uint32_t brow = (uint32_t)b * I.in_ld;
+            if (pro == PRO_PLAIN && n_parts == 1) {
+                // common case (unsplit producer): eight 128-bit loads in flight per lane, one memory round
+                // trip for up to 8192 staged elements
+                constexpr int U = 8;
+                for (int i0 = tid * 4; i0 < kn; i0 += kWgThreads * 4 * U) {
+                    f32x4 y[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int i = i0 + u * kWgThreads * 4;
+                        const uint32_t k = (uint32_t)(k0 + i);
+                        y[u] = ld_act4(ab, (i < kn && k < I.k_len) ? I.in_parts + brow + k : 0xfffffff0u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int i = i0 + u * kWgThreads * 4;
+                        const uint32_t k = (uint32_t)(k0 + i);
+                        if (k + 1 >= I.k_len) y[u].y = 0.f;
+                        if (k + 2 >= I.k_len) y[u].z = 0.f;
+                        if (k + 3 >= I.k_len) y[u].w = 0.f;
+                        if (i < kn) store_x4<MFMA>(xs, b, i, y[u], nterm, plane_stride);
+                    }
+                }
+                continue;
+            }
             for (int i0 = tid * 4; i0 < kn; i0 += kWgThreads * 4 * 2) {
                 // two quads per thread and iteration keep several loads in flight
                 f32x4 y[2];
@@ -304,7 +374,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
             }
         }
     }
-    __syncthreads();
+    wg_sync(lp, lds);
 }
 
 // chunks in unit u of a matrix with S splits of nkb chunks per row group (last split ragged)
@@ -322,24 +392,26 @@ struct GemvStream {
 
 // Issue the first weight loads of a GEMV task.  They depend on nothing the
 // previous operator produces, so this runs before the dependency wait.
-__device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st)
+__device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st, bool ring, int npf)
 {
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
     uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb;
     uint32_t ulast = I.u0 + I.nu;  // one past the last unit
     uint32_t end = (ulast / I.S) * I.kbt + (ulast % I.S) * I.nkb;
     st.total = end - first;
+    if (ring) return;
     st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
     const uint32_t last = st.total ? st.total - 1 : 0;
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) {
+        if (j >= npf) continue;
         uint32_t idx = min((uint32_t)wave + (uint32_t)j * kWaves, last);
         st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)idx * 64);
     }
 }
 
 template <bool MFMA>
-__device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, const LdsPlan &lp, GemvStream &st, int batch)
+__device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, Wg &lp, GemvStream &st, int batch)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     const uint32_t rlog = instr_rlog(I), R = 1u << rlog, ck = chunk_k(rlog);
@@ -368,16 +440,16 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     auto flush = [&]() {
         if (!MFMA) {
             float v = (a0 + a1) + (a2 + a3);
-            // sum the 64 / R lanes that share a row
-            // lanes sharing a row differ in the lane bits >= rlog: in-row bits by DPP, the two row bits by permute
-            // (row rotations by 8, 4, 2, 1 sum the lanes of a 16-lane row that are congruent modulo R)
+            // Lanes sharing an output row differ in the lane bits >= rlog.  The bits inside a 16-lane
+            // row are summed with DPP row rotations (by 8, 4, 2, 1: lanes congruent modulo R); the
+            // four rows of the wave are NOT combined here -- each leaves its partial in its own slot
+            // of the reduction area and the final fixed-order sum adds the 16 (wave, row) slots.
+            // (A cross-row permute would stall the wave on the LDS crossbar at every unit.)
             if (R <= 8) v = dpp_add<0x128>(v);
             if (R <= 4) v = dpp_add<0x124>(v);
             if (R <= 2) v = dpp_add<0x122>(v);
             if (R <= 1) v = dpp_add<0x121>(v);
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
-            if ((uint32_t)lane < R) red[wave * red_per_wave + ul * R + lane] = v;
+            if ((uint32_t)(lane & 15) < R) red[(wave * 4 + (lane >> 4)) * red_per_wave + ul * R + (lane & 15)] = v;
             a0 = a1 = a2 = a3 = 0.f;
         } else {
             // cacc[j] = C[row 4*ksub + j][col lane & 15]; sum the nterm columns of each sequence
@@ -385,8 +457,9 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float v = cacc[j];
-                float v1 = __shfl_down(v, 1, 64);
-                float v2 = __shfl_down(v, 2, 64);
+                // the term columns of a sequence are neighbours inside the 16-lane row: DPP row shifts
+                float v1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x101, 0xf, 0xf, true));
+                float v2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x102, 0xf, 0xf, true));
                 float sum = v + v1 + (nterm == 3 ? v2 : 0.f);
                 int b = col / nterm;
                 if (col < ncols && col == b * nterm)
@@ -426,16 +499,50 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     };
 
     const uint32_t total = st.total;
-    if (total) {
+    if (lp.ring) {
+        // Weights come from the LDS page ring filled by the loader wave.  Chunk n of this
+        // workgroup's stream lives in slot n % ring_slots and belongs to consumer wave n & 3.
+        const uint32_t n0 = lp.chunk_n;                       // global index of the task's chunk 0
+        const uint32_t i0 = ((uint32_t)wave - n0) & 3u;       // first local index owned by this wave
+        kbi = i0;
+        lds_vptr landed = lds_word(lds, kSyncLanded);
+        lds_vptr hw = lds_word(lds, kSyncHw) + wave;
+        const char *ring = lds + lp.ring_off;
+        constexpr int U = 4;                                   // LDS reads in flight per lane
+        const uint32_t nslot = lp.ring_slots;
+        uint32_t slot = (n0 + i0) % nslot;                     // slot of this wave's next chunk (advances by 4, wraps)
+        for (uint32_t i = i0; i < total; i += U * kWaves) {
+            uint32_t last_i = i + (U - 1) * kWaves;
+            if (last_i >= total) last_i = i + ((total - 1 - i) / kWaves) * kWaves;
+            const uint32_t need = n0 + last_i + 1;            // published count that covers this group
+            if ((int32_t)(lp.landed_c - need) < 0) {
+                uint32_t it = 0;
+                do { lp.landed_c = *landed; } while ((int32_t)(lp.landed_c - need) < 0 && ++it < kLdsSpinLimit);
+            }
+            u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                w[u] = *(const u32x4 *)(ring + (size_t)slot * kChunkBytes + lane * 16);
+                if (i + (uint32_t)(u + 1) * kWaves < total) { slot += kWaves; if (slot >= nslot) slot -= nslot; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (i + (uint32_t)u * kWaves < total) consume(w[u]);
+            // the slots of this group may be refilled now
+            if (lane == 0) *hw = n0 + last_i + 1;
+        }
+    } else if (total) {
         const uint32_t last = total - 1;
-        for (uint32_t base = 0; base < total; base += kPrefetch * kWaves) {
+        const uint32_t round = (uint32_t)lp.npf * kWaves;
+        for (uint32_t base = 0; base < total; base += round) {
 #pragma unroll
             for (int j = 0; j < kPrefetch; ++j) {
+                if (j >= lp.npf) continue;
                 const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
                 if (idx < total) consume(st.buf[j]);
                 // refill the slot: always a load (clamped to the task's last chunk), so the slot's
                 // registers are written by exactly one instruction and nothing waits on it here
-                const uint32_t nidx = min(idx + kPrefetch * kWaves, last);
+                const uint32_t nidx = min(idx + round, last);
                 st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
             }
         }
@@ -445,7 +552,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         flush();
         ++ul;
     }
-    __syncthreads();
+    wg_sync(lp, lds);
 
     // cross-wave sum in fixed wave order, then the epilogue
     const ActBuf ab = act_buf(P);
@@ -453,8 +560,9 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     const uint32_t nb = (uint32_t)(MFMA ? batch : 1);
     auto rsum = [&](uint32_t t) {
         float v = red[t];
+        constexpr int kSlots = MFMA ? kWaves : kWaves * 4;   // VALU path: one slot per (wave, 16-lane row)
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) v += red[w * red_per_wave + t];
+        for (int w = 1; w < kSlots; ++w) v += red[w * red_per_wave + t];
         return v;
     };
     if (I.flags & F_SILU_EPI) {
@@ -487,6 +595,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     (void)ab;
 }
 
+// Task-internal trace mark k (0..3) of instruction pc; compiled to nothing unless tracing.
+__device__ __forceinline__ void trace_mark(const Params &P, uint32_t pc, int k)
+{
+    if ((P.flags & 1u) && threadIdx.x == 0 && P.only_seq == kNone)
+        ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 4 + k] = wall_clock64();
+}
+
 // ---------------------------------------------------------------- attention task
 // Flash-decode partial over the history positions owned by chunk task c of
 // (sequence b, kv head g): blocks c, c+nc, c+2nc, ... of `bs` positions.  All
@@ -516,11 +631,13 @@ __device__ __forceinline__ float safe_exp_diff(float a, float M)
     return (a == -INFINITY) ? 0.f : __expf(a - M);
 }
 
-// position (in the cache) of flattened index idx of task c
+// position (in the cache) of flattened index idx of task c; blocks are kAttBlock = 16 positions
+constexpr int kAttBlockLog = 4;
 __device__ __forceinline__ int att_pos(int idx, int bs, int nc, int c)
 {
-    int blk = idx / bs;
-    return (c + blk * nc) * bs + (idx - blk * bs);
+    (void)bs;
+    const int blk = idx >> kAttBlockLog;
+    return ((c + blk * nc) << kAttBlockLog) + (idx & ((1 << kAttBlockLog) - 1));
 }
 
 template <int D>
@@ -534,7 +651,7 @@ __device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, At
     if (b >= P.batch) return;
     const int p = position_of(P, b);
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
-    const int nblk_all = (p + bs - 1) / bs;                       // blocks containing positions < p
+    const int nblk_all = (p + bs - 1) >> kAttBlockLog;            // blocks containing positions < p
     const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
     st.p = p; st.npos = my_blocks * bs;
     const size_t head_elems = (size_t)P.max_context * D;
@@ -556,7 +673,7 @@ __device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, At
 }
 
 template <int D>
-__device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, const LdsPlan &lp, AttStream &as)
+__device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp, AttStream &as, uint32_t pc)
 {
     constexpr int LPP = D / 8;       // lanes per position (16 B each)
     constexpr int PPW = 64 / LPP;    // positions per wavefront load
@@ -574,28 +691,39 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     float *sq = (float *)(lds + lp.xs_off);              // [G][D] rotated, pre-scaled q
     float *snew = sq + kMaxGroup * D;                    // [2][D] new k (rotated, bf16-rounded) and v
     float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][D + 2]
-    const int jb_new = p / (int)I.bs;
+    const int jb_new = p >> kAttBlockLog;
     const bool owner = (jb_new % (int)I.nc) == (int)I.c;
 
     // ---- prologue: q heads (and new k / v) : sum partials, optional RMSNorm, RoPE
     const int nvec = G + (owner ? 2 : 0);
-    for (int vi = wave; vi < nvec; vi += kWaves) {
-        int row0;   // first row of this vector in the fused QKV output
-        uint32_t gain_off = kNone;
-        bool rot = true;
-        if (vi < G) { row0 = (g * G + vi) * D; gain_off = I.qn_gain; }
-        else if (vi == G) { row0 = qd + g * D; gain_off = I.kn_gain; }
-        else { row0 = qd + kvd + g * D; rot = false; }
-        const int i = lane;   // pair index (i, i + D/2)
-        float a = 0.f, c2 = 0.f;
-        if (i < D / 2) {
+    // Each wave owns vectors wave, wave+4, wave+8 (q heads, then new k, then new v).  All their
+    // loads are issued before any is used, so the prologue costs one memory round trip.
+    constexpr int kRounds = (kMaxGroup + 2 + kWaves - 1) / kWaves;
+    float pa[kRounds], pb[kRounds];
+    const int i = lane;   // pair index (i, i + D/2)
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int vi = wave + r * kWaves;
+        pa[r] = 0.f; pb[r] = 0.f;
+        if (vi < nvec && i < D / 2) {
+            const int row0 = vi < G ? (g * G + vi) * D : (vi == G ? qd + g * D : qd + kvd + g * D);
             for (uint32_t s = 0; s < I.n_parts; ++s) {
                 const float *pp = act + I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld + row0;
                 float u0 = ld_act(pp + i), u1 = ld_act(pp + i + D / 2);
-                a += u0;
-                c2 += u1;
+                pa[r] += u0;
+                pb[r] += u1;
             }
         }
+    }
+    float cs = 0.f, sn = 0.f;
+    if (i < D / 2) { cs = rope[2 * i]; sn = rope[2 * i + 1]; }
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int vi = wave + r * kWaves;
+        if (vi >= nvec) continue;
+        const bool rot = vi <= G;
+        const uint32_t gain_off = vi < G ? I.qn_gain : I.kn_gain;
+        float a = pa[r], c2 = pb[r];
         if (rot) {
             if (P.qk_norm && gain_off != kNone) {
                 float ss = wave_sum(a * a + c2 * c2);
@@ -605,12 +733,9 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                     c2 = c2 * inv * bf_to_f(vecs[gain_off + i + D / 2]);
                 }
             }
-            if (i < D / 2) {
-                float cs = rope[2 * i], sn = rope[2 * i + 1];
-                float ra = a * cs - c2 * sn;
-                float rb = c2 * cs + a * sn;
-                a = ra; c2 = rb;
-            }
+            float ra = a * cs - c2 * sn;
+            float rb = c2 * cs + a * sn;
+            a = ra; c2 = rb;
         }
         if (i < D / 2) {
             if (vi < G) {
@@ -629,19 +754,11 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
             }
         }
     }
-    __syncthreads();
+    wg_sync(lp, lds);
+    trace_mark(P, pc, 0);
 
     // ---- main loop over this task's history positions (t < p)
     const int sub = as.sub, dl = lane % LPP;   // position inside the load, 8-dim slice
-    float qr[kMaxGroup][8];
-#pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h)
-        if (h < G) {
-            const f32x4 *qp = (const f32x4 *)(sq + h * D + dl * 8);
-            f32x4 q0 = qp[0], q1 = qp[1];
-            qr[h][0] = q0.x; qr[h][1] = q0.y; qr[h][2] = q0.z; qr[h][3] = q0.w;
-            qr[h][4] = q1.x; qr[h][5] = q1.y; qr[h][6] = q1.z; qr[h][7] = q1.w;
-        }
     AttState st;
 #pragma unroll
     for (int h = 0; h < kMaxGroup; ++h) {
@@ -652,42 +769,67 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
     const int npos = as.npos;
 
-    auto step = [&](const u32x4 &kw, const u32x4 &vw, bool valid) {
-        float kf[8] = {bf_lo(kw.x), bf_hi(kw.x), bf_lo(kw.y), bf_hi(kw.y), bf_lo(kw.z), bf_hi(kw.z), bf_lo(kw.w), bf_hi(kw.w)};
-        float vf[8] = {bf_lo(vw.x), bf_hi(vw.x), bf_lo(vw.y), bf_hi(vw.y), bf_lo(vw.z), bf_hi(vw.z), bf_lo(vw.w), bf_hi(vw.w)};
+    // Online softmax over batches of three positions per lane group: one running-max update and one
+    // rescale of the accumulators per batch instead of per position (wave64 VALU ops cost four
+    // cycles each, and this loop is VALU-bound).
+    auto batch3 = [&](const u32x4 &k0, const u32x4 &v0, bool ok0, const u32x4 &k1, const u32x4 &v1, bool ok1,
+                      const u32x4 &k2, const u32x4 &v2, bool ok2) {
+        const u32x4 kw[3] = {k0, k1, k2};
+        const u32x4 vw[3] = {v0, v1, v2};
+        const bool ok[3] = {ok0, ok1, ok2};
+        float vf[3][8];
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            vf[u][0] = bf_lo(vw[u].x); vf[u][1] = bf_hi(vw[u].x); vf[u][2] = bf_lo(vw[u].y); vf[u][3] = bf_hi(vw[u].y);
+            vf[u][4] = bf_lo(vw[u].z); vf[u][5] = bf_hi(vw[u].z); vf[u][6] = bf_lo(vw[u].w); vf[u][7] = bf_hi(vw[u].w);
+        }
 #pragma unroll
         for (int h = 0; h < kMaxGroup; ++h)
             if (h < G) {
-                float s = 0.f;
+                // q stays in LDS (all lanes of a position group read the same 32 bytes: broadcast)
+                const f32x4 *qp = (const f32x4 *)(sq + h * D + dl * 8);
+                const f32x4 q0 = qp[0], q1 = qp[1];
+                float sc3[3];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) s += qr[h][j] * kf[j];
-                s = (LPP == 16) ? row_sum16(s) : row_sum8(s);
-                if (valid) {
-                    float mn = fmaxf(st.m[h], s);
-                    float sc = safe_exp_diff(st.m[h], mn);
-                    float pe = __expf(s - mn);
-                    st.l[h] = st.l[h] * sc + pe;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) st.acc[h][j] = st.acc[h][j] * sc + pe * vf[j];
-                    st.m[h] = mn;
+                for (int u = 0; u < 3; ++u) {
+                    float d = q0.x * bf_lo(kw[u].x) + q0.y * bf_hi(kw[u].x) + q0.z * bf_lo(kw[u].y) + q0.w * bf_hi(kw[u].y) +
+                              q1.x * bf_lo(kw[u].z) + q1.y * bf_hi(kw[u].z) + q1.z * bf_lo(kw[u].w) + q1.w * bf_hi(kw[u].w);
+                    d = (LPP == 16) ? row_sum16(d) : row_sum8(d);
+                    sc3[u] = ok[u] ? d : -INFINITY;
                 }
+                const float mn = fmaxf(fmaxf(st.m[h], sc3[0]), fmaxf(sc3[1], sc3[2]));
+                const float rs = safe_exp_diff(st.m[h], mn);
+                const float p0 = safe_exp_diff(sc3[0], mn), p1 = safe_exp_diff(sc3[1], mn), p2 = safe_exp_diff(sc3[2], mn);
+                st.l[h] = st.l[h] * rs + (p0 + p1 + p2);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    st.acc[h][j] = st.acc[h][j] * rs + (p0 * vf[0][j] + p1 * vf[1][j] + p2 * vf[2][j]);
+                st.m[h] = mn;
             }
     };
+    static_assert(kAttPrefetch % 3 == 0, "the prefetch slots are consumed three at a time");
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     for (int base = 0; base * PPW < npos; base += kAttPrefetch * kWaves) {
 #pragma unroll
-        for (int j = 0; j < kAttPrefetch; ++j) {
-            const int grp = (base + wave + j * kWaves) * PPW;
-            if (grp < npos) {
-                const int t = att_pos(grp + sub, bs, nc, c);
-                step(as.kbuf[j], as.vbuf[j], t < p);
+        for (int j0 = 0; j0 < kAttPrefetch; j0 += 3) {
+            bool ok[3];
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int grp = (base + wave + (j0 + u) * kWaves) * PPW;
+                ok[u] = grp < npos && att_pos(grp + sub, bs, nc, c) < p;
             }
-            const int ngrp = grp + kAttPrefetch * kWaves * PPW;
-            if (ngrp < npos) {
-                int t = att_pos(ngrp + sub, bs, nc, c);
-                t = t < P.max_context ? t : P.max_context - 1;
-                as.kbuf[j] = __builtin_nontemporal_load(as.kp + (size_t)t * LPP);
-                as.vbuf[j] = __builtin_nontemporal_load(as.vp + (size_t)t * LPP);
+            if ((base + wave + j0 * kWaves) * PPW < npos)
+                batch3(as.kbuf[j0], as.vbuf[j0], ok[0], as.kbuf[j0 + 1], as.vbuf[j0 + 1], ok[1], as.kbuf[j0 + 2], as.vbuf[j0 + 2], ok[2]);
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int ngrp = (base + wave + (j0 + u) * kWaves) * PPW + kAttPrefetch * kWaves * PPW;
+                if (ngrp < npos) {
+                    int t = att_pos(ngrp + sub, bs, nc, c);
+                    t = t < P.max_context ? t : P.max_context - 1;
+                    as.kbuf[j0 + u] = __builtin_nontemporal_load(as.kp + (size_t)t * LPP);
+                    as.vbuf[j0 + u] = __builtin_nontemporal_load(as.vp + (size_t)t * LPP);
+                }
             }
         }
     }
@@ -703,9 +845,10 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         vw.y = (uint32_t)f_to_bf(vn[2]) | ((uint32_t)f_to_bf(vn[3]) << 16);
         vw.z = (uint32_t)f_to_bf(vn[4]) | ((uint32_t)f_to_bf(vn[5]) << 16);
         vw.w = (uint32_t)f_to_bf(vn[6]) | ((uint32_t)f_to_bf(vn[7]) << 16);
-        step(kw, vw, sub == 0);
+        batch3(kw, vw, sub == 0, zero4, zero4, false, zero4, zero4, false);
     }
 
+    trace_mark(P, pc, 1);
     // ---- every (wave, position slot) leaves its running state in LDS; merged below in fixed order
     constexpr int NSLOT = kWaves * PPW;
     {
@@ -721,19 +864,30 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                 if (dl == 0) { dst[D] = st.m[h]; dst[D + 1] = st.l[h]; }
             }
     }
-    __syncthreads();
+    wg_sync(lp, lds);
+    trace_mark(P, pc, 2);
 
+    // merged max, denominators and per-slot weights of every head, computed once per (head, slot)
+    float *sfac = smerge + (size_t)NSLOT * G * (D + 2);     // [G][NSLOT] weights, then [G] max, [G] denominators
+    if (tid < G * NSLOT) {
+        const int h = tid / NSLOT, w = tid % NSLOT;
+        float M = -INFINITY;
+#pragma unroll
+        for (int x = 0; x < NSLOT; ++x) M = fmaxf(M, smerge[((size_t)x * G + h) * (D + 2) + D]);
+        const float *src = smerge + ((size_t)w * G + h) * (D + 2);
+        sfac[h * NSLOT + w] = safe_exp_diff(src[D], M);
+        if (w == 0) sfac[G * NSLOT + h] = M;
+    }
+    wg_sync(lp, lds);
     float *outp = (float *)(P.ws + P.lay.act) + I.out;
     for (int e = tid; e < G * D; e += kWgThreads) {
         int h = e / D, i = e % D;
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < NSLOT; ++w) M = fmaxf(M, smerge[((size_t)w * G + h) * (D + 2) + D]);
+        const float M = sfac[G * NSLOT + h];
         float L = 0.f, A = 0.f;
 #pragma unroll
         for (int w = 0; w < NSLOT; ++w) {
             const float *src = smerge + ((size_t)w * G + h) * (D + 2);
-            float f = safe_exp_diff(src[D], M);
+            const float f = sfac[h * NSLOT + w];
             L += src[D + 1] * f;
             A += src[i] * f;
         }
@@ -746,7 +900,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 
 // Combine the nc flash-decode partials of q heads h0 .. h0+nh of sequence b: the partial rows
 // are copied to LDS with all their 128-bit loads in flight together, then reduced in fixed order.
-__device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, char *lds, const LdsPlan &lp)
+__device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp)
 {
     const int b = (int)I.b;
     if (b >= P.batch) return;
@@ -758,7 +912,7 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
         const int h = (int)I.h0 + hh;
         const uint32_t src = I.out + (uint32_t)(((size_t)b * P.n_q_heads + h) * nc) * (uint32_t)RS;
         const int nq4 = nc * RS / 4;
-        if (hh) __syncthreads();
+        if (hh) wg_sync(lp, lds);
         for (int q0 = threadIdx.x; q0 < nq4; q0 += kWgThreads * 4) {
             f32x4 v[4];
 #pragma unroll
@@ -772,11 +926,13 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
                 if (q < nq4) *(f32x4 *)(stage + 4 * q) = v[u];
             }
         }
-        __syncthreads();
+        wg_sync(lp, lds);
         for (int i = threadIdx.x; i < D; i += kWgThreads) {
             float M = -INFINITY;
+#pragma unroll 8
             for (int c = 0; c < nc; ++c) M = fmaxf(M, stage[c * RS + D]);
             float L = 0.f, A = 0.f;
+#pragma unroll 8
             for (int c = 0; c < nc; ++c) {
                 const float *s = stage + c * RS;
                 float f = safe_exp_diff(s[D], M);
@@ -796,8 +952,8 @@ __device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, u
 
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
 template <bool PERSISTENT>
-__device__ __forceinline__ void exec_instr(const Params &P, const LdsPlan &lp, char *lds, const Instr &I, uint32_t pc,
-                                           bool &dead)
+__device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
+                                           bool &dead, uint32_t nxt = 0)
 {
     const int tid = threadIdx.x;
     uint32_t *sflag = (uint32_t *)(lds + kLdsMisc + 128);
@@ -808,26 +964,28 @@ __device__ __forceinline__ void exec_instr(const Params &P, const LdsPlan &lp, c
 
     GemvStream st;
     AttStream as;
-    if (I.op == OP_GEMV) gemv_issue(P, I, st);
+    if (I.op == OP_GEMV) gemv_issue(P, I, st, lp.ring, lp.npf);
     else if (I.op == OP_ATT) {
         if (P.head_dim == 128) att_issue<128>(P, *(const InstrAtt *)&I, as);
         else att_issue<64>(P, *(const InstrAtt *)&I, as);
     }
 
+    if (PERSISTENT && I.op == OP_GEMV) trace_mark(P, pc, 0);
     if (PERSISTENT) {
         if (tid == 0) {
             uint32_t ok = 1;
-            if (!dead) {
+            if (!dead && !(P.dbg & 1u)) {
 #pragma unroll
                 for (int k = 0; k < 2; ++k)
                     if (ok && I.wait_ctr[k] != kNone)
-                        ok = wait_counter(counters + (size_t)I.wait_ctr[k] * kCounterStride,
-                                          P.epoch * I.wait_cnt[k], P.spin_limit) ? 1u : 0u;
+                        ok = wait_counter(counters + (size_t)I.wait_ctr[k] * P.ctr_stride,
+                                          P.epoch * I.wait_cnt[k], P.spin_limit, P.poll_sleep) ? 1u : 0u;
             }
             if (!ok) set_err(P, 0, 1u + pc);
             sflag[0] = ok;
+            if (I.op == OP_GEMV) trace_mark(P, pc, 1);
         }
-        __syncthreads();
+        wg_sync(lp, lds);
         if (sflag[0] == 0) dead = true;
     }
     if (tracing && tid == 0) t1 = wall_clock64();
@@ -843,10 +1001,11 @@ __device__ __forceinline__ void exec_instr(const Params &P, const LdsPlan &lp, c
             if (tracing && tid == 0) t2 = wall_clock64();
             gemv_main<false>(P, I, lds, lp, st, 1);
         }
+        lp.chunk_n += st.total;
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
-        if (P.head_dim == 128) att_task<128>(P, A, lds, lp, as);
-        else att_task<64>(P, A, lds, lp, as);
+        if (P.head_dim == 128) att_task<128>(P, A, lds, lp, as, pc);
+        else att_task<64>(P, A, lds, lp, as, pc);
     } else if (I.op == OP_COMB) {
         comb_task(P, *(const InstrAtt *)&I, lds, lp);
     }
@@ -854,14 +1013,14 @@ __device__ __forceinline__ void exec_instr(const Params &P, const LdsPlan &lp, c
     if (PERSISTENT && I.sig_ctr != kNone) {
         // each wave drains its write-through stores, the barrier collects all waves, then one
         // thread publishes the task with the counter increment
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        if (!(P.dbg & 2u)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        wg_sync(lp, lds);
         if (tid == 0)
-            __hip_atomic_fetch_add((uint32_t *)counters + (size_t)I.sig_ctr * kCounterStride, 1u, __ATOMIC_RELAXED,
+            __hip_atomic_fetch_add((uint32_t *)counters + (size_t)I.sig_ctr * P.ctr_stride, 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tracing && tid == 0) {
-        uint64_t *r = (uint64_t *)(P.ws + P.lay.trace) + ((size_t)blockIdx.x * P.max_instr + pc) * 4;
+        uint64_t *r = (uint64_t *)(P.ws + P.lay.trace) + ((size_t)blockIdx.x * P.max_instr + pc) * 8;
         r[0] = t0; r[1] = t1; r[2] = t2 ? t2 : t1; r[3] = wall_clock64();
     }
 }
@@ -873,49 +1032,171 @@ __device__ __forceinline__ void read_instr(const uint32_t *slot, Instr &I)
     for (int j = 0; j < kInstrDwords; ++j) dst[j] = rfl(slot[j]);
 }
 
+__device__ __forceinline__ Wg make_wg(const LdsPlan &p, bool ring, int npf = kPrefetch)
+{
+    Wg wg;
+    wg.red_bytes = p.red_bytes; wg.xs_off = p.xs_off; wg.ring_off = p.ring_off; wg.ring_slots = p.ring_slots;
+    wg.ring = ring; wg.bar_target = 0; wg.chunk_n = 0; wg.landed_c = 0; wg.npf = npf;
+    return wg;
+}
+
+// ---- loader wave (ring kernel) --------------------------------------------------------------
+// Streams the weight chunks of every GEMV task of this workgroup, in list order, into the LDS
+// page ring with 128-bit global->LDS DMA loads.  It runs ahead of the consumers by up to the
+// ring capacity, across task and operator boundaries: weights depend on nothing (paper
+// Sec. 4.2.3), so HBM streaming continues while the consumers wait on dependency counters.
+// Page states (Sec. 4.2.2 Step 3): a slot is Locked from the DMA issue until the loader has
+// seen it land (vmcnt) and published it, Ready until its consumer wave moves its high-water
+// mark past it, then Empty again.  LDS sync words are accessed with inline asm so that the
+// compiler does not serialise them against the DMA queue.
+__device__ __forceinline__ uint32_t lds_ld_u32(uint32_t addr)
+{
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ void lds_st_u32(uint32_t addr, uint32_t v)
+{
+    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_min4(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return min(min(v.x, v.y), min(v.z, v.w));
+}
+
+constexpr int kDmaDepth = 56;   // DMA loads the loader keeps in flight (vmcnt is 6 bits)
+
+// s_waitcnt vmcnt(k) needs an immediate: wait until at most 4 * (k4) loads are outstanding
+__device__ __forceinline__ void vm_wait4(uint32_t k4)
+{
+    switch (k4) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+    case 7: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+    case 8: asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); break;
+    case 9: asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); break;
+    case 10: asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); break;
+    case 11: asm volatile("s_waitcnt vmcnt(44)" ::: "memory"); break;
+    case 12: asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); break;
+    case 13: asm volatile("s_waitcnt vmcnt(52)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(56)" ::: "memory"); break;
+    }
+}
+
+__device__ __forceinline__ void loader_wave(const Params &P, const LdsPlan &lp, char *lds)
+{
+    typedef const __attribute__((address_space(4))) uint32_t *cptr;      // instruction lists never change during a launch
+    typedef const __attribute__((address_space(1))) void *gptr;
+    typedef __attribute__((address_space(3))) void *lptr;
+    const uint32_t lane = threadIdx.x & 63;
+    cptr list = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr)lds;
+    const uint32_t nslot = lp.ring_slots;
+    const char *wbase = P.ws + P.lay.weights;
+    uint32_t n = 0, pub = 0, slot = 0, hw_min = 0;
+    for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
+        const uint32_t op = list[(size_t)pc * kInstrDwords + 0];
+        if (op == OP_END) break;
+        if (op != OP_GEMV) continue;
+        const uint32_t w_chunk = list[(size_t)pc * kInstrDwords + 9], kbt = list[(size_t)pc * kInstrDwords + 10],
+                       nkb = list[(size_t)pc * kInstrDwords + 11], S = list[(size_t)pc * kInstrDwords + 12],
+                       u0 = list[(size_t)pc * kInstrDwords + 13], nu = list[(size_t)pc * kInstrDwords + 14];
+        const uint32_t first = (u0 / S) * kbt + (u0 % S) * nkb, ue = u0 + nu;
+        const uint32_t total = (ue / S) * kbt + (ue % S) * nkb - first;
+        const char *src = wbase + ((size_t)w_chunk + first) * kChunkBytes + lane * 16;
+        for (uint32_t i = 0; i < total; ++i) {
+            if (n >= nslot && (int32_t)(hw_min - (n - nslot + 1)) < 0) {
+                // ring full: publish what lands, four chunks at a time, until a consumer frees the slot
+                uint32_t it = 0;
+                do {
+                    const uint32_t out = n - pub;
+                    if (out) {
+                        const uint32_t k4 = out > 4 ? (out - 1) >> 2 : 0;   // leave at most 4*k4 < out outstanding
+                        vm_wait4(k4);
+                        pub = n - min(out, k4 * 4);
+                        lds_st_u32(lds0 + kSyncLanded, pub);
+                    }
+                    hw_min = lds_min4(lds0 + kSyncHw);
+                } while ((int32_t)(hw_min - (n - nslot + 1)) < 0 && ++it < kLdsSpinLimit);
+                if (it >= kLdsSpinLimit) set_err(P, 2, 1u);
+            }
+            __builtin_amdgcn_global_load_lds((gptr)(uintptr_t)(src + (size_t)i * kChunkBytes),
+                                             (lptr)(lds + lp.ring_off + (size_t)slot * kChunkBytes), 16, 0, 2 /* nt */);
+            ++n;
+            if (++slot == nslot) slot = 0;
+            if (n - pub > (uint32_t)kDmaDepth) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaDepth) : "memory");
+                pub = n - kDmaDepth;
+                lds_st_u32(lds0 + kSyncLanded, pub);
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_st_u32(lds0 + kSyncLanded, n);
+}
+
 // Persistent walk of this workgroup's whole list; the next instruction is fetched while the
 // current one runs.
-__device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan lp)
+template <bool RING, int NPF>
+__device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    Wg lp = make_wg(plan, RING, NPF);
+    if (RING) {
+        // LDS is not cleared between launches: reset the sync words before any role starts
+        if (threadIdx.x < 16) ((uint32_t *)(lds + kSyncLanded))[threadIdx.x] = 0u;
+        __syncthreads();                       // the only hardware barrier all five waves share
+        if (threadIdx.x >= kWgThreads) {
+            loader_wave(P, plan, lds);
+            return;
+        }
+    }
     const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
     uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);   // two slots of 32 dwords
     bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
     fetch_instr(list, 0, sinstr);
     for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
-        __syncthreads();
+        wg_sync(lp, lds);
         Instr I;
         read_instr(sinstr + (pc & 1u) * kInstrDwords, I);
         if (I.op == OP_END) break;
         uint32_t nxt = 0;
         const bool more = pc + 1 < P.max_instr;
         if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
-        exec_instr<true>(P, lp, lds, I, pc, dead);
+        exec_instr<true>(P, lp, lds, I, pc, dead, nxt);
         if (more && threadIdx.x < kInstrDwords) sinstr[((pc + 1) & 1u) * kInstrDwords + threadIdx.x] = nxt;
     }
 }
 
 // One operator instance: the instructions of this workgroup whose ref_seq matches (they are
 // adjacent in the list), found with one parallel scan.
-__device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan lp)
+__device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    Wg lp = make_wg(plan, false);
     const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
     uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);
     uint32_t *srange = (uint32_t *)(lds + kLdsMisc + 160);   // [0] first match, [1] match count
     if (threadIdx.x == 0) { srange[0] = 0xffffffffu; srange[1] = 0u; }
-    __syncthreads();
+    wg_sync(lp, lds);
     for (uint32_t i = threadIdx.x; i < P.max_instr; i += kWgThreads) {
         uint32_t op = list[(size_t)i * kInstrDwords], seq = list[(size_t)i * kInstrDwords + 2];
         if (op != OP_END && seq == P.only_seq) { atomicMin(srange, i); atomicAdd(srange + 1, 1u); }
     }
-    __syncthreads();
+    wg_sync(lp, lds);
     const uint32_t first = srange[0], n = srange[1];
     bool dead = false;
     for (uint32_t pc = first; pc < first + n && n; ++pc) {
-        __syncthreads();
+        wg_sync(lp, lds);
         fetch_instr(list, pc, sinstr);
-        __syncthreads();
+        wg_sync(lp, lds);
         Instr I;
         read_instr(sinstr, I);
         exec_instr<false>(P, lp, lds, I, pc, dead);
@@ -925,7 +1206,16 @@ __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan lp)
 }  // namespace mk
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent(P, lp); }
+mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, mk::kPrefetch>(P, lp); }
+
+// Two workgroups per CU (two waves per SIMD, at most 256 VGPRs each, half the prefetch depth per
+// wave): one workgroup's dependency latency overlaps the other's streaming.
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads, 2)
+mk_megakernel_x2(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, mk::kPrefetch / 2>(P, lp); }
+
+// Ring variant: four consumer waves plus one loader wave per workgroup.
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads + 64)
+mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true, mk::kPrefetch>(P, lp); }
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
 mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op(P, lp); }

@@ -143,7 +143,7 @@ struct LdsBudget {
 
 static uint32_t att_scratch_bytes(const Dims &d)
 {
-    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 2)) * 4u;   // q, new k/v, per-slot merge
+    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 2 + 1) + 2 * kMaxGroup) * 4u;   // q, new k/v, per-slot merge, merge weights
 }
 
 static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
@@ -158,13 +158,15 @@ static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
 // straight into registers and the whole remainder is available to activations.
 static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
 {
-    b.cap_outs = 1024;
-    b.red_bytes = (uint32_t)(kWaves * b.cap_outs * 4);
+    // reduction area: one slot per wave (matrix-core path) or per (wave, 16-lane row) (VALU path)
+    b.cap_outs = t.mfma ? 1024 : 256;
+    b.red_bytes = (uint32_t)(kWaves * (t.mfma ? 1 : 4) * b.cap_outs * 4);
     const int64_t fixed = kLdsRed + b.red_bytes;
+    // pages are the 1 KB chunk slots of the ring; a pipeline stage is 16 of them
     const int64_t pages_total = pages_available(kLdsMax, 1, kLdsMisc - kLdsInstr, kLdsRed - kLdsMisc, b.red_bytes, t.page_bytes);
     const int64_t need = std::max<int64_t>(att_scratch_bytes(d), norm_stage_bytes(d, t));
     const int64_t pages_act = (need + t.page_bytes - 1) / t.page_bytes;
-    if (t.ring_pages > 0 && pipeline_stages(pages_total, t.ring_pages, 0, pages_act, 1) < 1) return false;
+    if (t.ring_pages > 0 && pipeline_stages(pages_total, 0, 0, pages_act, 16) * 16 < t.ring_pages) return false;
     const int64_t left = kLdsMax - fixed - (int64_t)t.ring_pages * t.page_bytes;
     if (left < need) return false;
     b.xs_cap = (uint32_t)left;
@@ -542,8 +544,11 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     s->ref_seqs = seqs;
     s->lds_red_bytes = b.lb.red_bytes;
     s->lds_xs_off = kLdsRed + b.lb.red_bytes;
-    s->lds_total = (uint32_t)align_up(s->lds_xs_off + b.max_xs_bytes, 256);
-    if (s->lds_total + (uint64_t)t.ring_pages * t.page_bytes > (uint64_t)kLdsMax) return MK_EINFEASIBLE;
+    s->lds_ring_off = (uint32_t)align_up(s->lds_xs_off + b.max_xs_bytes, 1024);
+    s->lds_ring_slots = (uint32_t)((uint64_t)t.ring_pages * t.page_bytes / kChunkBytes);
+    s->lds_total = t.ring_pages ? s->lds_ring_off + s->lds_ring_slots * kChunkBytes
+                                : (uint32_t)align_up(s->lds_xs_off + b.max_xs_bytes, 256);
+    if (s->lds_total > (uint64_t)kLdsMax) return MK_EINFEASIBLE;
     // workspace layout
     Layout &L = s->lay;
     uint64_t off = 0;
@@ -551,10 +556,10 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     L.vecs = off; off = align_up(off + s->wm.n_vec * 2, 4096);
     L.rope = off; off = align_up(off + (uint64_t)d.Tm * d.d * 4, 4096);
     L.act = off; off = align_up(off + s->am.n_floats * 4, 4096);
-    L.counters = off; off = align_up(off + (uint64_t)s->n_counters * kCounterStride * 4, 4096);
+    L.counters = off; off = align_up(off + (uint64_t)s->n_counters * kCounterStrideMax * 4, 4096);
     L.instr = off; off = align_up(off + s->instr.size() * 4, 4096);
     L.err = off; off = align_up(off + 64, 4096);
-    L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 32 : 0), 4096);
+    L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 64 : 0), 4096);
     L.total = off;
     s->sim = simulate(s);
     return MK_OK;
@@ -569,7 +574,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     if (rc) return rc;
     const int mfma = cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
     if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
-    if (cfg.ring_kb > 0) { set_error("mk_config: ring_kb > 0 is not available in this build"); return MK_EINVAL; }
+    if (cfg.ring_kb > 0 && (cfg.ring_kb < 32 || cfg.ring_kb > 144)) { set_error("mk_config: ring_kb must be 0 (no ring) or 32..144"); return MK_EINVAL; }
 
     for (int v : {cfg.split_qkv, cfg.split_o, cfg.split_gateup, cfg.split_down, cfg.attn_chunks})
         if (v < 0) { set_error("mk_config: negative split / chunk count"); return MK_EINVAL; }
@@ -589,7 +594,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     std::vector<int> c_nc;
     if (cfg.attn_chunks > 0) c_nc.push_back(cfg.attn_chunks);
     else
-        for (int nc = 1; nc <= 64; nc *= 2) {
+        for (int nc = 1; nc <= 64; nc *= 2) {   // (the combine task stages nc partial rows in LDS)
             if ((int64_t)d.Bm * d.nkv * nc > 2 * (int64_t)cfg.n_workgroups && nc > 1) break;
             c_nc.push_back(nc);
         }
@@ -611,7 +616,9 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     best.s_qkv = c_sqkv[0]; best.s_o = c_so[0]; best.s_gu = c_sgu[0]; best.s_d = c_sd[0];
     best.r_qkv = best.r_o = best.r_gu = best.r_d = c_r[0]; best.r_head = cfg.chunk_rows ? c_r[0] : 4;
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
-    best.ring_pages = 0; best.page_bytes = 16 * 1024; best.n_stage = 1;
+    best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
+    best.ring_pages = cfg.ring_kb > 0 ? cfg.ring_kb / 16 * 16 : 0;
+    best.n_stage = best.ring_pages ? best.ring_pages / 16 : 1;
     int tried = 0, pruned = 0;
     double best_ms = -1, best_duty = 0;
     auto eval = [&](const Tiling &t, double &ms, double &duty) {

@@ -64,7 +64,7 @@ struct mk_schedule {
     mk::WeightMap wm;
     mk::ActMap am;
     mk::Layout lay;
-    uint32_t lds_red_bytes, lds_xs_off, lds_total;
+    uint32_t lds_red_bytes, lds_xs_off, lds_total, lds_ring_off, lds_ring_slots;
     int n_wg, max_instr, n_counters, n_tasks;
     std::vector<uint32_t> instr;          // [n_wg][max_instr][32]
     std::vector<uint32_t> ref_seqs;       // distinct operator-instance ranks in topological order
@@ -74,7 +74,7 @@ struct mk_schedule {
     char *ws;
     size_t ws_bytes;
     int device;
-    bool bound, loaded;
+    bool bound, loaded, two_per_cu;
     uint32_t epoch;
     void *ev0, *ev1;
     bool ev_valid;

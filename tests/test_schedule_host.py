@@ -92,7 +92,7 @@ def test_fixed_tiling_overrides_are_honoured():
 
 @pytest.mark.parametrize("bad", [dict(head_dim=8), dict(hidden=100), dict(max_batch=9), dict(max_batch=0),
                                  dict(n_q_heads=3), dict(n_layers=0), dict(max_context=0),
-                                 dict(max_batch=2, use_mfma=0), dict(ring_kb=64), dict(split_down=10 ** 6)])
+                                 dict(max_batch=2, use_mfma=0), dict(ring_kb=200), dict(split_down=10 ** 6)])
 def test_bad_configs_are_rejected(bad):
     cfg = synth.model_cfg(synth.CONFIGS["c0_tiny"])
     opts = {k: bad.pop(k) for k in list(bad) if k in ("use_mfma", "ring_kb", "split_down")}
