@@ -59,7 +59,10 @@ typedef struct mk_config {
     int32_t n_workgroups;    /* persistent grid size; 0 = one per CU of device_id    */
     int32_t device_id;       /* only read when n_workgroups == 0 or at bind time     */
     int32_t use_mfma;        /* -1 auto (batch>1 -> MFMA), 0 VALU GEMV, 1 MFMA GEMV  */
-    int32_t ring_kb;         /* LDS weight-page ring in KB; 0 = no ring (direct loads), -1 = auto */
+    int32_t ring_kb;         /* LDS weight-page ring in KB (16..144, rounded down to 16): each wavefront streams its
+                              * share of the workgroup's weights through its quarter of the ring, ahead of the
+                              * consumer and across task boundaries; 0 = no ring (weights go straight to registers);
+                              * -1 = auto (currently 0: the direct path measures faster); -2 = let the search pick   */
     int32_t split_qkv, split_o, split_gateup, split_down; /* K splits; 0 = search    */
     int32_t attn_chunks;     /* attention tasks per (sequence, KV head); 0 = search  */
     int32_t chunk_rows;      /* rows per 1 KB weight chunk for every matrix (2,4,8,16); 0 = search per matrix */
@@ -171,7 +174,8 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *token_ids, const int32_
                           void *kv_cache, float *logits_out, int32_t batch, void *stream);
 
 /* Synchronises `stream` and reports the kernel's sticky error flag:
- * MK_OK, MK_ETIMEOUT (a wait hit spin_limit) or MK_EINVAL (bad token/position).
+ * MK_OK, MK_ETIMEOUT (a wait hit spin_limit), MK_EINVAL (bad token/position) or
+ * MK_ESCHED (the weight-page ring ran dry, i.e. corrupted instruction lists).
  * Clears the flag and re-arms the counters when an error was found. */
 int mk_check(mk_schedule *s, void *stream);
 

@@ -114,7 +114,7 @@ def _chk(rc: int) -> None:
         raise MkError(rc, mk_last_error())
 
 
-_CFG_DEFAULTS = dict(n_workgroups=0, device_id=0, use_mfma=-1, ring_kb=0, split_qkv=0, split_o=0, split_gateup=0,
+_CFG_DEFAULTS = dict(n_workgroups=0, device_id=0, use_mfma=-1, ring_kb=-1, split_qkv=0, split_o=0, split_gateup=0,
                      split_down=0, attn_chunks=0, chunk_rows=0, spin_limit=0, flags=0)
 
 

@@ -31,7 +31,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     dobj = os.path.join(CSRC, "mk_api.o")
     dev = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-c",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-result", os.path.join(CSRC, "mk_api.hip"), "-o", dobj]
+           "-Wno-unused-result", "-Wno-inline-asm", os.path.join(CSRC, "mk_api.hip"), "-o", dobj]
     link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", dobj, obj, "-o", LIB]
     for cmd in (host, dev, link):
         if verbose:

@@ -202,13 +202,9 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_x2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     int per_cu = 0;
-    s->two_per_cu = !s->tl.ring_pages && s->n_wg > prop.multiProcessorCount;
-    if (s->two_per_cu)
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_x2, mk::kWgThreads, s->lds_total));
-    else if (s->tl.ring_pages)
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_ring, mk::kWgThreads + 64, s->lds_total));
+    if (s->tl.ring_pages)
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_ring, mk::kWgThreads, s->lds_total));
     else
         HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel, mk::kWgThreads, s->lds_total));
     if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
@@ -220,6 +216,23 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     s->ws = (char *)dev; s->ws_bytes = bytes;
     // instruction lists
     HIP_TRY(hipMemcpyAsync(s->ws + s->lay.instr, s->instr.data(), s->instr.size() * 4, hipMemcpyHostToDevice, st));
+    // weight stream of every workgroup: (first chunk, chunk count) of its GEMV tasks in list order
+    std::vector<uint32_t> wstream((size_t)s->n_wg * s->max_instr * 2, mk::kNone);
+    for (int w = 0; w < s->n_wg; ++w) {
+        const mk::Instr *l = (const mk::Instr *)s->instr.data() + (size_t)w * s->max_instr;
+        uint32_t *dst = wstream.data() + (size_t)w * s->max_instr * 2;
+        for (int i = 0, e = 0; i < s->max_instr && l[i].op != mk::OP_END; ++i) {
+            if (l[i].op != mk::OP_GEMV) continue;
+            const mk::Instr &I = l[i];
+            if (I.S == 0) { mk::set_error("a GEMV task has zero K splits"); return MK_ESCHED; }
+            const uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb, ue = I.u0 + I.nu;
+            const uint32_t total = (ue / I.S) * I.kbt + (ue % I.S) * I.nkb - first;
+            if ((uint64_t)I.w_chunk + first + total > s->wm.n_chunks) { mk::set_error("a GEMV task reaches beyond the weight region"); return MK_ESCHED; }
+            dst[2 * e] = I.w_chunk + first; dst[2 * e + 1] = total;
+            ++e;
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(s->ws + s->lay.stream, wstream.data(), wstream.size() * 4, hipMemcpyHostToDevice, st));
     // RoPE table: angle = pos * theta^(-2i/d), evaluated in double, stored as (cos, sin) fp32
     {
         const int d = s->dm.d, T = s->dm.Tm;
@@ -233,7 +246,7 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
                 tab[((size_t)p * (d / 2) + i) * 2 + 1] = (float)std::sin(ang);
             }
         HIP_TRY(hipMemcpyAsync(s->ws + s->lay.rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st));
-        HIP_TRY(hipStreamSynchronize(st));   // the host vectors above die here
+        HIP_TRY(hipStreamSynchronize(st));   // the host vectors above (and the stream table) die here
     }
     int rc = reset_sync_state(s, st);
     if (rc) return rc;
@@ -336,10 +349,8 @@ int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positio
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
-    if (s->two_per_cu)
-        hipLaunchKernelGGL(mk_megakernel_x2, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
-    else if (s->tl.ring_pages)
-        hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads + 64), s->lds_total, st, P, lp);
+    if (s->tl.ring_pages && !(P.dbg & 4u))
+        hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     else
         hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());
@@ -371,9 +382,9 @@ int mk_check(mk_schedule *s, void *stream)
     if (!s || !s->bound) { mk::set_error("mk_check on an unbound schedule"); return MK_ESTATE; }
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipStreamSynchronize(st));
-    uint32_t e[8] = {0};
+    uint32_t e[16] = {0};
     HIP_TRY(hipMemcpy(e, s->ws + s->lay.err, sizeof e, hipMemcpyDeviceToHost));
-    if (e[0] == 0 && e[1] == 0) return MK_OK;
+    if (e[0] == 0 && e[1] == 0 && e[2] == 0) return MK_OK;
     int rc = reset_sync_state(s, st);
     HIP_TRY(hipStreamSynchronize(st));
     if (rc) return rc;
@@ -382,6 +393,10 @@ int mk_check(mk_schedule *s, void *stream)
         snprintf(buf, sizeof buf, "a dependency wait hit the spin limit (first reported at instruction %u of some workgroup)", e[0] - 1);
         mk::set_error(buf);
         return MK_ETIMEOUT;
+    }
+    if (e[2]) {
+        mk::set_error("the weight-page ring ran dry: stream table and instruction lists disagree");
+        return MK_ESCHED;
     }
     mk::set_error(e[1] == 1 ? "token id outside [0, vocab)" : "position outside [0, max_context)");
     return MK_EINVAL;

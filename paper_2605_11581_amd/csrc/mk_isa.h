@@ -30,7 +30,8 @@ constexpr int kPrefetch = 16;          // 128-bit weight loads a lane keeps in f
 // LDS map of a workgroup:
 //   [0, 256)    current instruction
 //   [256, 512)  block-reduction scratch, flags
-//   [512, ...)  cross-wave partial sums (red), then the staged input vector / attention scratch (xs)
+//   [512, ...)  cross-wave partial sums (red), then the staged input vector / attention scratch (xs),
+//               then (1 KB aligned) the weight-page ring: ring_slots / 4 pages of 1 KB per wavefront
 constexpr int kLdsInstr = 0;
 constexpr int kLdsMisc = 256;
 constexpr int kLdsRed = 512;
@@ -134,6 +135,8 @@ struct Layout {
     uint64_t instr;      // Instr[n_wg][max_instr]
     uint64_t err;        // uint32[8] sticky error flags
     uint64_t trace;      // uint64[n_wg][max_instr][8]: task begin, dependencies met, prologue done, end, 4 task-internal marks
+    uint64_t stream;     // uint32[n_wg][max_instr][2]: weight stream of a workgroup, one (first chunk, chunk count) per GEMV
+                         // task in list order, closed by (kNone, kNone); derived from the instruction lists at bind time
     uint64_t total;
 };
 
@@ -158,7 +161,8 @@ struct Params {
     uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
     uint32_t ctr_stride;  // dwords between dependency counters
     uint32_t poll_sleep;  // s_sleep units between two polls of a dependency counter
-    uint32_t dbg;         // timing experiments only: bit 0 skip dependency waits, bit 1 skip the store drain (results invalid)
+    uint32_t dbg;         // development only: bit 0 skip dependency waits, bit 1 skip the store drain (both: results invalid,
+                          // timing experiments), bit 2 run a ring schedule with the direct-load kernel
 };
 
 }  // namespace mk

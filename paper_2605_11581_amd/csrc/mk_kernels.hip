@@ -9,8 +9,10 @@
 // (mk_op_kernel) runs the same task bodies, one launch per DAG operator.
 //
 // Weight streaming follows the paper's decoupling (Sec. 4.2.3, Fig. 4): loads
-// that do not depend on the previous operator (the task's first weight chunks)
-// are issued before the dependency wait.
+// that do not depend on the previous operator are issued before the dependency
+// wait -- through the LDS page ring the whole weight stream of a workgroup runs
+// ahead of its consumers across task boundaries; without a ring the first
+// chunks of each task are loaded into registers before the wait.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,52 +27,45 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct LdsPlan {
     uint32_t red_bytes;   // cross-wave reduction region
     uint32_t xs_off;      // byte offset of the staged-input region
-    uint32_t ring_off;    // byte offset of the weight-page ring (ring kernel only)
-    uint32_t ring_slots;  // 1 KB chunk slots in the ring (multiple of 4)
+    uint32_t ring_off;    // byte offset of the weight-page ring (1 KB aligned)
+    uint32_t ring_slots;  // 1 KB pages in the ring, a quarter per wavefront (0: no ring)
 };
 
-// Per-wave view of the workgroup: LDS plan plus the state of the consumer barrier.
-// In the ring kernel a fifth wave (the loader) streams weights into LDS pages and never
-// takes part in barriers, so the four consumer waves synchronise through an LDS counter
-// instead of s_barrier.
+// Per-wave view of the workgroup: LDS plan plus the state of this wavefront's weight-page ring.
+//
+// Page ring (persistent kernel with ring_slots > 0; paper Sec. 4.1.1 pages, Sec. 4.2.2 Step 3 page
+// states, Sec. 4.2.3 decoupled weight loads).  The weight chunks a workgroup consumes over the
+// whole step form one static stream (its GEMV tasks in list order); wavefront w owns the chunks
+// with task-local index w, w+4, ... of every task.  Each wavefront streams its own chunks into
+// its own ring of S = ring_slots / 4 pages with 128-bit global->LDS DMA loads, up to S chunks
+// ahead of its consumption and across task and operator boundaries: weights depend on nothing,
+// so HBM streaming continues while the workgroup waits on dependency counters.  A page is
+// Locked from the DMA issue until the wavefront's in-order load counter shows it has landed,
+// Ready until the wavefront has read it into registers, then refilled at once.  Pages are
+// handled in stages of kStagePages: a stage holds up to four consecutive chunks of ONE task (the
+// last stage of a task may be partly used), is filled by one burst of DMA loads and read back
+// by one burst of LDS reads.  Because a wavefront only reads pages it filled itself, the ring
+// needs no cross-wave synchronisation.  All fields are wave-uniform.
+constexpr uint32_t kStagePages = 4;
+typedef const __attribute__((address_space(4))) uint32_t *cptr;   // data that never changes during a launch
 struct Wg {
-    uint32_t red_bytes, xs_off, ring_off, ring_slots;
-    bool ring;
-    uint32_t bar_target;  // consumer barrier: arrivals expected so far
-    uint32_t chunk_n;     // ring: global index (in this workgroup's weight stream) of the next task's first chunk
-    uint32_t landed_c;    // ring: cached copy of the loader's published count
+    uint32_t red_bytes, xs_off;
+    bool ring;            // weights come through the page ring (else: straight into registers)
     int npf;              // 128-bit weight loads a lane keeps in flight (direct-load path), <= kPrefetch
+    uint32_t wave;
+    uint32_t ring_off;    // byte offset of this wave's page 0 from the LDS base
+    uint32_t ring_lds;    // LDS address of this wave's page 0
+    uint32_t nst;         // stages (groups of kStagePages pages) of this wave
+    uint32_t head, tail;  // chunks this wave has issued / read back
+    uint32_t hst, tst;    // stage the next group is loaded into / read from
+    cptr pf_ptr;          // next entry of the workgroup's stream table
+    uint32_t pf_left;     // table entries not yet read (bounds the walk)
+    const char *pf_src;   // address of this wave's next chunk in the current entry
+    uint32_t pf_rem;      // chunks of the current entry this wave has not issued yet
+    bool pf_live;
 };
 
-// LDS sync words of the ring kernel (inside the misc area)
-constexpr int kSyncLanded = kLdsMisc + 192;   // chunks the loader has published as landed
-constexpr int kSyncHw = kLdsMisc + 208;       // [4] per consumer wave: 1 + last chunk it has finished with (16-byte aligned)
-constexpr int kSyncBar = kLdsMisc + 224;      // consumer barrier counter
-constexpr uint32_t kLdsSpinLimit = 1u << 24;
-
-// LDS sync words are read through explicit local-address-space volatile pointers (a generic
-// volatile pointer would turn every poll into a flat load).
-typedef volatile __attribute__((address_space(3))) uint32_t *lds_vptr;
-__device__ __forceinline__ lds_vptr lds_word(char *lds, int byte_off)
-{
-    return (lds_vptr)((__attribute__((address_space(3))) char *)lds + byte_off);
-}
-
-__device__ __forceinline__ void wg_sync(Wg &wg, char *lds)
-{
-    if (!wg.ring) {
-        __syncthreads();
-        return;
-    }
-    lds_vptr bar = lds_word(lds, kSyncBar);
-    wg.bar_target += kWaves;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    uint32_t it = 0;
-    while ((int32_t)(*bar - wg.bar_target) < 0)
-        if (++it > kLdsSpinLimit) break;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
+__device__ __forceinline__ void wg_sync(Wg &, char *) { __syncthreads(); }
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ uint32_t rfl(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -140,14 +135,17 @@ __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
 // Poll a dependency counter until it has received `target` signals (wrap-safe).
 // Bounded: after `limit` polls the wait gives up and reports failure, so every
 // wave always reaches the end of its instruction list.
-__device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t target, uint32_t limit, uint32_t nap)
+__device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t target, uint32_t limit, uint32_t nap,
+                                             uint32_t *polls = nullptr)
 {
     uint32_t it = 0;
+    bool ok = true;
     while ((int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-        if (++it > limit) return false;
+        if (++it > limit) { ok = false; break; }
         for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(2);
     }
-    return true;
+    if (polls) *polls += it + 1;
+    return ok;
 }
 
 __device__ __forceinline__ int clamp_i(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
@@ -384,22 +382,113 @@ __device__ __forceinline__ uint32_t unit_nkb(uint32_t u, uint32_t S, uint32_t nk
     return (s == S - 1) ? kbt - s * nkb : nkb;
 }
 
+// ---- weight-page ring ------------------------------------------------------------------------
+// Wait until at most 4 * k4 vector-memory operations of this wave are outstanding (k4 is clamped
+// to 15; rounding the allowance down only waits longer).  s_waitcnt takes its count as an
+// immediate, so the wait is one entry of a table of (s_waitcnt, s_branch) pairs of 8 bytes each,
+// entered through a computed jump: the three instructions between s_getpc_b64 and the table are
+// 4 bytes each, hence the offset 12.
+__device__ __forceinline__ void vm_wait4(uint32_t k4)
+{
+    uint32_t tmp;
+    asm volatile(
+        "s_min_u32 %0, %1, 15\n\t"
+        "s_lshl_b32 %0, %0, 3\n\t"
+        "s_add_u32 %0, %0, 12\n\t"
+        "s_getpc_b64 vcc\n\t"
+        "s_add_u32 vcc_lo, vcc_lo, %0\n\t"
+        "s_addc_u32 vcc_hi, vcc_hi, 0\n\t"
+        "s_setpc_b64 vcc\n\t"
+        "s_waitcnt vmcnt(0)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(4)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(8)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(12)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(16)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(20)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(24)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(28)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(32)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(36)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(40)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(44)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(48)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(52)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(56)\n\ts_branch .Lvmw_%=\n\t"
+        "s_waitcnt vmcnt(60)\n\ts_branch .Lvmw_%=\n"
+        ".Lvmw_%=:"
+        : "=&s"(tmp) : "s"(k4) : "memory", "vcc", "scc");
+}
+
+// One 128-bit global->LDS DMA load of a 1 KB chunk: lane l's 16 bytes land at dst + 16 l.  Written
+// as inline assembly on purpose: the compiler does not track it, so it never serialises the
+// wave's LDS reads against the DMA queue; the ring code waits for landing itself (vm_wait4).
+__device__ __forceinline__ void dma_chunk(uint32_t dst_lds, const char *src, uint32_t lane_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 ::"s"(dst_lds), "v"(lane_off), "s"(src) : "memory", "m0");
+}
+
+// Move the stream cursor to the next table entry that holds chunks of this wave (rare path).
+__device__ __forceinline__ void ring_advance(const Params &P, Wg &wg)
+{
+    while (wg.pf_live && wg.pf_rem == 0) {
+        if (wg.pf_left == 0) { wg.pf_live = false; break; }
+        const uint32_t base = wg.pf_ptr[0], total = wg.pf_ptr[1];
+        wg.pf_ptr += 2; --wg.pf_left;
+        if (total == kNone) { wg.pf_live = false; break; }
+        if (total > wg.wave) {
+            wg.pf_rem = (total - wg.wave + kWaves - 1) / kWaves;
+            wg.pf_src = P.ws + P.lay.weights + ((size_t)base + wg.wave) * kChunkBytes;
+        }
+    }
+}
+
+// Fill the next stage with the next group of this wave's stream: up to four chunks of one task
+// (no-op once the stream is exhausted).  Consecutive chunks of a wave are kWaves chunks apart.
+__device__ __forceinline__ void ring_fill_stage(const Params &P, Wg &wg)
+{
+    if (wg.pf_rem == 0) ring_advance(P, wg);
+    if (!wg.pf_live) return;
+    const uint32_t lane_off = (threadIdx.x & 63u) * 16u;
+    const uint32_t dst = wg.ring_lds + wg.hst * (kStagePages * kChunkBytes);
+    const char *src = wg.pf_src;
+    constexpr size_t kStep = (size_t)kWaves * kChunkBytes;
+    uint32_t n;
+    if (wg.pf_rem >= kStagePages) {
+        n = kStagePages;
+        dma_chunk(dst, src, lane_off);
+        dma_chunk(dst + kChunkBytes, src + kStep, lane_off);
+        dma_chunk(dst + 2 * kChunkBytes, src + 2 * kStep, lane_off);
+        dma_chunk(dst + 3 * kChunkBytes, src + 3 * kStep, lane_off);
+    } else {
+        n = wg.pf_rem;
+        dma_chunk(dst, src, lane_off);
+        if (n > 1) dma_chunk(dst + kChunkBytes, src + kStep, lane_off);
+        if (n > 2) dma_chunk(dst + 2 * kChunkBytes, src + 2 * kStep, lane_off);
+    }
+    wg.pf_src = src + n * kStep;
+    wg.pf_rem -= n;
+    wg.head += n;
+    wg.hst = wg.hst + 1 == wg.nst ? 0 : wg.hst + 1;
+}
+
 struct GemvStream {
     const __attribute__((address_space(1))) u32x4 *wp;   // this lane's pointer to chunk 0 of the task
     uint32_t total;       // chunks in the task
-    u32x4 buf[kPrefetch];
+    u32x4 buf[kPrefetch]; // direct-load path only
 };
 
 // Issue the first weight loads of a GEMV task.  They depend on nothing the
 // previous operator produces, so this runs before the dependency wait.
-__device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st, bool ring, int npf)
+template <bool RING>
+__device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st, int npf)
 {
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
     uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb;
     uint32_t ulast = I.u0 + I.nu;  // one past the last unit
     uint32_t end = (ulast / I.S) * I.kbt + (ulast % I.S) * I.nkb;
     st.total = end - first;
-    if (ring) return;
+    if (RING) return;
     st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
     const uint32_t last = st.total ? st.total - 1 : 0;
 #pragma unroll
@@ -410,7 +499,7 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
     }
 }
 
-template <bool MFMA>
+template <bool MFMA, bool RING>
 __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, Wg &lp, GemvStream &st, int batch)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
@@ -499,37 +588,51 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     };
 
     const uint32_t total = st.total;
-    if (lp.ring) {
-        // Weights come from the LDS page ring filled by the loader wave.  Chunk n of this
-        // workgroup's stream lives in slot n % ring_slots and belongs to consumer wave n & 3.
-        const uint32_t n0 = lp.chunk_n;                       // global index of the task's chunk 0
-        const uint32_t i0 = ((uint32_t)wave - n0) & 3u;       // first local index owned by this wave
-        kbi = i0;
-        lds_vptr landed = lds_word(lds, kSyncLanded);
-        lds_vptr hw = lds_word(lds, kSyncHw) + wave;
-        const char *ring = lds + lp.ring_off;
-        constexpr int U = 4;                                   // LDS reads in flight per lane
-        const uint32_t nslot = lp.ring_slots;
-        uint32_t slot = (n0 + i0) % nslot;                     // slot of this wave's next chunk (advances by 4, wraps)
-        for (uint32_t i = i0; i < total; i += U * kWaves) {
-            uint32_t last_i = i + (U - 1) * kWaves;
-            if (last_i >= total) last_i = i + ((total - 1 - i) / kWaves) * kWaves;
-            const uint32_t need = n0 + last_i + 1;            // published count that covers this group
-            if ((int32_t)(lp.landed_c - need) < 0) {
-                uint32_t it = 0;
-                do { lp.landed_c = *landed; } while ((int32_t)(lp.landed_c - need) < 0 && ++it < kLdsSpinLimit);
+    if (RING) {
+        // Weights come from this wave's LDS page ring, a stage (up to four chunks) at a time:
+        // wait until the stage's DMA loads have landed (loads complete in issue order, so "at most
+        // head - tail - n outstanding" means the n oldest chunks are there), read it back, hand the
+        // stage to the DMA again as soon as the reads have returned, and use the registers while
+        // the next stage is being read.
+        const uint32_t mine = total > (uint32_t)wave ? (total - (uint32_t)wave + kWaves - 1) / kWaves : 0u;
+        const uint32_t ng = (mine + kStagePages - 1) / kStagePages;
+        const char *ring = lds + lp.ring_off + lane * 16;
+        bool ok = true;
+        // n == 0: no further stage of this task -- the registers are still (re)defined by in-bounds
+        // reads whose values are never used, which keeps them free of loop-carried copies
+        auto read_stage = [&](u32x4 (&w)[kStagePages], uint32_t n) {
+            if (n) {
+                const uint32_t out = lp.head - lp.tail;
+                if (out < n) {   // stream table and instruction list disagree: never use an unfilled page
+                    set_err(P, 2, 1u);
+                    ok = false;
+                } else {
+                    vm_wait4((out - n) >> 2);
+                }
             }
-            u32x4 w[U];
+            const char *base = ring + (size_t)lp.tst * (kStagePages * kChunkBytes);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                w[u] = *(const u32x4 *)(ring + (size_t)slot * kChunkBytes + lane * 16);
-                if (i + (uint32_t)(u + 1) * kWaves < total) { slot += kWaves; if (slot >= nslot) slot -= nslot; }
+            for (uint32_t u = 0; u < kStagePages; ++u) w[u] = *(const u32x4 *)(base + u * kChunkBytes);
+            if (n) {
+                lp.tail += n;
+                lp.tst = lp.tst + 1 == lp.nst ? 0 : lp.tst + 1;
             }
+        };
+        auto step = [&](u32x4 (&wc)[kStagePages], u32x4 (&wn)[kStagePages], uint32_t g) {
+            const uint32_t n = g < ng ? min(kStagePages, mine - g * kStagePages) : 0u;
+            // the reads of this stage have returned: its pages go back to the DMA
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (n) ring_fill_stage(P, lp);
+            read_stage(wn, g + 1 < ng ? min(kStagePages, mine - (g + 1) * kStagePages) : 0u);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (i + (uint32_t)u * kWaves < total) consume(w[u]);
-            // the slots of this group may be refilled now
-            if (lane == 0) *hw = n0 + last_i + 1;
+            for (uint32_t u = 0; u < kStagePages; ++u)
+                if (u < n && ok) consume(wc[u]);
+        };
+        u32x4 w0[kStagePages], w1[kStagePages];
+        read_stage(w0, min(kStagePages, mine));
+        for (uint32_t g = 0; g < ng; g += 2) {
+            step(w0, w1, g);
+            step(w1, w0, g + 1);
         }
     } else if (total) {
         const uint32_t last = total - 1;
@@ -665,6 +768,8 @@ __device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, At
         // clamped to a valid row: rows at or beyond p are masked when consumed
         int t = att_pos(grp + st.sub, bs, nc, c);
         t = t < P.max_context ? t : P.max_context - 1;
+        st.kbuf[j] = u32x4{0u, 0u, 0u, 0u};
+        st.vbuf[j] = u32x4{0u, 0u, 0u, 0u};
         if (grp < st.npos) {
             st.kbuf[j] = __builtin_nontemporal_load(st.kp + (size_t)t * LPP);
             st.vbuf[j] = __builtin_nontemporal_load(st.vp + (size_t)t * LPP);
@@ -780,8 +885,10 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         float vf[3][8];
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
-            vf[u][0] = bf_lo(vw[u].x); vf[u][1] = bf_hi(vw[u].x); vf[u][2] = bf_lo(vw[u].y); vf[u][3] = bf_hi(vw[u].y);
-            vf[u][4] = bf_lo(vw[u].z); vf[u][5] = bf_hi(vw[u].z); vf[u][6] = bf_lo(vw[u].w); vf[u][7] = bf_hi(vw[u].w);
+            // a masked position contributes exactly zero whatever its (possibly never written) row holds
+            const u32x4 vv = ok[u] ? vw[u] : u32x4{0u, 0u, 0u, 0u};
+            vf[u][0] = bf_lo(vv.x); vf[u][1] = bf_hi(vv.x); vf[u][2] = bf_lo(vv.y); vf[u][3] = bf_hi(vv.y);
+            vf[u][4] = bf_lo(vv.z); vf[u][5] = bf_hi(vv.z); vf[u][6] = bf_lo(vv.w); vf[u][7] = bf_hi(vv.w);
         }
 #pragma unroll
         for (int h = 0; h < kMaxGroup; ++h)
@@ -951,9 +1058,9 @@ __device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, u
 }
 
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
-template <bool PERSISTENT>
+template <bool PERSISTENT, bool RING>
 __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
-                                           bool &dead, uint32_t nxt = 0)
+                                           bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr)
 {
     const int tid = threadIdx.x;
     uint32_t *sflag = (uint32_t *)(lds + kLdsMisc + 128);
@@ -962,9 +1069,10 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     const bool tracing = PERSISTENT && (P.flags & 1u);
     if (tracing && tid == 0) t0 = wall_clock64();
 
+    const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u);
     GemvStream st;
     AttStream as;
-    if (I.op == OP_GEMV) gemv_issue(P, I, st, lp.ring, lp.npf);
+    if (I.op == OP_GEMV) gemv_issue<RING>(P, I, st, lp.npf);
     else if (I.op == OP_ATT) {
         if (P.head_dim == 128) att_issue<128>(P, *(const InstrAtt *)&I, as);
         else att_issue<64>(P, *(const InstrAtt *)&I, as);
@@ -973,18 +1081,26 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     if (PERSISTENT && I.op == OP_GEMV) trace_mark(P, pc, 0);
     if (PERSISTENT) {
         if (tid == 0) {
-            uint32_t ok = 1;
-            if (!dead && !(P.dbg & 1u)) {
-#pragma unroll
-                for (int k = 0; k < 2; ++k)
-                    if (ok && I.wait_ctr[k] != kNone)
-                        ok = wait_counter(counters + (size_t)I.wait_ctr[k] * P.ctr_stride,
-                                          P.epoch * I.wait_cnt[k], P.spin_limit, P.poll_sleep) ? 1u : 0u;
+            uint32_t ok = 1, polls = 0;
+            if (waiting) {
+                if (I.wait_ctr[0] != kNone)
+                    ok = wait_counter(counters + (size_t)I.wait_ctr[0] * P.ctr_stride, P.epoch * I.wait_cnt[0],
+                                      P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
+                if (ok && I.wait_ctr[1] != kNone)
+                    ok = wait_counter(counters + (size_t)I.wait_ctr[1] * P.ctr_stride, P.epoch * I.wait_cnt[1],
+                                      P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
             }
             if (!ok) set_err(P, 0, 1u + pc);
             sflag[0] = ok;
-            if (I.op == OP_GEMV) trace_mark(P, pc, 1);
+            if (I.op == OP_GEMV) {
+                trace_mark(P, pc, 1);
+                if (tracing) ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 6] = polls;   // mark 2: polls issued
+            }
         }
+        // The next instruction (loaded by the caller before this task began) has certainly arrived
+        // by now; parking it in its LDS slot here means nothing waits on memory between the end
+        // of this task and the start of the next one.
+        if (nxt_slot && tid < kInstrDwords) nxt_slot[tid] = nxt;
         wg_sync(lp, lds);
         if (sflag[0] == 0) dead = true;
     }
@@ -995,13 +1111,12 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         if (I.flags & F_MFMA) {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
             if (tracing && tid == 0) t2 = wall_clock64();
-            gemv_main<true>(P, I, lds, lp, st, P.batch);
+            gemv_main<true, RING>(P, I, lds, lp, st, P.batch);
         } else {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
             if (tracing && tid == 0) t2 = wall_clock64();
-            gemv_main<false>(P, I, lds, lp, st, 1);
+            gemv_main<false, RING>(P, I, lds, lp, st, 1);
         }
-        lp.chunk_n += st.total;
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
         if (P.head_dim == 128) att_task<128>(P, A, lds, lp, as, pc);
@@ -1032,132 +1147,32 @@ __device__ __forceinline__ void read_instr(const uint32_t *slot, Instr &I)
     for (int j = 0; j < kInstrDwords; ++j) dst[j] = rfl(slot[j]);
 }
 
-__device__ __forceinline__ Wg make_wg(const LdsPlan &p, bool ring, int npf = kPrefetch)
+__device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *lds, bool ring, int npf = kPrefetch)
 {
+    typedef __attribute__((address_space(3))) char *lptr;
     Wg wg;
-    wg.red_bytes = p.red_bytes; wg.xs_off = p.xs_off; wg.ring_off = p.ring_off; wg.ring_slots = p.ring_slots;
-    wg.ring = ring; wg.bar_target = 0; wg.chunk_n = 0; wg.landed_c = 0; wg.npf = npf;
+    wg.red_bytes = p.red_bytes; wg.xs_off = p.xs_off;
+    wg.ring = ring; wg.npf = npf;
+    wg.wave = rfl(threadIdx.x >> 6);
+    wg.nst = p.ring_slots / (kWaves * kStagePages);
+    wg.ring_off = p.ring_off + wg.wave * wg.nst * kStagePages * kChunkBytes;
+    wg.ring_lds = (uint32_t)(uintptr_t)(lptr)lds + wg.ring_off;
+    wg.head = wg.tail = 0; wg.hst = wg.tst = 0;
+    wg.pf_ptr = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.stream) + (size_t)blockIdx.x * P.max_instr * 2);
+    wg.pf_left = P.max_instr;
+    wg.pf_src = nullptr; wg.pf_rem = 0; wg.pf_live = wg.ring && wg.nst > 0;
     return wg;
-}
-
-// ---- loader wave (ring kernel) --------------------------------------------------------------
-// Streams the weight chunks of every GEMV task of this workgroup, in list order, into the LDS
-// page ring with 128-bit global->LDS DMA loads.  It runs ahead of the consumers by up to the
-// ring capacity, across task and operator boundaries: weights depend on nothing (paper
-// Sec. 4.2.3), so HBM streaming continues while the consumers wait on dependency counters.
-// Page states (Sec. 4.2.2 Step 3): a slot is Locked from the DMA issue until the loader has
-// seen it land (vmcnt) and published it, Ready until its consumer wave moves its high-water
-// mark past it, then Empty again.  LDS sync words are accessed with inline asm so that the
-// compiler does not serialise them against the DMA queue.
-__device__ __forceinline__ uint32_t lds_ld_u32(uint32_t addr)
-{
-    uint32_t v;
-    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
-    return v;
-}
-__device__ __forceinline__ void lds_st_u32(uint32_t addr, uint32_t v)
-{
-    asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_min4(uint32_t addr)
-{
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
-    return min(min(v.x, v.y), min(v.z, v.w));
-}
-
-constexpr int kDmaDepth = 56;   // DMA loads the loader keeps in flight (vmcnt is 6 bits)
-
-// s_waitcnt vmcnt(k) needs an immediate: wait until at most 4 * (k4) loads are outstanding
-__device__ __forceinline__ void vm_wait4(uint32_t k4)
-{
-    switch (k4) {
-    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
-    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
-    case 7: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
-    case 8: asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); break;
-    case 9: asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); break;
-    case 10: asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); break;
-    case 11: asm volatile("s_waitcnt vmcnt(44)" ::: "memory"); break;
-    case 12: asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); break;
-    case 13: asm volatile("s_waitcnt vmcnt(52)" ::: "memory"); break;
-    default: asm volatile("s_waitcnt vmcnt(56)" ::: "memory"); break;
-    }
-}
-
-__device__ __forceinline__ void loader_wave(const Params &P, const LdsPlan &lp, char *lds)
-{
-    typedef const __attribute__((address_space(4))) uint32_t *cptr;      // instruction lists never change during a launch
-    typedef const __attribute__((address_space(1))) void *gptr;
-    typedef __attribute__((address_space(3))) void *lptr;
-    const uint32_t lane = threadIdx.x & 63;
-    cptr list = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr)lds;
-    const uint32_t nslot = lp.ring_slots;
-    const char *wbase = P.ws + P.lay.weights;
-    uint32_t n = 0, pub = 0, slot = 0, hw_min = 0;
-    for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
-        const uint32_t op = list[(size_t)pc * kInstrDwords + 0];
-        if (op == OP_END) break;
-        if (op != OP_GEMV) continue;
-        const uint32_t w_chunk = list[(size_t)pc * kInstrDwords + 9], kbt = list[(size_t)pc * kInstrDwords + 10],
-                       nkb = list[(size_t)pc * kInstrDwords + 11], S = list[(size_t)pc * kInstrDwords + 12],
-                       u0 = list[(size_t)pc * kInstrDwords + 13], nu = list[(size_t)pc * kInstrDwords + 14];
-        const uint32_t first = (u0 / S) * kbt + (u0 % S) * nkb, ue = u0 + nu;
-        const uint32_t total = (ue / S) * kbt + (ue % S) * nkb - first;
-        const char *src = wbase + ((size_t)w_chunk + first) * kChunkBytes + lane * 16;
-        for (uint32_t i = 0; i < total; ++i) {
-            if (n >= nslot && (int32_t)(hw_min - (n - nslot + 1)) < 0) {
-                // ring full: publish what lands, four chunks at a time, until a consumer frees the slot
-                uint32_t it = 0;
-                do {
-                    const uint32_t out = n - pub;
-                    if (out) {
-                        const uint32_t k4 = out > 4 ? (out - 1) >> 2 : 0;   // leave at most 4*k4 < out outstanding
-                        vm_wait4(k4);
-                        pub = n - min(out, k4 * 4);
-                        lds_st_u32(lds0 + kSyncLanded, pub);
-                    }
-                    hw_min = lds_min4(lds0 + kSyncHw);
-                } while ((int32_t)(hw_min - (n - nslot + 1)) < 0 && ++it < kLdsSpinLimit);
-                if (it >= kLdsSpinLimit) set_err(P, 2, 1u);
-            }
-            __builtin_amdgcn_global_load_lds((gptr)(uintptr_t)(src + (size_t)i * kChunkBytes),
-                                             (lptr)(lds + lp.ring_off + (size_t)slot * kChunkBytes), 16, 0, 2 /* nt */);
-            ++n;
-            if (++slot == nslot) slot = 0;
-            if (n - pub > (uint32_t)kDmaDepth) {
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaDepth) : "memory");
-                pub = n - kDmaDepth;
-                lds_st_u32(lds0 + kSyncLanded, pub);
-            }
-        }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    lds_st_u32(lds0 + kSyncLanded, n);
 }
 
 // Persistent walk of this workgroup's whole list; the next instruction is fetched while the
 // current one runs.
-template <bool RING, int NPF>
+template <bool RING>
 __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    Wg lp = make_wg(plan, RING, NPF);
-    if (RING) {
-        // LDS is not cleared between launches: reset the sync words before any role starts
-        if (threadIdx.x < 16) ((uint32_t *)(lds + kSyncLanded))[threadIdx.x] = 0u;
-        __syncthreads();                       // the only hardware barrier all five waves share
-        if (threadIdx.x >= kWgThreads) {
-            loader_wave(P, plan, lds);
-            return;
-        }
-    }
+    Wg lp = make_wg(P, plan, lds, RING);
+    if (RING)   // fill the ring with the first stages of this wave's stream
+        for (uint32_t i = 0; i < lp.nst; ++i) ring_fill_stage(P, lp);
     const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
     uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);   // two slots of 32 dwords
     bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
@@ -1170,9 +1185,10 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
         uint32_t nxt = 0;
         const bool more = pc + 1 < P.max_instr;
         if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
-        exec_instr<true>(P, lp, lds, I, pc, dead, nxt);
-        if (more && threadIdx.x < kInstrDwords) sinstr[((pc + 1) & 1u) * kInstrDwords + threadIdx.x] = nxt;
+        exec_instr<true, RING>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
     }
+    // no DMA load may still be writing LDS when the workgroup retires
+    if (RING) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 // One operator instance: the instructions of this workgroup whose ref_seq matches (they are
@@ -1180,7 +1196,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
 __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    Wg lp = make_wg(plan, false);
+    Wg lp = make_wg(P, plan, lds, false);
     const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
     uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);
     uint32_t *srange = (uint32_t *)(lds + kLdsMisc + 160);   // [0] first match, [1] match count
@@ -1199,23 +1215,18 @@ __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
         wg_sync(lp, lds);
         Instr I;
         read_instr(sinstr, I);
-        exec_instr<false>(P, lp, lds, I, pc, dead);
+        exec_instr<false, false>(P, lp, lds, I, pc, dead);
     }
 }
 
 }  // namespace mk
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, mk::kPrefetch>(P, lp); }
+mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false>(P, lp); }
 
-// Two workgroups per CU (two waves per SIMD, at most 256 VGPRs each, half the prefetch depth per
-// wave): one workgroup's dependency latency overlaps the other's streaming.
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads, 2)
-mk_megakernel_x2(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, mk::kPrefetch / 2>(P, lp); }
-
-// Ring variant: four consumer waves plus one loader wave per workgroup.
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads + 64)
-mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true, mk::kPrefetch>(P, lp); }
+// Same walk with the per-wave LDS page ring carrying the weight stream.
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
+mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true>(P, lp); }
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
 mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op(P, lp); }

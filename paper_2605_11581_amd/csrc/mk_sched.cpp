@@ -560,6 +560,7 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     L.instr = off; off = align_up(off + s->instr.size() * 4, 4096);
     L.err = off; off = align_up(off + 64, 4096);
     L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 64 : 0), 4096);
+    L.stream = off; off = align_up(off + (uint64_t)s->n_wg * s->max_instr * 8, 4096);
     L.total = off;
     s->sim = simulate(s);
     return MK_OK;
@@ -574,7 +575,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     if (rc) return rc;
     const int mfma = cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
     if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
-    if (cfg.ring_kb > 0 && (cfg.ring_kb < 32 || cfg.ring_kb > 144)) { set_error("mk_config: ring_kb must be 0 (no ring) or 32..144"); return MK_EINVAL; }
+    if (cfg.ring_kb < -2 || (cfg.ring_kb > 0 && (cfg.ring_kb < 16 || cfg.ring_kb > 144))) { set_error("mk_config: ring_kb must be -2 (search), -1 (auto), 0 (no ring) or 16..144"); return MK_EINVAL; }
 
     for (int v : {cfg.split_qkv, cfg.split_o, cfg.split_gateup, cfg.split_down, cfg.attn_chunks})
         if (v < 0) { set_error("mk_config: negative split / chunk count"); return MK_EINVAL; }
@@ -617,7 +618,14 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     best.r_qkv = best.r_o = best.r_gu = best.r_d = c_r[0]; best.r_head = cfg.chunk_rows ? c_r[0] : 4;
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
-    best.ring_pages = cfg.ring_kb > 0 ? cfg.ring_kb / 16 * 16 : 0;
+    // weight-page ring: a pipeline stage is 16 pages (4 per wavefront).  The depth is only searched
+    // when asked for (ring_kb == -2): measured on MI355X the direct-load path is the faster one at
+    // every depth that fits, so "auto" (-1) keeps weights out of LDS.
+    std::vector<int> c_ring;
+    if (cfg.ring_kb > 0) c_ring = {cfg.ring_kb / 16 * 16};
+    else if (cfg.ring_kb == -2) c_ring = {0, 32, 48, 64, 80, 96, 112, 128};
+    else c_ring = {0};
+    best.ring_pages = c_ring[0];
     best.n_stage = best.ring_pages ? best.ring_pages / 16 : 1;
     int tried = 0, pruned = 0;
     double best_ms = -1, best_duty = 0;
@@ -633,7 +641,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     struct Dim { int Tiling::*field; std::vector<int> *vals; };
     Dim dimsv[] = {{&Tiling::r_qkv, &c_r}, {&Tiling::s_qkv, &c_sqkv}, {&Tiling::r_o, &c_r}, {&Tiling::s_o, &c_so},
                    {&Tiling::r_gu, &c_rgu}, {&Tiling::s_gu, &c_sgu}, {&Tiling::r_d, &c_r}, {&Tiling::s_d, &c_sd},
-                   {&Tiling::nc, &c_nc}};
+                   {&Tiling::nc, &c_nc}, {&Tiling::ring_pages, &c_ring}};
     {
         double ms, du;
         if (eval(best, ms, du)) { best_ms = ms; best_duty = du; }
@@ -644,6 +652,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
             for (int v : *dm.vals) {
                 Tiling t = best;
                 t.*(dm.field) = v;
+                t.n_stage = t.ring_pages ? t.ring_pages / 16 : 1;
                 if (t.*(dm.field) == best.*(dm.field) && best_ms >= 0) continue;
                 double ms, du;
                 if (!eval(t, ms, du)) continue;

@@ -74,7 +74,7 @@ struct mk_schedule {
     char *ws;
     size_t ws_bytes;
     int device;
-    bool bound, loaded, two_per_cu;
+    bool bound, loaded;
     uint32_t epoch;
     void *ev0, *ev1;
     bool ev_valid;

@@ -105,6 +105,9 @@ def test_c0_greedy_32_steps_match_oracle():
     dict(chunk_rows=16, split_qkv=2, split_o=2, split_gateup=2, split_down=4, attn_chunks=4),
     dict(chunk_rows=8, split_gateup=2, split_down=2), dict(n_workgroups=40, attn_chunks=8), dict(attn_chunks=1),
     dict(use_mfma=1, split_qkv=2, split_o=4, split_gateup=2, split_down=2),
+    # weight-page ring (LDS-DMA stream across task boundaries): shallow, deep, ragged stages, matrix-core path
+    dict(ring_kb=16), dict(ring_kb=32, attn_chunks=2), dict(ring_kb=96, chunk_rows=2), dict(ring_kb=64, n_workgroups=24),
+    dict(ring_kb=48, use_mfma=1, split_o=2, split_down=2),
 ], ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()))
 def test_c0_variants(opts):
     say("c0 variant", opts)
@@ -176,6 +179,51 @@ def test_batched_sequences_with_ragged_positions():
     got = pr.gpu_step(cur[:2], [n + 3 for n in lens[:2]])
     assert rel_err(got[0], want[0]) <= TIGHT and rel_err(got[1], want[1]) <= TIGHT
     pr.close()
+
+
+def test_ring_and_direct_kernels_agree_bit_for_bit():
+    """The page ring changes where the weights wait (LDS instead of registers), not the arithmetic:
+    on the same schedule the ring kernel, the direct-load kernel and the per-operator launches
+    produce identical logits."""
+    full = tiny(max_batch=2, index=3)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    pr = Pair(cfg, w, ring_kb=32)
+    assert pr.dec.stats["ring_pages"] == 32
+    pr.prefill(synth.make_prompt(full, 45)[:-1])
+    ring = pr.gpu_step([7, 9], [44, 0])
+    per_op = pr.gpu_step([7, 9], [44, 0], per_op=True)
+    assert np.array_equal(ring, per_op)
+    pr.close()
+    pr = Pair(cfg, w, ring_kb=0)
+    pr.prefill(synth.make_prompt(full, 45)[:-1])
+    direct = pr.gpu_step([7, 9], [44, 0])
+    # a different LDS budget may pick another tiling, hence another summation order
+    assert rel_err(direct[0], ring[0]) <= TIGHT and rel_err(direct[1], ring[1]) <= TIGHT
+    pr.close()
+
+
+def test_cache_rows_beyond_the_position_are_never_used():
+    """KV slots at and after the current position hold whatever the caller left there (here NaN and
+    Inf bit patterns); masked positions must contribute exactly nothing."""
+    full = tiny(max_context=96)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full)
+    for opts in (dict(), dict(attn_chunks=4), dict(ring_kb=32, attn_chunks=2)):
+        pr = Pair(cfg, w, **opts)
+        prompt = synth.make_prompt(full, 21)
+        pr.orc.prefill(prompt[:-1], pr.kv_h)
+        poisoned = pr.kv_h.copy()
+        poisoned[:, :, :, :, 20:, :] = np.where(np.arange(poisoned.shape[-1]) % 2 == 0, 0x7FC0, 0x7F80).astype(poisoned.dtype)
+        pr.kv_d.copy_(torch.from_numpy(poisoned.view(np.int16)).to(DEV))
+        cur = int(prompt[-1])
+        for s in range(3):
+            want = pr.orc.step([cur], [20 + s], pr.kv_h)[0]
+            got = pr.gpu_step([cur], [20 + s])[0]
+            assert np.isfinite(got).all(), (opts, s)
+            assert rel_err(got, want) <= TIGHT, (opts, s)
+            cur = oracle.argmax(want)
+        pr.close()
 
 
 def test_two_runs_are_bit_identical():

@@ -92,7 +92,8 @@ def test_fixed_tiling_overrides_are_honoured():
 
 @pytest.mark.parametrize("bad", [dict(head_dim=8), dict(hidden=100), dict(max_batch=9), dict(max_batch=0),
                                  dict(n_q_heads=3), dict(n_layers=0), dict(max_context=0),
-                                 dict(max_batch=2, use_mfma=0), dict(ring_kb=200), dict(split_down=10 ** 6)])
+                                 dict(max_batch=2, use_mfma=0), dict(ring_kb=200), dict(ring_kb=8), dict(ring_kb=-3),
+                                 dict(split_down=10 ** 6)])
 def test_bad_configs_are_rejected(bad):
     cfg = synth.model_cfg(synth.CONFIGS["c0_tiny"])
     opts = {k: bad.pop(k) for k in list(bad) if k in ("use_mfma", "ring_kb", "split_down")}
@@ -100,6 +101,30 @@ def test_bad_configs_are_rejected(bad):
     with pytest.raises(mk.MkError) as e:
         mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=64, **opts))
     assert e.value.code in (mk.MK_EINVAL, mk.MK_EINFEASIBLE)
+
+
+def test_page_ring_obeys_the_lds_budget():
+    """Eq. 1-2 in the builder: the ring (pages of 1 KB, stages of 16) plus the staged activations,
+    the reduction area and the instruction/flag areas never exceed 160 KB; a ring that cannot fit
+    next to the attention scratch of the 1.5B shape is refused; the search mode picks a depth
+    that fits."""
+    h = build("c0_tiny", ring_kb=100)
+    st = mk.mk_get_stats(h)
+    assert st["ring_pages"] == 96 and st["page_bytes"] == 1024 and st["n_stage"] == 6
+    assert st["lds_bytes"] <= 160 * 1024 and st["lds_bytes"] >= 96 * 1024
+    mk.mk_schedule_verify(h)
+    blob = mk.mk_schedule_dump(h)
+    h2 = mk.mk_schedule_load(blob)
+    assert mk.mk_get_stats(h2)["ring_pages"] == 96 and mk.mk_schedule_dump(h2) == blob
+    mk.mk_destroy(h); mk.mk_destroy(h2)
+    with pytest.raises(mk.MkError) as e:
+        build("c2_1p5b", ring_kb=144)
+    assert e.value.code == mk.MK_EINFEASIBLE
+    h = build("c2_1p5b", ring_kb=-2)
+    st = mk.mk_get_stats(h)
+    assert st["ring_pages"] % 16 == 0 and st["lds_bytes"] <= 160 * 1024
+    mk.mk_destroy(h)
+    assert mk.mk_get_stats(build("c2_1p5b"))["ring_pages"] == 0     # auto: weights stay out of LDS
 
 
 def test_build_is_deterministic_and_roundtrips():
