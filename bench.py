@@ -138,7 +138,8 @@ def main() -> int:
         "config": {"workload": f"{args.config}: Qwen2.5-1.5B-shaped decoder, batch {B}, KV context {ctx0}+step, "
                                f"{steps} single-launch decode steps", "batch": B, "context0": ctx0,
                    "schedule": {k: dec.stats[k] for k in ("n_workgroups", "split_qkv", "split_o", "split_gateup",
-                                                          "split_down", "attn_chunks", "use_mfma", "lds_bytes")}},
+                                                          "split_down", "attn_chunks", "rows_qkv", "rows_o", "rows_gateup",
+                                                          "rows_down", "rows_head", "use_mfma", "ring_pages", "lds_bytes")}},
         "hbm_gbs_whole_run": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config) if B == 1 else None,

@@ -66,6 +66,8 @@ typedef struct mk_config {
     int32_t split_qkv, split_o, split_gateup, split_down; /* K splits; 0 = search    */
     int32_t attn_chunks;     /* attention tasks per (sequence, KV head); 0 = search  */
     int32_t chunk_rows;      /* rows per 1 KB weight chunk for every matrix (2,4,8,16); 0 = search per matrix */
+    int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head; /* the same per matrix (overrides chunk_rows);
+                              * 0 = chunk_rows / search (the LM head defaults to 16)                              */
     uint32_t spin_limit;     /* dependency-wait poll limit; 0 = library default      */
     uint32_t flags;          /* MK_F_*                                               */
 } mk_config;

@@ -1,0 +1,159 @@
+"""Profile-guided choice of the tiling parameters (paper Sec. 4.2.2 Step 4: candidates are
+scored by offline profiling and the best trace is locked in).
+
+The host-side search of ``mk_build_schedule`` ranks candidates with a pipeline cost model.
+This module closes the loop on the device: starting from the model's choice it walks the tiling
+parameters one at a time (K splits, attention chunking, rows per weight chunk of every matrix),
+builds each candidate schedule, runs a few decode steps of the real workload and keeps what
+measures fastest.  Results are kept in ``tuned.json`` next to this file, keyed by the model shape
+and grid size; ``tuned_opts`` hands them to callers as defaults for ``binding.make_config``.
+
+Only sequencing lives here; every candidate runs through the same C ABI as any other schedule.
+
+    python -m paper_2605_11581_amd.autotune --config c2_1p5b --write
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from typing import Callable, Dict, List, Optional, Tuple
+
+TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned.json")
+
+# parameter -> candidate values, in the order they are walked
+SPACE: List[Tuple[str, List[int]]] = [
+    ("split_o", [1, 2, 4]),
+    ("rows_down", [2, 4, 8, 16]),
+    ("rows_gateup", [4, 8, 16]),
+    ("rows_o", [2, 4, 8, 16]),
+    ("rows_qkv", [2, 4, 8, 16]),
+    ("attn_chunks", [16, 32, 64]),
+    ("split_down", [1, 2, 4]),
+    ("split_qkv", [1, 2]),
+    ("rows_head", [8, 16]),
+]
+_STAT_OF = {"split_o": "split_o", "rows_down": "rows_down", "rows_gateup": "rows_gateup", "rows_o": "rows_o",
+            "rows_qkv": "rows_qkv", "attn_chunks": "attn_chunks", "split_down": "split_down", "split_qkv": "split_qkv",
+            "rows_head": "rows_head", "split_gateup": "split_gateup"}
+
+
+def shape_key(model: Dict, n_workgroups: int) -> str:
+    dims = ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "intermediate", "vocab", "max_batch")
+    return "-".join(str(int(model[k])) for k in dims) + f"-wg{int(n_workgroups)}"
+
+
+def tuned_opts(model: Dict, n_workgroups: int) -> Dict[str, int]:
+    """Tiling overrides recorded for this model shape and grid size ({} if none)."""
+    try:
+        with open(TABLE) as f:
+            table = json.load(f)
+    except OSError:
+        return {}
+    entry = table.get(shape_key(model, n_workgroups))
+    return dict(entry["opts"]) if entry else {}
+
+
+def autotune(model: Dict, dev_weights: Dict, position: int, device: str = "cuda:0", steps: int = 24, warmup: int = 4,
+             rounds: int = 2, base_opts: Optional[Dict] = None, log: Callable[[str], None] = lambda s: None):
+    """Coordinate descent over SPACE with the device as the scorer.  ``dev_weights``: tensors already
+    on ``device`` (see runtime.stage_weights).  Returns (best overrides, best ms per step, history)."""
+    import torch
+    from . import binding as mk
+    from .runtime import Decoder
+
+    base_opts = dict(base_opts or {})
+    B = int(model["max_batch"])
+    tok = torch.full((B,), 17, dtype=torch.int32, device=device)
+    pos = torch.full((B,), int(position), dtype=torch.int32, device=device)
+    logits = torch.empty(B, model["vocab"], dtype=torch.float32, device=device)
+    history = []
+
+    def measure(opts: Dict) -> Optional[float]:
+        try:
+            dec = Decoder(model, device=device, **base_opts, **opts)
+        except mk.MkError as e:
+            if e.code in (mk.MK_EINFEASIBLE, mk.MK_EINVAL):
+                return None
+            raise
+        try:
+            dec.load_weights(dev_weights)
+            kv = dec.new_kv()
+            for _ in range(warmup):
+                dec.step(tok, pos, kv, logits)
+            dec.check()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(steps):
+                dec.step(tok, pos, kv, logits)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t) * 1e3 / steps
+            dec.check()
+            return ms
+        finally:
+            dec.close()
+
+    # start from what the cost model picks, with every searched parameter pinned to that choice
+    dec0 = Decoder(model, device=device, ring_kb=-1, **base_opts)   # naming a tiling key bypasses recorded choices
+    st = dec0.stats
+    dec0.close()
+    best = {k: int(st[_STAT_OF[k]]) for k, _ in SPACE}
+    best_ms = measure(best)
+    log(f"start {best} -> {best_ms:.4f} ms")
+    history.append((dict(best), best_ms))
+    for r in range(rounds):
+        improved = False
+        for name, values in SPACE:
+            for v in values:
+                if v == best[name]:
+                    continue
+                cand = dict(best)
+                cand[name] = v
+                ms = measure(cand)
+                history.append((cand, ms))
+                log(f"round {r} {name}={v}: " + ("infeasible" if ms is None else f"{ms:.4f} ms"))
+                if ms is not None and ms < best_ms * 0.997:   # 0.3 % guard against timer noise
+                    best, best_ms, improved = cand, ms, True
+        if not improved:
+            break
+    return best, best_ms, history
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="c2_1p5b")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=24)
+    ap.add_argument("--rounds", type=int, default=2)
+    ap.add_argument("--write", action="store_true", help="record the result in tuned.json")
+    args = ap.parse_args()
+    import torch
+    from . import synth
+    from .runtime import stage_weights
+
+    full = synth.CONFIGS[args.config]
+    model = synth.model_cfg(full, max_batch=args.batch, max_context=full["ctx0"] + 512)
+    dev = "cuda:0"
+    w = stage_weights(synth.make_weights(full), dev)
+    n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+    pos = full["ctx0"] + 128
+    best, ms, hist = autotune(model, w, pos, device=dev, steps=args.steps, rounds=args.rounds,
+                              log=lambda s: print(s, flush=True))
+    print(json.dumps({"config": args.config, "key": shape_key(model, n_wg), "opts": best, "ms_per_step": round(ms, 5)}))
+    if args.write:
+        try:
+            table = json.load(open(TABLE))
+        except OSError:
+            table = {}
+        table[shape_key(model, n_wg)] = {"opts": best, "ms_per_step": round(ms, 5), "position": pos,
+                                         "workload": args.config, "candidates_timed": len(hist)}
+        with open(TABLE, "w") as f:
+            json.dump(table, f, indent=1, sort_keys=True)
+            f.write("\n")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

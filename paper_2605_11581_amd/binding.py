@@ -31,7 +31,8 @@ class mk_config(C.Structure):
                                          "intermediate", "vocab", "qkv_bias", "qk_norm", "tie_embeddings")] + [
         ("rope_theta", C.c_float), ("rms_eps", C.c_float)] + [
         (n, C.c_int32) for n in ("max_batch", "max_context", "n_workgroups", "device_id", "use_mfma", "ring_kb",
-                                 "split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows")] + [
+                                 "split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows",
+                                 "rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head")] + [
         ("spin_limit", C.c_uint32), ("flags", C.c_uint32)]
 
 
@@ -115,7 +116,8 @@ def _chk(rc: int) -> None:
 
 
 _CFG_DEFAULTS = dict(n_workgroups=0, device_id=0, use_mfma=-1, ring_kb=-1, split_qkv=0, split_o=0, split_gateup=0,
-                     split_down=0, attn_chunks=0, chunk_rows=0, spin_limit=0, flags=0)
+                     split_down=0, attn_chunks=0, chunk_rows=0, rows_qkv=0, rows_o=0, rows_gateup=0, rows_down=0,
+                     rows_head=0, spin_limit=0, flags=0)
 
 
 def make_config(model: Dict, **opts) -> mk_config:

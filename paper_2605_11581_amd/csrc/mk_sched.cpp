@@ -587,10 +587,21 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     // rows per weight chunk: the matrix-core path needs 16; the VALU path may trade rows for K
     std::vector<int> c_r = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2, 1};
     std::vector<int> c_rgu = mfma ? std::vector<int>{4} : std::vector<int>{4, 3, 2};
+    auto rows_log = [](int rows) { return rows == 2 ? 1 : rows == 4 ? 2 : rows == 8 ? 3 : rows == 16 ? 4 : -1; };
     if (cfg.chunk_rows) {
-        int rl = cfg.chunk_rows == 2 ? 1 : cfg.chunk_rows == 4 ? 2 : cfg.chunk_rows == 8 ? 3 : cfg.chunk_rows == 16 ? 4 : -1;
+        int rl = rows_log(cfg.chunk_rows);
         if (rl < 0 || (mfma && rl != 4)) { set_error("mk_config: chunk_rows must be 2, 4, 8 or 16 (16 on the matrix-core path)"); return MK_EINVAL; }
         c_r = {rl}; c_rgu = {rl};
+    }
+    // per-matrix overrides
+    std::vector<int> c_rq = c_r, c_ro = c_r, c_rd = c_r, c_rh = {cfg.chunk_rows ? c_r[0] : 4};
+    struct RowOpt { int rows; std::vector<int> *dst; int min_log; };
+    for (RowOpt o : {RowOpt{cfg.rows_qkv, &c_rq, 1}, RowOpt{cfg.rows_o, &c_ro, 1}, RowOpt{cfg.rows_gateup, &c_rgu, 1},
+                     RowOpt{cfg.rows_down, &c_rd, 1}, RowOpt{cfg.rows_head, &c_rh, 1}}) {
+        if (!o.rows) continue;
+        int rl = rows_log(o.rows);
+        if (rl < o.min_log || (mfma && rl != 4)) { set_error("mk_config: rows_* must be 2, 4, 8 or 16 (16 on the matrix-core path)"); return MK_EINVAL; }
+        *o.dst = {rl};
     }
     std::vector<int> c_nc;
     if (cfg.attn_chunks > 0) c_nc.push_back(cfg.attn_chunks);
@@ -615,7 +626,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     // coordinate descent over the tiling parameters, each candidate scored by the simulator
     Tiling best{};
     best.s_qkv = c_sqkv[0]; best.s_o = c_so[0]; best.s_gu = c_sgu[0]; best.s_d = c_sd[0];
-    best.r_qkv = best.r_o = best.r_gu = best.r_d = c_r[0]; best.r_head = cfg.chunk_rows ? c_r[0] : 4;
+    best.r_qkv = c_rq[0]; best.r_o = c_ro[0]; best.r_gu = c_rgu[0]; best.r_d = c_rd[0]; best.r_head = c_rh[0];
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
     // weight-page ring: a pipeline stage is 16 pages (4 per wavefront).  The depth is only searched
@@ -639,8 +650,8 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
         return true;
     };
     struct Dim { int Tiling::*field; std::vector<int> *vals; };
-    Dim dimsv[] = {{&Tiling::r_qkv, &c_r}, {&Tiling::s_qkv, &c_sqkv}, {&Tiling::r_o, &c_r}, {&Tiling::s_o, &c_so},
-                   {&Tiling::r_gu, &c_rgu}, {&Tiling::s_gu, &c_sgu}, {&Tiling::r_d, &c_r}, {&Tiling::s_d, &c_sd},
+    Dim dimsv[] = {{&Tiling::r_qkv, &c_rq}, {&Tiling::s_qkv, &c_sqkv}, {&Tiling::r_o, &c_ro}, {&Tiling::s_o, &c_so},
+                   {&Tiling::r_gu, &c_rgu}, {&Tiling::s_gu, &c_sgu}, {&Tiling::r_d, &c_rd}, {&Tiling::s_d, &c_sd},
                    {&Tiling::nc, &c_nc}, {&Tiling::ring_pages, &c_ring}};
     {
         double ms, du;
@@ -951,7 +962,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 2;
+constexpr uint32_t kVersion = 3;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)

@@ -11,32 +11,51 @@ import torch
 from . import binding as mk
 
 
-def _dev_bits(a: np.ndarray, device) -> torch.Tensor:
+def _dev_bits(a, device) -> torch.Tensor:
+    if isinstance(a, torch.Tensor):
+        return a
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
+
+
+def stage_weights(w: Dict, device) -> Dict:
+    """Upload host weights (numpy uint16 bf16 bit patterns; per-layer entries are lists) once, for
+    callers that load the same tensors into several schedules."""
+    dev: Dict = {}
+    for k, v in w.items():
+        if v is None:
+            dev[k] = None
+        elif isinstance(v, (list, tuple)):
+            dev[k] = [_dev_bits(a, device) for a in v]
+        else:
+            dev[k] = _dev_bits(v, device)
+    return dev
+
+
+_TILING_KEYS = {"split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows", "rows_qkv", "rows_o",
+                "rows_gateup", "rows_down", "rows_head", "ring_kb", "use_mfma"}
 
 
 class Decoder:
     def __init__(self, model: Dict, device: str = "cuda:0", schedule_blob: Optional[bytes] = None, **opts):
+        """Tiling parameters not given in ``opts`` come from the offline search; when ``opts`` names
+        none at all, the profile-guided choices recorded for this shape (autotune.py) are applied."""
         self.device = torch.device(device)
         self.model = dict(model)
         if schedule_blob is not None:
             self.h = mk.mk_schedule_load(schedule_blob)
         else:
+            if not (_TILING_KEYS & set(opts)):
+                from .autotune import tuned_opts
+                n_wg = opts.get("n_workgroups") or torch.cuda.get_device_properties(self.device).multi_processor_count
+                opts = {**tuned_opts(model, n_wg), **opts}
             self.h = mk.mk_build_schedule(mk.make_config(model, device_id=self.device.index or 0, **opts))
         self.stats = mk.mk_get_stats(self.h)
         self.workspace = torch.empty(mk.mk_workspace_bytes(self.h), dtype=torch.uint8, device=self.device)
         mk.mk_bind_workspace(self.h, self.workspace)
 
     def load_weights(self, w: Dict) -> None:
-        """``w``: numpy uint16 bf16 bit patterns (per-layer entries are lists); staged layer by layer."""
-        dev: Dict = {}
-        for k, v in w.items():
-            if v is None:
-                dev[k] = None
-            elif isinstance(v, (list, tuple)):
-                dev[k] = [_dev_bits(a, self.device) for a in v]
-            else:
-                dev[k] = _dev_bits(v, self.device)
+        """``w``: numpy uint16 bf16 bit patterns or int16 device tensors (per-layer entries are lists)."""
+        dev = stage_weights(w, self.device)
         mk.mk_load_weights(self.h, dev)
         torch.cuda.synchronize(self.device)   # the staged copies may be freed now
 

@@ -127,6 +127,31 @@ def test_page_ring_obeys_the_lds_budget():
     assert mk.mk_get_stats(build("c2_1p5b"))["ring_pages"] == 0     # auto: weights stay out of LDS
 
 
+def test_recorded_profile_guided_tilings_build_and_verify():
+    """Every entry of the tuned table (written by the on-device search) names its shape by the key
+    the runtime looks up, and its overrides give a schedule that passes verification."""
+    import json
+    from paper_2605_11581_amd import autotune
+    table = json.load(open(autotune.TABLE))
+    assert table, "tuned.json is empty"
+    by_key = {}
+    for name, full in synth.CONFIGS.items():
+        for b in (1, 2, 4, 8):
+            by_key[autotune.shape_key(synth.model_cfg(full, max_batch=b), 256)] = (name, b)
+    for key, entry in table.items():
+        assert key in by_key, f"{key} matches no known configuration"
+        name, b = by_key[key]
+        model = synth.model_cfg(synth.CONFIGS[name], max_batch=b)
+        assert autotune.tuned_opts(model, 256) == entry["opts"]
+        h = mk.mk_build_schedule(mk.make_config(model, n_workgroups=256, **entry["opts"]))
+        mk.mk_schedule_verify(h)
+        st = mk.mk_get_stats(h)
+        for k, v in entry["opts"].items():
+            assert st[k] == v, (key, k)
+        mk.mk_destroy(h)
+    assert autotune.tuned_opts(synth.model_cfg(synth.CONFIGS["c0_tiny"]), 7) == {}
+
+
 def test_build_is_deterministic_and_roundtrips():
     h1, h2 = build("c0_tiny"), build("c0_tiny")
     b1, b2 = mk.mk_schedule_dump(h1), mk.mk_schedule_dump(h2)
