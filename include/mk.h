@@ -163,10 +163,21 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream);
  *   token_ids, positions : dev int32 [batch]; 0 <= id < vocab, 0 <= pos < max_context
  *     (the kernel clamps out-of-range values and raises the error flag)
  *   kv_cache  : dev bf16 [n_layers][2][max_batch][n_kv_heads][max_context][head_dim]
- *   logits_out: dev fp32 [batch][vocab]
- *   next_token_out : dev int32 [batch] or NULL; unused by this entry point (reserved) */
+ *   logits_out: dev fp32 [batch][vocab] */
 int mk_decode_step(mk_schedule *s, const int32_t *token_ids, const int32_t *positions,
                    void *kv_cache, float *logits_out, int32_t batch, void *stream);
+
+/* n_steps greedy decode steps as ONE persistent kernel launch (the kernel stays resident and walks
+ * its instruction lists once per step; nothing returns to the host in between).  Step 0 decodes
+ * token_ids at positions; step s > 0 decodes the arg-max token of step s-1 (first maximum, i.e. the
+ * smallest row among equal logits) at positions + s.  Steps are ordered on the device by the
+ * dependency counter of the arg-max tasks that close every step.
+ *   tokens_out : dev int32 [n_steps][batch], the greedy token chosen by every step
+ *   logits_out : dev fp32 [batch][vocab], holds the LAST step's logits when the launch ends
+ *   positions[b] + n_steps - 1 must stay below max_context (otherwise clamped, error flag raised)
+ * Other arguments as for mk_decode_step. */
+int mk_decode_steps(mk_schedule *s, const int32_t *token_ids, const int32_t *positions, void *kv_cache,
+                    float *logits_out, int32_t *tokens_out, int32_t batch, int32_t n_steps, void *stream);
 
 /* Baseline with the same device task bodies and the same instruction lists,
  * but one kernel launch per DAG operator (stream order supplies the

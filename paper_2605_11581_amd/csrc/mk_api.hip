@@ -45,11 +45,13 @@ uint32_t dbg_knob(const char *name, uint32_t dflt, uint32_t lo, uint32_t hi)
 }
 
 mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv,
-                       float *logits, int batch)
+                       float *logits, int batch, int32_t *next_tokens = nullptr, int n_steps = 1)
 {
     mk::Params P{};
     P.ws = s->ws; P.lay = s->lay;
     P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
+    P.next_tokens = next_tokens ? next_tokens : (int32_t *)(s->ws + s->lay.tokens);
+    P.n_steps = n_steps; P.amax = s->am.amax;
     P.batch = batch; P.max_batch = s->dm.Bm; P.max_context = s->dm.Tm;
     P.n_layers = s->dm.L; P.hidden = s->dm.H; P.n_q_heads = s->dm.nq; P.n_kv_heads = s->dm.nkv;
     P.head_dim = s->dm.d; P.inter_pad = s->gm.ipad; P.vocab = s->dm.V;
@@ -334,18 +336,16 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
     return MK_OK;
 }
 
-int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
-                   int32_t batch, void *stream)
+static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                        int32_t *next_tokens, int32_t batch, int32_t n_steps, hipStream_t st)
 {
-    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
-    if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    if (s->epoch >= 0x00800000u) {   // keep epoch * signals far from wrapping
-        rc = reset_sync_state(s, st);
+    if ((uint64_t)s->epoch + (uint64_t)n_steps >= 0x00800000u) {   // keep epoch * signals far from wrapping
+        int rc = reset_sync_state(s, st);
         if (rc) return rc;
     }
-    s->epoch += 1;
-    mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
+    mk::Params P = make_params(s, tokens, positions, kv, logits, batch, next_tokens, n_steps);
+    P.epoch = s->epoch + 1;
+    s->epoch += (uint32_t)n_steps;
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
@@ -356,6 +356,24 @@ int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positio
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
     return MK_OK;
+}
+
+int mk_decode_step(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                   int32_t batch, void *stream)
+{
+    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
+    if (rc) return rc;
+    return launch_steps(s, tokens, positions, kv, logits, nullptr, batch, 1, (hipStream_t)stream);
+}
+
+int mk_decode_steps(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                    int32_t *tokens_out, int32_t batch, int32_t n_steps, void *stream)
+{
+    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
+    if (rc) return rc;
+    if (!tokens_out) { mk::set_error("null device pointer"); return MK_EINVAL; }
+    if (n_steps < 1 || n_steps > s->dm.Tm) { mk::set_error("n_steps outside 1..max_context"); return MK_EINVAL; }
+    return launch_steps(s, tokens, positions, kv, logits, tokens_out, batch, n_steps, (hipStream_t)stream);
 }
 
 int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,

@@ -36,10 +36,10 @@ constexpr int kLdsInstr = 0;
 constexpr int kLdsMisc = 256;
 constexpr int kLdsRed = 512;
 
-enum Op : uint32_t { OP_END = 0, OP_GEMV = 1, OP_ATT = 2, OP_COMB = 3 };
+enum Op : uint32_t { OP_END = 0, OP_GEMV = 1, OP_ATT = 2, OP_COMB = 3, OP_ARGMAX = 4 };
 
 // stage of an operator instance inside a layer; ref_seq = layer * 8 + stage
-enum Stage : uint32_t { ST_QKV = 0, ST_ATT = 1, ST_COMB = 2, ST_O = 3, ST_GU = 4, ST_DOWN = 5, ST_HEAD = 6 };
+enum Stage : uint32_t { ST_QKV = 0, ST_ATT = 1, ST_COMB = 2, ST_O = 3, ST_GU = 4, ST_DOWN = 5, ST_HEAD = 6, ST_ARGMAX = 7 };
 
 enum Pro : uint32_t {
     PRO_EMBED_NORM = 0,  // x = embedding row; store slice; RMSNorm
@@ -53,7 +53,10 @@ enum Flags : uint32_t {
     F_MFMA = 2u,        // matrix-core GEMV/thin GEMM instead of VALU FMA
     F_LOGITS = 4u,      // output goes to the caller's logits buffer
     F_ADD_RESID = 8u,   // epilogue adds the residual row (needs S == 1): out = resid + W x
-    F_SILU_EPI = 16u    // epilogue of the fused gate/up matrix (needs S == 1): out = silu(gate) * up
+    F_SILU_EPI = 16u,   // epilogue of the fused gate/up matrix (needs S == 1): out = silu(gate) * up
+    F_ARGMAX = 32u,     // LM-head task: also leave (max logit, its row) per sequence in partial slot `spare`
+    F_WAIT_PREV = 64u   // wait_ctr[0] is awaited at the PREVIOUS step's target: the first tasks of a step wait
+                        // for the greedy token (and with it for every task) of the step before
 };
 
 // Weight chunk geometry.  A chunk is one wavefront-wide 128-bit load (1 KB): R rows x (512 / R)
@@ -92,7 +95,7 @@ struct Instr {                 // 32 dwords
     uint32_t out_ld;           // 28  floats between sequences of the output
     uint32_t bias;             // 29  bf16 element offset of the bias or kNone
     uint32_t k_len;            // 30  true K (input elements beyond it are zero)
-    uint32_t spare;            // 31
+    uint32_t spare;            // 31  F_ARGMAX: slot of this task in the arg-max partial buffer
 };
 __host__ __device__ inline uint32_t instr_pro(const Instr &I) { return I.cfg & 15u; }
 __host__ __device__ inline uint32_t instr_rlog(const Instr &I) { return (I.cfg >> 4) & 15u; }
@@ -120,7 +123,8 @@ struct InstrAtt {
     uint32_t h0, nh;           // 21,22 COMB: first q head and number of q heads to combine
     uint32_t o_out;            // 23  COMB: float offset of o[b][nq*d]
     uint32_t o_ld;             // 24
-    uint32_t pad[7];
+    uint32_t n_slots;          // 25  ARGMAX: partial slots to reduce (one per LM-head task)
+    uint32_t pad[6];
 };
 static_assert(sizeof(Instr) == kInstrDwords * 4, "instruction size");
 static_assert(sizeof(InstrAtt) == kInstrDwords * 4, "instruction size");
@@ -135,6 +139,7 @@ struct Layout {
     uint64_t instr;      // Instr[n_wg][max_instr]
     uint64_t err;        // uint32[8] sticky error flags
     uint64_t trace;      // uint64[n_wg][max_instr][8]: task begin, dependencies met, prologue done, end, 4 task-internal marks
+    uint64_t tokens;     // int32[max_batch]: greedy token of the latest step (single-step entry point)
     uint64_t stream;     // uint32[n_wg][max_instr][2]: weight stream of a workgroup, one (first chunk, chunk count) per GEMV
                          // task in list order, closed by (kNone, kNone); derived from the instruction lists at bind time
     uint64_t total;
@@ -147,6 +152,9 @@ struct Params {
     const int32_t *positions;
     uint16_t *kv;
     float *logits;
+    int32_t *next_tokens;   // [n_steps][batch] greedy tokens, written by the arg-max task of every step
+    int32_t n_steps;        // decode steps walked by this launch (token of step s+1 = arg-max of step s)
+    uint32_t amax;          // float offset of the arg-max partials [slot][max_batch][2] in the activation region
     int32_t batch, max_batch, max_context;
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, inter_pad, vocab;
     int32_t qk_norm;

@@ -59,10 +59,18 @@ struct Wg {
     uint32_t head, tail;  // chunks this wave has issued / read back
     uint32_t hst, tst;    // stage the next group is loaded into / read from
     cptr pf_ptr;          // next entry of the workgroup's stream table
-    uint32_t pf_left;     // table entries not yet read (bounds the walk)
+    cptr pf_begin;        // first entry (the stream repeats once per decode step of the launch)
+    uint32_t pf_steps;    // steps whose stream has not been started yet
+    uint32_t pf_left;     // table entries not yet read in this pass (bounds the walk)
     const char *pf_src;   // address of this wave's next chunk in the current entry
     uint32_t pf_rem;      // chunks of the current entry this wave has not issued yet
     bool pf_live;
+    // ---- the decode step this walk of the list belongs to (a launch may walk the list several times)
+    uint32_t epoch;             // dependency-counter epoch of the step
+    int pos_off;                // added to the caller's positions: steps done so far in this launch
+    const int32_t *tok_src;     // tokens decoded by this step: the caller's, or the previous step's greedy tokens
+    int32_t *tok_out;           // where this step's greedy tokens go
+    float *logits;              // where this step's logits go
 };
 
 __device__ __forceinline__ void wg_sync(Wg &, char *) { __syncthreads(); }
@@ -150,15 +158,18 @@ __device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t targe
 
 __device__ __forceinline__ int clamp_i(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-__device__ __forceinline__ int token_of(const Params &P, int b)
+// Tokens may have been written by another workgroup earlier in the same launch (greedy feedback):
+// read them past the caches, like every other cross-workgroup value.
+__device__ __forceinline__ int token_of(const Params &P, const Wg &wg, int b)
 {
-    int t = (int)rfl((uint32_t)P.tokens[b]);
+    typedef const __attribute__((address_space(1))) uint32_t *gptr;
+    int t = (int)rfl(__hip_atomic_load((gptr)(uintptr_t)(wg.tok_src + b), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     if (t < 0 || t >= P.vocab) { set_err(P, 1, 1u); t = clamp_i(t, 0, P.vocab - 1); }
     return t;
 }
-__device__ __forceinline__ int position_of(const Params &P, int b)
+__device__ __forceinline__ int position_of(const Params &P, const Wg &wg, int b)
 {
-    int p = (int)rfl((uint32_t)P.positions[b]);
+    int p = (int)rfl((uint32_t)P.positions[b]) + wg.pos_off;
     if (p < 0 || p >= P.max_context) { set_err(P, 1, 2u); p = clamp_i(p, 0, P.max_context - 1); }
     return p;
 }
@@ -192,6 +203,17 @@ __device__ __forceinline__ f32x4 ld_act4(const ActBuf &a, uint32_t float_off)
 __device__ __forceinline__ void st_act4(const ActBuf &a, uint32_t float_off, f32x4 v)
 {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), a.r, (int)(float_off * 4u), 0, kAuxSc1);
+}
+
+// (value, index) maximum over a wavefront; equal values keep the smaller index.  All lanes end with the result.
+__device__ __forceinline__ void argmax_wave(float &v, uint32_t &i)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float ov = __shfl_xor(v, o, 64);
+        const uint32_t oi = (uint32_t)__shfl_xor((int)i, o, 64);
+        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+    }
 }
 
 // ---------------------------------------------------------------- GEMV task
@@ -238,7 +260,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         for (int b = 0; b < batch; ++b) {
             f32x4 v[kQuadsPerThread];
             if (pro == PRO_EMBED_NORM) {
-                const int tok = token_of(P, b);
+                const int tok = token_of(P, lp, b);
 #pragma unroll
                 for (int j = 0; j < kQuadsPerThread; ++j) {
                     const int q = tid + j * kWgThreads;
@@ -416,7 +438,7 @@ __device__ __forceinline__ void vm_wait4(uint32_t k4)
         "s_waitcnt vmcnt(56)\n\ts_branch .Lvmw_%=\n\t"
         "s_waitcnt vmcnt(60)\n\ts_branch .Lvmw_%=\n"
         ".Lvmw_%=:"
-        : "=&s"(tmp) : "s"(k4) : "memory", "vcc", "scc");
+        : "=&s"(tmp) : "s"(rfl(k4)) : "memory", "vcc", "scc");
 }
 
 // One 128-bit global->LDS DMA load of a 1 KB chunk: lane l's 16 bytes land at dst + 16 l.  Written
@@ -424,18 +446,25 @@ __device__ __forceinline__ void vm_wait4(uint32_t k4)
 // wave's LDS reads against the DMA queue; the ring code waits for landing itself (vm_wait4).
 __device__ __forceinline__ void dma_chunk(uint32_t dst_lds, const char *src, uint32_t lane_off)
 {
+    // the operands are wave-uniform by construction; readfirstlane pins them to scalar registers
+    const uint64_t a = (uint64_t)(uintptr_t)src;
+    const uint64_t src_s = (uint64_t)rfl((uint32_t)a) | ((uint64_t)rfl((uint32_t)(a >> 32)) << 32);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-                 ::"s"(dst_lds), "v"(lane_off), "s"(src) : "memory", "m0");
+                 ::"s"(rfl(dst_lds)), "v"(lane_off), "s"(src_s) : "memory", "m0");
 }
 
 // Move the stream cursor to the next table entry that holds chunks of this wave (rare path).
 __device__ __forceinline__ void ring_advance(const Params &P, Wg &wg)
 {
     while (wg.pf_live && wg.pf_rem == 0) {
-        if (wg.pf_left == 0) { wg.pf_live = false; break; }
-        const uint32_t base = wg.pf_ptr[0], total = wg.pf_ptr[1];
+        const uint32_t base = wg.pf_left ? wg.pf_ptr[0] : kNone, total = wg.pf_left ? wg.pf_ptr[1] : kNone;
+        if (total == kNone) {   // end of the step's stream: start over for the next step, if any
+            if (wg.pf_steps == 0) { wg.pf_live = false; break; }
+            --wg.pf_steps;
+            wg.pf_ptr = wg.pf_begin; wg.pf_left = P.max_instr;
+            continue;
+        }
         wg.pf_ptr += 2; --wg.pf_left;
-        if (total == kNone) { wg.pf_live = false; break; }
         if (total > wg.wave) {
             wg.pf_rem = (total - wg.wave + kWaves - 1) / kWaves;
             wg.pf_src = P.ws + P.lay.weights + ((size_t)base + wg.wave) * kChunkBytes;
@@ -688,10 +717,40 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             if (I.bias != kNone && s == 0 && row < I.n_rows)
                 v += bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
             if (I.flags & F_LOGITS) {
-                if (row < I.n_rows) P.logits[(size_t)b * P.vocab + row] = v;
+                if (row < I.n_rows) lp.logits[(size_t)b * P.vocab + row] = v;
+                // this thread is the only reader of index t of the reduction area: keep the finished
+                // logit there for the arg-max pass below
+                if (I.flags & F_ARGMAX) red[t] = row < I.n_rows ? v : -INFINITY;
             } else {
                 if (I.flags & F_ADD_RESID) v += ld_act(actw + I.resid + (size_t)b * I.out_ld + row);
                 st_act(actw + I.out + (size_t)s * I.out_split_stride + (size_t)b * I.out_ld + row, v);
+            }
+        }
+        if (I.flags & F_ARGMAX) {
+            // (max logit, its row) of this task per sequence; ties go to the smaller row
+            float *sv = (float *)(lds + kLdsMisc + 64);
+            uint32_t *si = (uint32_t *)(lds + kLdsMisc + 80);
+            for (uint32_t b = 0; b < nb; ++b) {
+                wg_sync(lp, lds);
+                float bv = -INFINITY;
+                uint32_t bi = 0xffffffffu;
+                for (uint32_t t = tid; t < red_per_wave; t += kWgThreads) {
+                    const uint32_t ub = t >> rlog;
+                    if (ub % nb != b) continue;
+                    const float v = red[t];
+                    const uint32_t row = ((u0 + ub / nb) / S) * R + (t & (R - 1));
+                    if (v > bv || (v == bv && row < bi)) { bv = v; bi = row; }
+                }
+                argmax_wave(bv, bi);
+                if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+                wg_sync(lp, lds);
+                if (tid == 0) {
+                    for (int w = 1; w < kWaves; ++w)
+                        if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+                    float *dst = actw + P.amax + ((size_t)I.spare * P.max_batch + b) * 2;
+                    st_act(dst, bv);
+                    st_act(dst + 1, __uint_as_float(bi));
+                }
             }
         }
     }
@@ -744,7 +803,7 @@ __device__ __forceinline__ int att_pos(int idx, int bs, int nc, int c)
 }
 
 template <int D>
-__device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, AttStream &st)
+__device__ __forceinline__ void att_issue(const Params &P, const Wg &lp, const InstrAtt &I, AttStream &st)
 {
     constexpr int LPP = D / 8, PPW = 64 / LPP;
     typedef const __attribute__((address_space(1))) u32x4 *gp;
@@ -752,7 +811,7 @@ __device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, At
     const int b = (int)I.b, g = (int)I.g;
     st.npos = 0; st.p = 0; st.sub = lane / LPP;
     if (b >= P.batch) return;
-    const int p = position_of(P, b);
+    const int p = position_of(P, lp, b);
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
     const int nblk_all = (p + bs - 1) >> kAttBlockLog;            // blocks containing positions < p
     const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
@@ -765,9 +824,11 @@ __device__ __forceinline__ void att_issue(const Params &P, const InstrAtt &I, At
 #pragma unroll
     for (int j = 0; j < kAttPrefetch; ++j) {
         const int grp = (wave + j * kWaves) * PPW;
-        // clamped to a valid row: rows at or beyond p are masked when consumed
+        // Rows at or beyond p are masked when consumed; their loads go to the last history row instead,
+        // so that no cache ever holds a line of a row before the step that appends it has written it
+        // (steps of one launch follow each other without a cache invalidate).
         int t = att_pos(grp + st.sub, bs, nc, c);
-        t = t < P.max_context ? t : P.max_context - 1;
+        t = t < p ? t : p - 1;
         st.kbuf[j] = u32x4{0u, 0u, 0u, 0u};
         st.vbuf[j] = u32x4{0u, 0u, 0u, 0u};
         if (grp < st.npos) {
@@ -849,18 +910,22 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                 sq[vi * D + i + D / 2] = c2 * scale;
             } else {
                 const int which = vi - G;  // 0 = K, 1 = V
-                uint16_t h0 = f_to_bf(a), h1 = f_to_bf(c2);
-                size_t base = ((((size_t)I.layer * 2 + which) * P.max_batch + b) * P.n_kv_heads + g) *
-                                  (size_t)P.max_context * D + (size_t)p * D;
-                P.kv[base + i] = h0;
-                P.kv[base + i + D / 2] = h1;
-                snew[which * D + i] = bf_to_f(h0);
-                snew[which * D + i + D / 2] = bf_to_f(h1);
+                snew[which * D + i] = bf_to_f(f_to_bf(a));
+                snew[which * D + i + D / 2] = bf_to_f(f_to_bf(c2));
             }
         }
     }
     wg_sync(lp, lds);
     trace_mark(P, pc, 0);
+    // append the new K and V rows (bf16 pairs, write-through: the next step of the same launch reads them)
+    if (owner && tid < D) {
+        typedef __attribute__((address_space(1))) uint32_t *gptr;
+        const int which = tid / (D / 2), j = tid % (D / 2);
+        const size_t base = ((((size_t)I.layer * 2 + which) * P.max_batch + b) * P.n_kv_heads + g) *
+                                (size_t)P.max_context * D + (size_t)p * D;
+        const uint32_t pk = (uint32_t)f_to_bf(snew[which * D + 2 * j]) | ((uint32_t)f_to_bf(snew[which * D + 2 * j + 1]) << 16);
+        __hip_atomic_store((gptr)(uintptr_t)(P.kv + base + 2 * j), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     // ---- main loop over this task's history positions (t < p)
     const int sub = as.sub, dl = lane % LPP;   // position inside the load, 8-dim slice
@@ -933,7 +998,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                 const int ngrp = (base + wave + (j0 + u) * kWaves) * PPW + kAttPrefetch * kWaves * PPW;
                 if (ngrp < npos) {
                     int t = att_pos(ngrp + sub, bs, nc, c);
-                    t = t < P.max_context ? t : P.max_context - 1;
+                    t = t < p ? t : p - 1;
                     as.kbuf[j0 + u] = __builtin_nontemporal_load(as.kp + (size_t)t * LPP);
                     as.vbuf[j0 + u] = __builtin_nontemporal_load(as.vp + (size_t)t * LPP);
                 }
@@ -1051,6 +1116,44 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
     }
 }
 
+// Greedy token of sequence b: reduce the (max logit, row) partials the LM-head tasks left, in slot
+// order (ties: smaller row, i.e. the first maximum), and hand the row to the caller and to the
+// next step of this launch.
+__device__ __forceinline__ void argmax_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp)
+{
+    const int b = (int)I.b, tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
+    if (b >= P.batch) return;
+    const float *part = (const float *)(P.ws + P.lay.act) + I.out;
+    float bv = -INFINITY;
+    uint32_t bi = 0xffffffffu;
+    for (uint32_t s0 = tid; s0 < I.n_slots; s0 += kWgThreads * 4) {
+        float v[4], x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t sl = min(s0 + u * kWgThreads, I.n_slots - 1);
+            v[u] = ld_act(part + ((size_t)sl * P.max_batch + b) * 2);
+            x[u] = ld_act(part + ((size_t)sl * P.max_batch + b) * 2 + 1);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t row = __float_as_uint(x[u]);
+            if (s0 + u * kWgThreads < I.n_slots && (v[u] > bv || (v[u] == bv && row < bi))) { bv = v[u]; bi = row; }
+        }
+    }
+    argmax_wave(bv, bi);
+    float *sv = (float *)(lds + kLdsMisc + 64);
+    uint32_t *si = (uint32_t *)(lds + kLdsMisc + 80);
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    wg_sync(lp, lds);
+    if (tid == 0) {
+        for (int w = 1; w < kWaves; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        if (bi >= (uint32_t)P.vocab) bi = 0;   // no finite logit at all
+        typedef __attribute__((address_space(1))) uint32_t *gptr;
+        __hip_atomic_store((gptr)(uintptr_t)(lp.tok_out + b), bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // ---------------------------------------------------------------- interpreter
 __device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, uint32_t *slot)
 {
@@ -1074,8 +1177,8 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     AttStream as;
     if (I.op == OP_GEMV) gemv_issue<RING>(P, I, st, lp.npf);
     else if (I.op == OP_ATT) {
-        if (P.head_dim == 128) att_issue<128>(P, *(const InstrAtt *)&I, as);
-        else att_issue<64>(P, *(const InstrAtt *)&I, as);
+        if (P.head_dim == 128) att_issue<128>(P, lp, *(const InstrAtt *)&I, as);
+        else att_issue<64>(P, lp, *(const InstrAtt *)&I, as);
     }
 
     if (PERSISTENT && I.op == OP_GEMV) trace_mark(P, pc, 0);
@@ -1084,10 +1187,11 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
             uint32_t ok = 1, polls = 0;
             if (waiting) {
                 if (I.wait_ctr[0] != kNone)
-                    ok = wait_counter(counters + (size_t)I.wait_ctr[0] * P.ctr_stride, P.epoch * I.wait_cnt[0],
+                    ok = wait_counter(counters + (size_t)I.wait_ctr[0] * P.ctr_stride,
+                                      (lp.epoch - ((I.flags & F_WAIT_PREV) ? 1u : 0u)) * I.wait_cnt[0],
                                       P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
                 if (ok && I.wait_ctr[1] != kNone)
-                    ok = wait_counter(counters + (size_t)I.wait_ctr[1] * P.ctr_stride, P.epoch * I.wait_cnt[1],
+                    ok = wait_counter(counters + (size_t)I.wait_ctr[1] * P.ctr_stride, lp.epoch * I.wait_cnt[1],
                                       P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
             }
             if (!ok) set_err(P, 0, 1u + pc);
@@ -1123,6 +1227,8 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         else att_task<64>(P, A, lds, lp, as, pc);
     } else if (I.op == OP_COMB) {
         comb_task(P, *(const InstrAtt *)&I, lds, lp);
+    } else if (I.op == OP_ARGMAX) {
+        argmax_task(P, *(const InstrAtt *)&I, lds, lp);
     }
 
     if (PERSISTENT && I.sig_ctr != kNone) {
@@ -1158,8 +1264,10 @@ __device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *l
     wg.ring_off = p.ring_off + wg.wave * wg.nst * kStagePages * kChunkBytes;
     wg.ring_lds = (uint32_t)(uintptr_t)(lptr)lds + wg.ring_off;
     wg.head = wg.tail = 0; wg.hst = wg.tst = 0;
-    wg.pf_ptr = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.stream) + (size_t)blockIdx.x * P.max_instr * 2);
+    wg.pf_ptr = wg.pf_begin = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.stream) + (size_t)blockIdx.x * P.max_instr * 2);
     wg.pf_left = P.max_instr;
+    wg.pf_steps = P.n_steps > 0 ? (uint32_t)P.n_steps - 1u : 0u;
+    wg.epoch = P.epoch; wg.pos_off = 0; wg.tok_src = P.tokens; wg.tok_out = P.next_tokens; wg.logits = P.logits;
     wg.pf_src = nullptr; wg.pf_rem = 0; wg.pf_live = wg.ring && wg.nst > 0;
     return wg;
 }
@@ -1176,16 +1284,25 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
     const uint32_t *list = (const uint32_t *)(P.ws + P.lay.instr) + (size_t)blockIdx.x * P.max_instr * kInstrDwords;
     uint32_t *sinstr = (uint32_t *)(lds + kLdsInstr);   // two slots of 32 dwords
     bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
-    fetch_instr(list, 0, sinstr);
-    for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
-        wg_sync(lp, lds);
-        Instr I;
-        read_instr(sinstr + (pc & 1u) * kInstrDwords, I);
-        if (I.op == OP_END) break;
-        uint32_t nxt = 0;
-        const bool more = pc + 1 < P.max_instr;
-        if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
-        exec_instr<true, RING>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
+    // A launch walks the list once per decode step.  Step s decodes the greedy tokens of step s-1 at
+    // the caller's positions + s; its tasks are ordered after step s-1 by the arg-max counter.
+    for (int step = 0; step < P.n_steps; ++step) {
+        lp.epoch = P.epoch + (uint32_t)step;
+        lp.pos_off = step;
+        lp.tok_src = step ? P.next_tokens + (size_t)(step - 1) * P.batch : P.tokens;
+        lp.tok_out = P.next_tokens + (size_t)step * P.batch;
+        wg_sync(lp, lds);   // the previous walk's last instruction has been read by every wave
+        fetch_instr(list, 0, sinstr);
+        for (uint32_t pc = 0; pc < P.max_instr; ++pc) {
+            wg_sync(lp, lds);
+            Instr I;
+            read_instr(sinstr + (pc & 1u) * kInstrDwords, I);
+            if (I.op == OP_END) break;
+            uint32_t nxt = 0;
+            const bool more = pc + 1 < P.max_instr;
+            if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
+            exec_instr<true, RING>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
+        }
     }
     // no DMA load may still be writing LDS when the workgroup retires
     if (RING) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -129,6 +129,7 @@ static void plan_act(const Dims &d, const Geom &g, const Tiling &t, ActMap &a)
     a.po = take((uint64_t)t.s_o * d.Bm * d.H);
     a.gu = take((uint64_t)t.s_gu * d.Bm * 2 * g.ipad);
     a.pd = take((uint64_t)t.s_d * d.Bm * d.H);
+    a.amax = take((uint64_t)g.head.groups * d.Bm * 2);   // at most one LM-head task per row group
     a.n_floats = f;
 }
 
@@ -188,6 +189,7 @@ struct Builder {
     std::vector<uint32_t> ctr_signals;  // signals per step of every counter
     uint32_t max_xs_bytes = 0;
     int n_tasks = 0;
+    uint32_t n_amax_slots = 0;          // LM-head tasks emitted so far (each owns one arg-max partial slot)
 
     Builder(const mk_config &c, const Dims &dd, const Tiling &tt, const Geom &gg, const WeightMap &w, const ActMap &a)
         : cfg(c), d(dd), t(tt), g(gg), wm(w), am(a), n_wg(c.n_workgroups), lists(c.n_workgroups), load(c.n_workgroups, 0.0) {}
@@ -244,7 +246,9 @@ struct Builder {
                 I.u0 = u; I.nu = nu;
                 I.wait_ctr[0] = wait_ctr; I.wait_ctr[1] = kNone;
                 I.wait_cnt[0] = wait_ctr == kNone ? 0 : ctr_signals[wait_ctr];
+                if (I.flags & F_WAIT_PREV) I.wait_cnt[0] = (uint32_t)d.Bm;   // the arg-max counter: one signal per sequence
                 I.wait_cnt[1] = 0;
+                if (I.flags & F_ARGMAX) I.spare = n_amax_slots++;
                 I.sig_ctr = kNone;
                 if (normk) {
                     // the first task of each participant stores its 4-aligned slice of the new residual
@@ -292,7 +296,10 @@ struct Builder {
         // The residual stream lives in xa / xb.  `res` is the buffer holding the current residual,
         // `parts` the K-split partial sums still to be added to it (summed in the next prologue).
         uint32_t res = am.xa, parts_off = 0, parts_n = 0;
-        uint32_t prev_done = kNone;
+        // Counter of the greedy-token tasks that close a step.  The first tasks of the NEXT step wait
+        // for it (F_WAIT_PREV), which orders whole steps inside a multi-step launch.
+        const uint32_t c_argmax = new_counter();
+        uint32_t prev_done = c_argmax;
         auto other = [&](uint32_t b) { return b == am.xa ? am.xb : am.xa; };
         for (int l = 0; l < d.L; ++l) {
             const uint32_t c_qkv = new_counter(), c_comb = new_counter(), c_o = new_counter(), c_gu = new_counter(),
@@ -309,6 +316,7 @@ struct Builder {
                 parts_n = 0;
                 q.gain = wm.g_attn[l];
                 q.out = am.pqkv; q.out_split_stride = d.Bm * d.nqkv; q.out_ld = d.nqkv; q.bias = wm.bias[l];
+                if (l == 0) q.flags |= F_WAIT_PREV;
                 if (!emit_gemv(q, g.qkv, prev_done, c_qkv)) return false;
             }
             // ---- attention partials: one task per (sequence, kv head, chunk)
@@ -386,10 +394,25 @@ struct Builder {
         }
         // ---- final norm + LM head (never stores a residual slice)
         Instr h = gemv_proto(ST_HEAD, d.L, g.head, wm.head, 1, PRO_RESID_NORM, parts_n, 0);
-        h.flags |= F_LOGITS;
+        h.flags |= F_LOGITS | F_ARGMAX;
         h.in_base = res; h.in_parts = parts_off; h.part_stride = d.Bm * d.H; h.in_ld = d.H;
         h.gain = wm.g_final; h.out_ld = d.V;
-        if (!emit_gemv(h, g.head, prev_done, kNone)) return false;
+        const uint32_t c_head = new_counter();
+        if (!emit_gemv(h, g.head, prev_done, c_head)) return false;
+        // ---- greedy token: one task per sequence reduces the (max, row) partials of the LM-head tasks
+        {
+            std::vector<int> order = by_load();
+            for (int b = 0; b < d.Bm; ++b) {
+                InstrAtt a{};
+                a.op = OP_ARGMAX; a.ref_seq = d.L * 8 + ST_ARGMAX; a.layer = d.L;
+                a.wait_ctr[0] = c_head; a.wait_cnt[0] = ctr_signals[c_head]; a.wait_ctr[1] = kNone;
+                a.sig_ctr = c_argmax; ++ctr_signals[c_argmax];
+                a.b = b; a.out = am.amax; a.n_slots = n_amax_slots;
+                Instr raw; memcpy(&raw, &a, sizeof raw);
+                lists[order[b % n_wg]].push_back(raw); ++n_tasks;
+                load[order[b % n_wg]] += 2.0;
+            }
+        }
         max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d));
         max_xs_bytes = std::max(max_xs_bytes, (uint32_t)(t.nc * (d.d + kPartPad) * 4));
         return true;
@@ -424,6 +447,7 @@ static bool replay(const mk_schedule *s, F &&visit, std::string *why)
                 for (int k = 0; k < 2; ++k)
                     if (I.wait_ctr[k] != kNone) {
                         if (I.wait_ctr[k] >= (uint32_t)s->n_counters) { if (why) *why = "wait on a counter that does not exist"; return false; }
+                        if (k == 0 && (I.flags & F_WAIT_PREV)) continue;   // satisfied by the previous step
                         if (got[I.wait_ctr[k]] < I.wait_cnt[k]) ready = false;
                     }
                 if (!ready) break;
@@ -479,7 +503,7 @@ static SimResult simulate(const mk_schedule *s)
     replay(s, [&](int w, int, const Instr &I) {
         double dep = 0.0;
         for (int k = 0; k < 2; ++k)
-            if (I.wait_ctr[k] != kNone) dep = std::max(dep, ctr_done[I.wait_ctr[k]] + sync_us);
+            if (I.wait_ctr[k] != kNone && !(k == 0 && (I.flags & F_WAIT_PREV))) dep = std::max(dep, ctr_done[I.wait_ctr[k]] + sync_us);
         double bytes = 0.0, pro = 0.0;
         if (I.op == OP_GEMV) {
             bytes = (double)task_chunks(I) * kChunkBytes;
@@ -495,8 +519,10 @@ static SimResult simulate(const mk_schedule *s)
         } else if (I.op == OP_ATT) {
             bytes = (double)d.Tm / s->tl.nc * d.d * 4.0;
             pro = 0.5;
-        } else {
+        } else if (I.op == OP_COMB) {
             pro = 0.3 + s->tl.nc * 0.01;
+        } else {
+            pro = 1.0;   // arg-max over the LM-head partials
         }
         // weight stream: may start once the ring has room, i.e. `window` bytes ahead of the consumer
         double lead = std::min(bytes, window);
@@ -561,6 +587,7 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     L.err = off; off = align_up(off + 64, 4096);
     L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 64 : 0), 4096);
     L.stream = off; off = align_up(off + (uint64_t)s->n_wg * s->max_instr * 8, 4096);
+    L.tokens = off; off = align_up(off + (uint64_t)kMaxBatch * 4, 4096);
     L.total = off;
     s->sim = simulate(s);
     return MK_OK;
@@ -717,6 +744,7 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
                     wr(I.xs_out + (uint64_t)b * I.in_ld + I.xs_lo, I.xs_hi - I.xs_lo);
             }
         }
+        if (I.flags & F_ARGMAX) wr(s->am.amax + (uint64_t)I.spare * d.Bm * 2, (uint64_t)d.Bm * 2);
         if (!(I.flags & F_LOGITS)) {
             for (uint32_t u = I.u0; u < I.u0 + I.nu; ++u)
                 for (int b = 0; b < d.Bm; ++b) {
@@ -745,6 +773,9 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
             for (uint32_t c = 0; c < A.nc; ++c) rd(A.out + (((uint64_t)A.b * d.nq + h) * A.nc + c) * (d.d + kPartPad), d.d + 2);
             wr(A.o_out + (uint64_t)A.b * A.o_ld + (uint64_t)h * d.d, d.d);
         }
+    } else if (I.op == OP_ARGMAX) {
+        const InstrAtt &A = *(const InstrAtt *)&I;
+        rd(A.out, (uint64_t)A.n_slots * d.Bm * 2);   // every slot's row of every sequence (a superset of what it reads)
     }
 }
 }  // namespace
@@ -768,7 +799,7 @@ int verify_schedule(const mk_schedule *s)
         for (; i < mi; ++i) {
             const Instr &I = all[(size_t)w * mi + i];
             if (I.op == OP_END) break;
-            if (I.op != OP_GEMV && I.op != OP_ATT && I.op != OP_COMB) return fail("unknown opcode");
+            if (I.op != OP_GEMV && I.op != OP_ATT && I.op != OP_COMB && I.op != OP_ARGMAX) return fail("unknown opcode");
             if (I.sig_ctr != kNone) {
                 if (I.sig_ctr >= (uint32_t)s->n_counters) return fail("signal to a counter that does not exist");
                 ++signals[I.sig_ctr];
@@ -795,17 +826,31 @@ int verify_schedule(const mk_schedule *s)
     {
         std::map<uint32_t, std::vector<std::pair<uint32_t, uint32_t>>> units;   // ref_seq -> [u0, u1)
         std::map<uint32_t, std::vector<uint32_t>> keys;
+        std::vector<uint32_t> slots, argmax_slots;
         for (int w = 0; w < n_wg; ++w)
             for (int i = 0; i < cnt[w]; ++i) {
                 const Instr &I = all[(size_t)w * mi + i];
                 if (I.op == OP_GEMV) {
                     if (I.nu == 0 || I.S == 0 || I.nkb == 0) return fail("empty GEMV task");
                     units[I.ref_seq].push_back({I.u0, I.u0 + I.nu});
+                    if (I.flags & F_ARGMAX) slots.push_back(I.spare);
                 } else {
                     const InstrAtt &A = *(const InstrAtt *)&I;
-                    keys[I.ref_seq].push_back(I.op == OP_ATT ? (A.b * d.nkv + A.g) * A.nc + A.c : A.b * d.nq + A.h0);
+                    keys[I.ref_seq].push_back(I.op == OP_ATT ? (A.b * d.nkv + A.g) * A.nc + A.c : I.op == OP_COMB ? A.b * d.nq + A.h0 : A.b);
+                    if (I.op == OP_ARGMAX) argmax_slots.push_back(A.n_slots);
                 }
             }
+        // arg-max: one task per sequence, the LM-head tasks own the partial slots 0 .. n-1, one each
+        {
+            auto &v = keys[d.L * 8 + ST_ARGMAX];
+            std::sort(v.begin(), v.end());
+            if ((int)v.size() != d.Bm) return fail("the step does not end with one arg-max task per sequence");
+            for (int b = 0; b < d.Bm; ++b) if (v[b] != (uint32_t)b) return fail("arg-max task missing or duplicated");
+            std::sort(slots.begin(), slots.end());
+            for (size_t i = 0; i < slots.size(); ++i) if (slots[i] != i) return fail("arg-max partial slot missing or duplicated");
+            if (slots.size() > (size_t)s->gm.head.groups) return fail("more arg-max partial slots than the buffer holds");
+            for (uint32_t n : argmax_slots) if (n != slots.size()) return fail("arg-max task reduces the wrong number of partial slots");
+        }
         for (int l = 0; l <= d.L; ++l) {
             const Geom &gm = s->gm;
             struct { uint32_t st; uint32_t total; } g[] = {
@@ -848,7 +893,7 @@ int verify_schedule(const mk_schedule *s)
         if (i > 0) memcpy(me, vc.data() + (first[w] + i - 1) * n_wg, sizeof(uint16_t) * n_wg);
         me[w] = (uint16_t)i;
         for (int k = 0; k < 2; ++k)
-            if (I.wait_ctr[k] != kNone) {
+            if (I.wait_ctr[k] != kNone && !(k == 0 && (I.flags & F_WAIT_PREV))) {
                 const uint16_t *c = cvc.data() + (size_t)I.wait_ctr[k] * n_wg;
                 for (int x = 0; x < n_wg; ++x) me[x] = std::max(me[x], c[x]);
             }
@@ -867,6 +912,33 @@ int verify_schedule(const mk_schedule *s)
         if (wa == wb) return t_idx[a] < t_idx[b];
         return vc[(size_t)b * n_wg + wa] >= (uint16_t)(t_idx[a] + 1);
     };
+
+    // (3b) steps of a multi-step launch follow each other without a kernel boundary.  They stay
+    //      ordered because (i) every task waits on something, (ii) only the first operator of a step
+    //      waits at the previous step's target, and it waits for the arg-max counter, (iii) every
+    //      task of a step happens before one of the arg-max tasks that signal that counter: so no
+    //      task of step e+1 starts before every task of step e has drained its stores.
+    {
+        std::vector<uint32_t> amx;
+        uint32_t amx_ctr = kNone;
+        for (uint32_t t = 0; t < n_tasks; ++t) {
+            const Instr &I = all[(size_t)t_wg[t] * mi + t_idx[t]];
+            if (I.op == OP_ARGMAX) { amx.push_back(t); amx_ctr = I.sig_ctr; }
+        }
+        for (uint32_t t = 0; t < n_tasks; ++t) {
+            const Instr &I = all[(size_t)t_wg[t] * mi + t_idx[t]];
+            if (I.wait_ctr[0] == kNone) return fail("a task waits on nothing: steps of one launch could overlap");
+            if (I.flags & F_WAIT_PREV) {
+                if (I.op != OP_GEMV || I.ref_seq != ST_QKV || I.wait_ctr[0] != amx_ctr) return fail("only the first operator may wait for the previous step, and only on the arg-max counter");
+            } else if (I.op == OP_GEMV && I.ref_seq == ST_QKV) {
+                return fail("the first operator of a step must wait for the previous step's arg-max");
+            }
+            if (I.op == OP_ARGMAX) continue;
+            bool before = false;
+            for (uint32_t a : amx) before = before || hb(t, a);
+            if (!before) { snprintf(buf, sizeof buf, "task ref_seq %u is not ordered before the arg-max that closes the step", I.ref_seq); return fail(buf); }
+        }
+    }
 
     // (4) walk the tasks in topological (operator) order with a last-writers table: every
     //     read-after-write, write-after-read and write-after-write pair must be ordered.

@@ -47,6 +47,7 @@ struct WeightMap {           // chunk / element offsets inside the workspace
 
 struct ActMap {              // float offsets inside the activation region
     uint32_t xa, xb, pqkv, attp, o, po, gu, pd;   // gu holds silu(gate)*up when the gate/up epilogue is fused
+    uint32_t amax;                                // arg-max partials [LM-head task slot][sequence][2] = (max logit, row)
     uint64_t n_floats;
 };
 

@@ -72,6 +72,13 @@ class Decoder:
         fn = mk.mk_decode_step_per_op if per_op else mk.mk_decode_step
         fn(self.h, tokens, positions, kv, logits, int(tokens.numel()))
 
+    def greedy(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor, logits: torch.Tensor,
+               n_steps: int) -> torch.Tensor:
+        """``n_steps`` greedy decode steps in ONE launch; returns the chosen tokens [n_steps][batch] (int32, device)."""
+        out = torch.empty(n_steps, int(tokens.numel()), dtype=torch.int32, device=self.device)
+        mk.mk_decode_steps(self.h, tokens, positions, kv, logits, out, int(tokens.numel()), n_steps)
+        return out
+
     def check(self) -> None:
         mk.mk_check(self.h)
 

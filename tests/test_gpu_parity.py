@@ -226,6 +226,86 @@ def test_cache_rows_beyond_the_position_are_never_used():
         pr.close()
 
 
+def _greedy_oracle(pr, first_tokens, first_positions, n_steps):
+    toks, cur = [], list(first_tokens)
+    last = None
+    for s in range(n_steps):
+        last = pr.orc.step(cur, [p + s for p in first_positions], pr.kv_h)
+        cur = [oracle.argmax(last[b]) for b in range(len(cur))]
+        toks.append(cur)
+    return np.array(toks, dtype=np.int32), last
+
+
+@pytest.mark.parametrize("opts", [dict(), dict(ring_kb=32), dict(n_workgroups=48, attn_chunks=4)],
+                         ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()) or "default")
+def test_c0_32_greedy_steps_in_one_launch(opts):
+    """The acceptance run of the tiny configuration with the token feedback on the device: one
+    launch walks the instruction lists 32 times; the greedy tokens equal the oracle's, the last
+    step's logits and the appended cache rows agree, and single steps continue from there."""
+    full = tiny()
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full)
+    pr = Pair(cfg, w, **opts)
+    n0, n = full["ctx0"], full["steps"]
+    prompt = synth.make_prompt(full, n0)
+    pr.prefill(prompt[:-1])
+    want_toks, want_last = _greedy_oracle(pr, [int(prompt[-1])], [n0 - 1], n)
+    t = torch.tensor([int(prompt[-1])], dtype=torch.int32, device=DEV)
+    p = torch.tensor([n0 - 1], dtype=torch.int32, device=DEV)
+    pr.logits.fill_(float("nan"))
+    got_toks = pr.dec.greedy(t, p, pr.kv_d, pr.logits, n)
+    pr.dec.check()
+    got_toks = got_toks.cpu().numpy()
+    say("greedy tokens", got_toks[:, 0].tolist())
+    assert np.array_equal(got_toks, want_toks)
+    assert rel_err(pr.logits[:1].cpu().numpy()[0], want_last[0]) <= TIGHT
+    kv_g = synth.bf16_bits_to_f32(pr.kv_d.cpu().numpy().view(np.uint16)[:, :, 0, :, n0 - 1:n0 - 1 + n, :])
+    kv_o = synth.bf16_bits_to_f32(pr.kv_h[:, :, 0, :, n0 - 1:n0 - 1 + n, :])
+    assert np.abs(kv_g - kv_o).max() <= 2 ** -7 * np.abs(kv_o).max()
+    # a plain single step continues where the multi-step launch stopped
+    nxt = int(want_toks[-1, 0])
+    want = pr.orc.step([nxt], [n0 - 1 + n], pr.kv_h)[0]
+    got = pr.gpu_step([nxt], [n0 - 1 + n])[0]
+    assert rel_err(got, want) <= TIGHT and int(got.argmax()) == oracle.argmax(want)
+    pr.close()
+
+
+def test_batched_greedy_steps_in_one_launch_and_argument_checks():
+    full = tiny(max_batch=3, index=5)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    pr = Pair(cfg, w)
+    lens = [9, 1, 26]
+    prompts = [synth.make_prompt(full, n, name=f"q{i}") for i, n in enumerate(lens)]
+    one = oracle.Decoder(synth.model_cfg(full, max_batch=1), w)
+    for b, pmt in enumerate(prompts):
+        kv1 = one.new_kv()
+        one.prefill(pmt[:-1], kv1)
+        pr.kv_h[:, :, b] = kv1[:, :, 0]
+    pr.kv_d.copy_(torch.from_numpy(pr.kv_h.view(np.int16)).to(DEV))
+    first = [int(p[-1]) for p in prompts]
+    pos0 = [n - 1 for n in lens]
+    want_toks, want_last = _greedy_oracle(pr, first, pos0, 7)
+    t = torch.tensor(first, dtype=torch.int32, device=DEV)
+    p = torch.tensor(pos0, dtype=torch.int32, device=DEV)
+    got = pr.dec.greedy(t, p, pr.kv_d, pr.logits, 7)
+    pr.dec.check()
+    assert np.array_equal(got.cpu().numpy(), want_toks)
+    for b in range(3):
+        assert rel_err(pr.logits[b].cpu().numpy(), want_last[b]) <= TIGHT
+    for bad_n in (0, cfg["max_context"] + 1):
+        with pytest.raises(mk.MkError) as e:
+            pr.dec.greedy(t, p, pr.kv_d, pr.logits, bad_n)
+        assert e.value.code == mk.MK_EINVAL
+    say("running past the end of the cache raises the position error and still terminates")
+    p_end = torch.tensor([cfg["max_context"] - 2] * 3, dtype=torch.int32, device=DEV)
+    pr.dec.greedy(t, p_end, pr.kv_d, pr.logits, 4)
+    with pytest.raises(mk.MkError) as e:
+        pr.dec.check()
+    assert e.value.code == mk.MK_EINVAL
+    pr.close()
+
+
 def test_two_runs_are_bit_identical():
     full = tiny()
     cfg = synth.model_cfg(full)

@@ -212,7 +212,61 @@ def test_verifier_rejects_dropped_wait():
     i, w = _first(h, 5, lambda w: w[WAIT_CTR0] != KNONE and w[OP] == 1)
     w[WAIT_CTR0] = KNONE
     mk.mk_instr_set(h, 5, i, w)
+    _expect_rejected(h, "waits on nothing")
+
+
+def test_verifier_rejects_wait_on_the_wrong_producer():
+    """A task that waits on an existing counter with the right signal count, but not the one its
+    input comes from, leaves a read-after-write pair unordered."""
+    h = build("c0_tiny")
+    # a down-projection task (stage 5) of layer 0 made to wait for the O projection instead of gate/up
+    def anywhere(pred):
+        for wg in range(256):
+            for i in range(mk.mk_instr_count(h, wg)):
+                w = mk.mk_instr_get(h, wg, i)
+                if pred(w):
+                    return wg, i, w
+        raise AssertionError("no such instruction")
+    wg, i, w = anywhere(lambda w: w[OP] == 1 and w[REF_SEQ] == 5)
+    _, _, o = anywhere(lambda w: w[OP] == 1 and w[REF_SEQ] == 4)
+    w[WAIT_CTR0], w[WAIT_CNT0] = o[WAIT_CTR0], o[WAIT_CNT0]
+    mk.mk_instr_set(h, wg, i, w)
     _expect_rejected(h, "not ordered")
+
+
+def test_verifier_guards_the_step_boundary():
+    """Steps of a multi-step launch are ordered only by the arg-max counter: the first operator must
+    wait for it at the previous step's target, nobody else may, and the arg-max must cover every
+    LM-head partial."""
+    F_WAIT_PREV, OP_ARGMAX, N_SLOTS = 64, 4, 25
+    h = build("c0_tiny")
+    i, w = _first(h, 0, lambda w: w[OP] == 1 and w[REF_SEQ] == 0)
+    assert w[FLAGS] & F_WAIT_PREV
+    w[FLAGS] = int(w[FLAGS]) & (0xFFFFFFFF ^ F_WAIT_PREV)
+    mk.mk_instr_set(h, 0, i, w)
+    _expect_rejected(h)          # waits inside the step for a counter signalled at its very end
+    h = build("c0_tiny")
+    done = False
+    for wg in range(256):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if not done and w[OP] == 1 and w[REF_SEQ] == 3:
+                w[FLAGS] |= F_WAIT_PREV
+                mk.mk_instr_set(h, wg, i, w)
+                done = True
+    assert done
+    _expect_rejected(h)
+    h = build("c0_tiny")
+    found = False
+    for wg in range(256):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if w[OP] == OP_ARGMAX:
+                w[N_SLOTS] -= 1
+                mk.mk_instr_set(h, wg, i, w)
+                found = True
+    assert found
+    _expect_rejected(h, "arg-max")
 
 
 def test_verifier_rejects_dropped_signal_and_bad_counter():
