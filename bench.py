@@ -146,6 +146,22 @@ def main() -> int:
                      "kernel": "mk_megakernel", "kernel_ms": round(kern_ms, 5), "algorithmic_bytes": int(bytes_launch)},
     }
 
+    # ---- the same number of greedy steps as ONE launch (token feedback on the device)
+    kv_ms = dec.new_kv(kv_h)
+    first = toks[warmup].clone()
+    p0 = poss[warmup].clone()
+    dec.greedy(first, p0, kv_ms, logits, min(steps, 8))
+    torch.cuda.synchronize()
+    kv_ms.copy_(kv_d if False else dec.new_kv(kv_h))
+    t4 = time.perf_counter()
+    dec.greedy(first, p0, kv_ms, logits, steps)
+    torch.cuda.synchronize()
+    ms_multi = (time.perf_counter() - t4) * 1e3 / steps
+    dec.check()
+    out["multi_step_launch"] = {"ms_per_step": round(ms_multi, 5), "tokens_per_s": round(B * 1e3 / ms_multi, 2),
+                                "steps_in_one_launch": steps, "tokens": "greedy, fed back on the device"}
+    del kv_ms
+
     if not args.no_per_op:
         n_po = min(steps, 32)
         run(warmup, 2, per_op=True)

@@ -51,7 +51,7 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.ws = s->ws; P.lay = s->lay;
     P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
     P.next_tokens = next_tokens ? next_tokens : (int32_t *)(s->ws + s->lay.tokens);
-    P.n_steps = n_steps; P.amax = s->am.amax;
+    P.n_steps = n_steps; P.amax = s->am.amax; P.want_tokens = next_tokens != nullptr;
     P.batch = batch; P.max_batch = s->dm.Bm; P.max_context = s->dm.Tm;
     P.n_layers = s->dm.L; P.hidden = s->dm.H; P.n_q_heads = s->dm.nq; P.n_kv_heads = s->dm.nkv;
     P.head_dim = s->dm.d; P.inter_pad = s->gm.ipad; P.vocab = s->dm.V;
@@ -202,6 +202,7 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     HIP_TRY(hipGetDeviceProperties(&prop, s->device));
     if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_steps, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     int per_cu = 0;
@@ -351,6 +352,8 @@ static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *po
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     if (s->tl.ring_pages && !(P.dbg & 4u))
         hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    else if (n_steps > 1)
+        hipLaunchKernelGGL(mk_megakernel_steps, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     else
         hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());

@@ -75,6 +75,26 @@ struct Wg {
 
 __device__ __forceinline__ void wg_sync(Wg &, char *) { __syncthreads(); }
 
+__device__ __forceinline__ uint32_t rfl(uint32_t v);
+template <class T>
+__device__ __forceinline__ T *rfl_ptr(T *p)
+{
+    const uint64_t a = (uint64_t)(uintptr_t)p;
+    return (T *)(uintptr_t)((uint64_t)rfl((uint32_t)a) | ((uint64_t)rfl((uint32_t)(a >> 32)) << 32));
+}
+// The ring state is wave-uniform by construction.  Re-reading it through readfirstlane at every
+// instruction boundary keeps it in scalar registers whatever the compiler's divergence analysis
+// concludes about the surrounding control flow.
+__device__ __forceinline__ void pin_uniform(Wg &wg)
+{
+    wg.head = rfl(wg.head); wg.tail = rfl(wg.tail); wg.hst = rfl(wg.hst); wg.tst = rfl(wg.tst);
+    wg.pf_rem = rfl(wg.pf_rem); wg.pf_left = rfl(wg.pf_left); wg.pf_steps = rfl(wg.pf_steps);
+    wg.pf_live = rfl((uint32_t)wg.pf_live) != 0;
+    wg.pf_src = rfl_ptr(wg.pf_src);
+    wg.pf_ptr = (cptr)(uintptr_t)rfl_ptr((const uint32_t *)(uintptr_t)wg.pf_ptr);
+    wg.epoch = rfl(wg.epoch); wg.pos_off = (int)rfl((uint32_t)wg.pos_off);
+}
+
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ uint32_t rfl(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -720,13 +740,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
                 if (row < I.n_rows) lp.logits[(size_t)b * P.vocab + row] = v;
                 // this thread is the only reader of index t of the reduction area: keep the finished
                 // logit there for the arg-max pass below
-                if (I.flags & F_ARGMAX) red[t] = row < I.n_rows ? v : -INFINITY;
+                if ((I.flags & F_ARGMAX) && P.want_tokens) red[t] = row < I.n_rows ? v : -INFINITY;
             } else {
                 if (I.flags & F_ADD_RESID) v += ld_act(actw + I.resid + (size_t)b * I.out_ld + row);
                 st_act(actw + I.out + (size_t)s * I.out_split_stride + (size_t)b * I.out_ld + row, v);
             }
         }
-        if (I.flags & F_ARGMAX) {
+        if ((I.flags & F_ARGMAX) && P.want_tokens) {
             // (max logit, its row) of this task per sequence; ties go to the smaller row
             float *sv = (float *)(lds + kLdsMisc + 64);
             uint32_t *si = (uint32_t *)(lds + kLdsMisc + 80);
@@ -1122,7 +1142,7 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
 __device__ __forceinline__ void argmax_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp)
 {
     const int b = (int)I.b, tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
-    if (b >= P.batch) return;
+    if (b >= P.batch || !P.want_tokens) return;
     const float *part = (const float *)(P.ws + P.lay.act) + I.out;
     float bv = -INFINITY;
     uint32_t bi = 0xffffffffu;
@@ -1172,7 +1192,10 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     const bool tracing = PERSISTENT && (P.flags & 1u);
     if (tracing && tid == 0) t0 = wall_clock64();
 
-    const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u);
+    // Nothing to wait for: the first step of a launch follows the previous launch in stream order,
+    // and an arg-max task whose result nobody takes only has to signal.
+    const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens);
+    const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u) && !no_dep;
     GemvStream st;
     AttStream as;
     if (I.op == OP_GEMV) gemv_issue<RING>(P, I, st, lp.npf);
@@ -1274,7 +1297,7 @@ __device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *l
 
 // Persistent walk of this workgroup's whole list; the next instruction is fetched while the
 // current one runs.
-template <bool RING>
+template <bool RING, bool MULTI>
 __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1286,7 +1309,8 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
     bool dead = false;   // a wait timed out: stop waiting, keep walking so the grid drains
     // A launch walks the list once per decode step.  Step s decodes the greedy tokens of step s-1 at
     // the caller's positions + s; its tasks are ordered after step s-1 by the arg-max counter.
-    for (int step = 0; step < P.n_steps; ++step) {
+    const int n_steps = MULTI ? P.n_steps : 1;   // the single-step kernel keeps the step context constant
+    for (int step = 0; step < n_steps; ++step) {
         lp.epoch = P.epoch + (uint32_t)step;
         lp.pos_off = step;
         lp.tok_src = step ? P.next_tokens + (size_t)(step - 1) * P.batch : P.tokens;
@@ -1301,6 +1325,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
             uint32_t nxt = 0;
             const bool more = pc + 1 < P.max_instr;
             if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
+            if (RING) pin_uniform(lp);
             exec_instr<true, RING>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
         }
     }
@@ -1339,11 +1364,15 @@ __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
 }  // namespace mk
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false>(P, lp); }
+mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, false>(P, lp); }
+
+// The same walk repeated once per decode step of the launch (greedy token feedback on the device).
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
+mk_megakernel_steps(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, true>(P, lp); }
 
 // Same walk with the per-wave LDS page ring carrying the weight stream.
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true>(P, lp); }
+mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true, true>(P, lp); }
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
 mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op(P, lp); }
