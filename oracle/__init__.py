@@ -74,6 +74,10 @@ def lib():
         L.orc_decode_step.restype = C.c_int
         L.orc_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]
+        L.orc_decode_step_q.restype = C.c_int
+        L.orc_decode_step_q.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]
+        L.orc_gemv_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_pages_available.restype = C.c_int64
         L.orc_pages_available.argtypes = [C.c_int64] * 6
         L.orc_pipeline_stages.restype = C.c_int64
@@ -176,11 +180,34 @@ _LAYER_KEYS = ("attn_norm", "wq", "wk", "wv", "bq", "bk", "bv", "q_norm", "k_nor
                "mlp_norm", "w_gate", "w_up", "w_down")
 
 
+_W4_KEYS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+class _W4(C.Structure):
+    _fields_ = [("group", C.c_int32)] + [(k, _PP) for k in _W4_KEYS] + [
+        ("s" + k[1:] if k[1] != "_" else "s" + k[1:], _PP) for k in _W4_KEYS]
+
+
+def gemv_w4(codes, scales_bits, group: int, x, bias_bits=None) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sc = _u16(scales_bits)
+    x = _f32(x)
+    n_out, half = codes.shape
+    assert sc.shape == (n_out, 2 * half // group)
+    b = _u16(bias_bits) if bias_bits is not None else None
+    y = np.empty(n_out, dtype=np.float32)
+    lib().orc_gemv_w4(_p(codes), _p(sc), n_out, 2 * half, int(group), _p(x), _p(b), _p(y))
+    return y
+
+
 @dataclass
 class Decoder:
-    """Holds a config + weights (dict of uint16 arrays; per-layer entries are lists)."""
+    """Holds a config + weights (dict of uint16 arrays; per-layer entries are lists).  With ``quant``
+    (dict: ``group``, uint8 code arrays under the seven projection names, bf16 scale arrays under
+    ``s_<name>``) those projections are taken in their W4A16 form."""
     cfg: Dict
     weights: Dict
+    quant: Optional[Dict] = None
 
     def __post_init__(self):
         c = self.cfg
@@ -202,6 +229,21 @@ class Decoder:
             self._keep.append(tab)
             setattr(ws, key, C.cast(tab, _PP))
         self._w = ws
+        self._q = None
+        if self.quant is not None:
+            q4 = _W4()
+            q4.group = int(self.quant["group"])
+            for key in _W4_KEYS:
+                skey = "s" + key[1:]
+                codes = [np.ascontiguousarray(a, dtype=np.uint8) for a in self.quant[key]]
+                scales = [_u16(a) for a in self.quant["s_" + key]]
+                assert len(codes) == L and len(scales) == L
+                tc = (C.c_void_p * L)(*[a.ctypes.data for a in codes])
+                ts = (C.c_void_p * L)(*[a.ctypes.data for a in scales])
+                self._keep += [codes, scales, tc, ts]
+                setattr(q4, key, C.cast(tc, _PP))
+                setattr(q4, skey, C.cast(ts, _PP))
+            self._q = q4
 
     def kv_shape(self):
         c = self.cfg
@@ -216,8 +258,8 @@ class Decoder:
         B = tokens.size
         assert kv.dtype == np.uint16 and kv.shape == self.kv_shape() and kv.flags.c_contiguous
         logits = np.empty((B, self.cfg["vocab"]), dtype=np.float32) if want_logits else None
-        rc = lib().orc_decode_step(C.byref(self._c), C.byref(self._w), B, _p(tokens), _p(positions),
-                                   _p(kv), _p(logits))
+        rc = lib().orc_decode_step_q(C.byref(self._c), C.byref(self._w), C.byref(self._q) if self._q is not None else None,
+                                     B, _p(tokens), _p(positions), _p(kv), _p(logits))
         if rc != 0:
             raise ValueError("orc_decode_step rejected its arguments")
         return logits

@@ -23,6 +23,16 @@
  *
  * Layouts.  All matrices are row-major [out][in] bf16.  KV cache:
  * [layer][2 (0=K,1=V)][max_batch][n_kv_heads][max_context][head_dim] bf16.
+ *
+ * W4A16 (paper Sec. 4.3.2 "MegaKernel Quantization Implementation", Sec. 5.1:
+ * the measured models are GPTQ-W4A16).  The paper fixes neither the code
+ * layout nor the zero point; the reading taken here is symmetric group
+ * quantisation of the seven decoder projections (embedding and LM head stay
+ * bf16, as in GPTQ checkpoints): w[r][k] = (q[r][k] - 8) * s[r][k / G] with
+ * q an unsigned 4-bit code, s a bf16 scale, G the group size along K.  Codes
+ * are packed two per byte, row-major [out][in/2]: byte j of a row holds
+ * k = 2j in its low nibble and k = 2j + 1 in its high nibble.  Scales are
+ * row-major [out][in/G].  Activations stay fp32 ("A16" or wider).
  */
 #include <math.h>
 #include <stdint.h>
@@ -58,6 +68,14 @@ typedef struct orc_weights {
     const uint16_t *const *w_up;   /* [inter][hidden] */
     const uint16_t *const *w_down; /* [hidden][inter] */
 } orc_weights;
+
+/* W4A16 form of the seven decoder projections (host pointers, per-layer
+ * arrays).  The matching bf16 matrix pointers of orc_weights are ignored. */
+typedef struct orc_w4 {
+    int32_t group;              /* group size along K; divides hidden, nq*d and intermediate */
+    const uint8_t *const *wq, *const *wk, *const *wv, *const *wo, *const *w_gate, *const *w_up, *const *w_down;
+    const uint16_t *const *sq, *const *sk, *const *sv, *const *so, *const *s_gate, *const *s_up, *const *s_down;
+} orc_w4;
 
 /* ---- bf16 <-> fp32 ------------------------------------------------------ */
 
@@ -102,6 +120,26 @@ void orc_gemv(const uint16_t *W, int n_out, int n_in, const float *x,
         const uint16_t *row = W + (size_t)r * (size_t)n_in;
         double acc = 0.0;
         for (int k = 0; k < n_in; ++k) acc += (double)orc_bf16_to_f32(row[k]) * (double)x[k];
+        if (bias) acc += (double)orc_bf16_to_f32(bias[r]);
+        y[r] = (float)acc;
+    }
+}
+
+/* y = W x (+ bias) for a W4 matrix: codes [n_out][n_in/2] bytes, scales
+ * [n_out][n_in/group] bf16, w = (q - 8) * s (see the file header). */
+void orc_gemv_w4(const uint8_t *codes, const uint16_t *scales, int n_out, int n_in, int group,
+                 const float *x, const uint16_t *bias, float *y)
+{
+    const int n_groups = n_in / group;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < n_out; ++r) {
+        const uint8_t *row = codes + (size_t)r * (size_t)(n_in / 2);
+        double acc = 0.0;
+        for (int k = 0; k < n_in; ++k) {
+            const int q = (k & 1) ? (row[k >> 1] >> 4) : (row[k >> 1] & 15);
+            const double s = (double)orc_bf16_to_f32(scales[(size_t)r * n_groups + k / group]);
+            acc += (double)(q - 8) * s * (double)x[k];
+        }
         if (bias) acc += (double)orc_bf16_to_f32(bias[r]);
         y[r] = (float)acc;
     }
@@ -184,14 +222,37 @@ static size_t kv_index(const orc_config *c, int layer, int which, int b, int g, 
  * its K/V at slot positions[b] of kv_cache, attends over slots 0..positions[b],
  * and writes logits[b][vocab] unless logits is NULL (then the LM head is
  * skipped -- used for prefill).  Returns 0, or -1 on a bad argument. */
+int orc_decode_step_q(const orc_config *c, const orc_weights *w, const orc_w4 *q4, int batch,
+                      const int32_t *tokens, const int32_t *positions,
+                      uint16_t *kv_cache, float *logits);
+
 int orc_decode_step(const orc_config *c, const orc_weights *w, int batch,
                     const int32_t *tokens, const int32_t *positions,
                     uint16_t *kv_cache, float *logits)
+{
+    return orc_decode_step_q(c, w, NULL, batch, tokens, positions, kv_cache, logits);
+}
+
+/* One projection of the decoder: the bf16 matrix, or its W4 form when q4 is given. */
+static void proj(const uint16_t *W, const uint8_t *codes, const uint16_t *scales, int group,
+                 int n_out, int n_in, const float *x, const uint16_t *bias, float *y)
+{
+    if (codes) orc_gemv_w4(codes, scales, n_out, n_in, group, x, bias, y);
+    else orc_gemv(W, n_out, n_in, x, bias, y);
+}
+
+/* The same step with the seven decoder projections taken from q4 (W4A16) when q4 != NULL. */
+int orc_decode_step_q(const orc_config *c, const orc_weights *w, const orc_w4 *q4, int batch,
+                      const int32_t *tokens, const int32_t *positions,
+                      uint16_t *kv_cache, float *logits)
 {
     const int H = c->hidden, nq = c->n_q_heads, nkv = c->n_kv_heads, d = c->head_dim;
     const int I = c->intermediate, V = c->vocab;
     const int qd = nq * d, kvd = nkv * d, group = nq / nkv;
     if (batch < 1 || batch > c->max_batch || nq % nkv != 0 || (d & 1)) return -1;
+    const int G = q4 ? q4->group : 0;
+    if (q4 && (G < 2 || (G & 1) || H % G || qd % G || I % G)) return -1;
+#define Q4(field) (q4 ? q4->field[l] : NULL)
     for (int b = 0; b < batch; ++b)
         if (tokens[b] < 0 || tokens[b] >= V || positions[b] < 0 || positions[b] >= c->max_context)
             return -1;
@@ -213,9 +274,9 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, int batch,
         for (int l = 0; l < c->n_layers; ++l) {
             /* attention block */
             orc_rmsnorm(x, w->attn_norm[l], H, c->rms_eps, h);
-            orc_gemv(w->wq[l], qd, H, h, c->qkv_bias ? w->bq[l] : NULL, q);
-            orc_gemv(w->wk[l], kvd, H, h, c->qkv_bias ? w->bk[l] : NULL, k);
-            orc_gemv(w->wv[l], kvd, H, h, c->qkv_bias ? w->bv[l] : NULL, v);
+            proj(q4 ? NULL : w->wq[l], Q4(wq), Q4(sq), G, qd, H, h, c->qkv_bias ? w->bq[l] : NULL, q);
+            proj(q4 ? NULL : w->wk[l], Q4(wk), Q4(sk), G, kvd, H, h, c->qkv_bias ? w->bk[l] : NULL, k);
+            proj(q4 ? NULL : w->wv[l], Q4(wv), Q4(sv), G, kvd, H, h, c->qkv_bias ? w->bv[l] : NULL, v);
             if (c->qk_norm) {
                 for (int hh = 0; hh < nq; ++hh)
                     orc_rmsnorm(q + hh * d, w->q_norm[l], d, c->rms_eps, q + hh * d);
@@ -237,15 +298,15 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, int batch,
                 orc_attend(q + hh * d, kv_cache + kv_index(c, l, 0, b, g, 0),
                            kv_cache + kv_index(c, l, 1, b, g, 0), p + 1, d, o + hh * d);
             }
-            orc_gemv(w->wo[l], H, qd, o, NULL, t1);
+            proj(q4 ? NULL : w->wo[l], Q4(wo), Q4(so), G, H, qd, o, NULL, t1);
             for (int i = 0; i < H; ++i) x[i] += t1[i];
 
             /* SwiGLU MLP block */
             orc_rmsnorm(x, w->mlp_norm[l], H, c->rms_eps, h);
-            orc_gemv(w->w_gate[l], I, H, h, NULL, t1);
-            orc_gemv(w->w_up[l], I, H, h, NULL, t2);
+            proj(q4 ? NULL : w->w_gate[l], Q4(w_gate), Q4(s_gate), G, I, H, h, NULL, t1);
+            proj(q4 ? NULL : w->w_up[l], Q4(w_up), Q4(s_up), G, I, H, h, NULL, t2);
             for (int i = 0; i < I; ++i) t1[i] = orc_silu(t1[i]) * t2[i];
-            orc_gemv(w->w_down[l], H, I, t1, NULL, h);
+            proj(q4 ? NULL : w->w_down[l], Q4(w_down), Q4(s_down), G, H, I, t1, NULL, h);
             for (int i = 0; i < H; ++i) x[i] += h[i];
         }
 
@@ -255,6 +316,7 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, int batch,
             orc_gemv(head, V, H, h, NULL, logits + (size_t)b * V);
         }
     }
+#undef Q4
     free(x); free(h); free(q); free(k); free(v); free(o); free(t1); free(t2);
     return 0;
 }

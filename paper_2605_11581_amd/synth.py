@@ -133,6 +133,43 @@ def make_weights(cfg: Dict, seed: int | None = None, gain_jitter: float = 0.0,
     return w
 
 
+W4_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def make_quant(cfg: Dict, group: int = 128, seed: int | None = None, std: float = 0.02) -> Dict:
+    """The seven decoder projections in W4A16 form (stand-in for a GPTQ checkpoint): unsigned 4-bit
+    codes uniform in [0, 16), packed two per byte (k even in the low nibble), and one bf16 scale
+    per (row, group of ``group`` consecutive k) ~ std / 4.6 * (1 + 0.1 N(0,1)), so that the
+    dequantised weights (q - 8) * s have about the spread of the bf16 weights.  One Philox stream
+    per tensor name.  Keys: ``group``, the projection names (uint8 [out][in/2]) and ``s_<name>``
+    (uint16 bf16 bits [out][in/group]); per-layer entries are lists."""
+    seed = seed_of(cfg) if seed is None else seed
+    L, H, d = cfg["n_layers"], cfg["hidden"], cfg["head_dim"]
+    qd, kvd, I = cfg["n_q_heads"] * d, cfg["n_kv_heads"] * d, cfg["intermediate"]
+    shapes = {"wq": (qd, H), "wk": (kvd, H), "wv": (kvd, H), "wo": (H, qd), "w_gate": (I, H), "w_up": (I, H),
+              "w_down": (H, I)}
+    q: Dict = {"group": int(group)}
+    for name in W4_NAMES:
+        q[name], q["s_" + name] = [], []
+    for l in range(L):
+        for name in W4_NAMES:
+            n_out, n_in = shapes[name]
+            assert n_in % group == 0 and n_in % 2 == 0, f"{name}: K = {n_in} is not a multiple of the group size"
+            g = _rng(seed, f"l{l}.{name}.q4")
+            q[name].append(g.integers(0, 256, size=(n_out, n_in // 2), dtype=np.uint8))
+            q["s_" + name].append(normal_bf16(seed, f"l{l}.{name}.s4", (n_out, n_in // group), 0.1 * std / 4.6, std / 4.6))
+    return q
+
+
+def dequant(codes: np.ndarray, scale_bits: np.ndarray, group: int) -> np.ndarray:
+    """fp64 weights of one W4 matrix (for tests: an independent restatement of the format)."""
+    lo = (codes & 15).astype(np.int64)
+    hi = (codes >> 4).astype(np.int64)
+    qv = np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1) - 8
+    s = bf16_bits_to_f32(scale_bits).astype(np.float64)
+    return qv * np.repeat(s, group, axis=1)
+
+
 def make_prompt(cfg: Dict, n: int, seed: int | None = None, name: str = "prompt") -> np.ndarray:
     seed = seed_of(cfg) if seed is None else seed
     return _rng(seed, name).integers(0, cfg["vocab"], size=n, dtype=np.int32)

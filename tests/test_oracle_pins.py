@@ -338,3 +338,55 @@ def test_page_model_matches_paper_figures():
     assert oracle.pages_available(100, 1, 10, 10, 10, 30) == 2
     assert oracle.pages_available(100, 2, 10, 10, 10, 30) == 1
     assert oracle.pipeline_stages(10, 3, 1, 2, 3) == 1
+
+
+# ---- W4A16 form of the projections (Sec. 4.3.2; format: see the oracle's header) -----------------
+
+def test_w4_gemv_matches_unpacked_dequantised_matmul():
+    rng = np.random.default_rng(5)
+    for n_out, n_in, group in ((7, 64, 32), (16, 256, 128), (3, 128, 64)):
+        codes = rng.integers(0, 256, size=(n_out, n_in // 2), dtype=np.uint8)
+        scales = synth.to_bf16_bits(rng.normal(0.01, 0.003, size=(n_out, n_in // group)).astype(np.float32))
+        x = rng.normal(size=n_in).astype(np.float32)
+        bias = synth.to_bf16_bits(rng.normal(size=n_out).astype(np.float32))
+        want = synth.dequant(codes, scales, group) @ x.astype(np.float64) + synth.bf16_bits_to_f32(bias)
+        got = oracle.gemv_w4(codes, scales, group, x, bias)
+        assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
+
+
+def test_w4_nibble_order_zero_point_and_group_scale():
+    n_out, n_in, group = 4, 64, 32
+    codes = np.full((n_out, n_in // 2), 0x88, dtype=np.uint8)       # every code 8: all weights zero
+    scales = synth.to_bf16_bits(np.array([[0.5, 2.0]] * n_out, dtype=np.float32))
+    x = np.arange(1, n_in + 1, dtype=np.float32)
+    assert np.array_equal(oracle.gemv_w4(codes, scales, group, x), np.zeros(n_out, dtype=np.float32))
+    c = codes.copy()
+    c[1, 3] = 0x8B                # low nibble of byte 3 -> k = 6, code 11 -> +3, first group (scale 0.5)
+    assert oracle.gemv_w4(c, scales, group, x)[1] == 3 * 0.5 * x[6]
+    c = codes.copy()
+    c[2, 20] = 0x28               # high nibble of byte 20 -> k = 41, code 2 -> -6, second group (scale 2)
+    y = oracle.gemv_w4(c, scales, group, x)
+    assert y[2] == -6 * 2.0 * x[41] and y[0] == 0 and y[1] == 0 and y[3] == 0
+
+
+def test_w4_step_equals_bf16_step_when_the_dequantised_weights_are_bf16_values():
+    """With power-of-two scales every (q - 8) * s is a bf16 value: the W4 decoder must then
+    reproduce the bf16 decoder run on those very weights, up to fp64 rounding order."""
+    full = dict(synth.CONFIGS["c0_tiny"], intermediate=640, index=11)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full)
+    q = synth.make_quant(full, group=64)
+    rng = np.random.default_rng(1)
+    for name in synth.W4_NAMES:
+        for l in range(cfg["n_layers"]):
+            exps = rng.integers(-9, -6, size=q["s_" + name][l].shape)
+            q["s_" + name][l] = synth.to_bf16_bits(np.ldexp(1.0, exps).astype(np.float32))
+            w[name][l] = synth.to_bf16_bits(synth.dequant(q[name][l], q["s_" + name][l], 64).astype(np.float32))
+    a = oracle.Decoder(cfg, w)
+    b = oracle.Decoder(cfg, w, quant=q)
+    kva, kvb = a.new_kv(), b.new_kv()
+    for p, t in enumerate([5, 900, 17, 3000]):
+        la = a.step([t], [p], kva)[0]
+        lb = b.step([t], [p], kvb)[0]
+        assert np.abs(la - lb).max() <= 1e-5 * np.abs(la).max()
+    assert np.array_equal(kva, kvb)
