@@ -68,6 +68,11 @@ typedef struct mk_config {
     int32_t chunk_rows;      /* rows per 1 KB weight chunk for every matrix (2,4,8,16); 0 = search per matrix */
     int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head; /* the same per matrix (overrides chunk_rows);
                               * 0 = chunk_rows / search (the LM head defaults to 16)                              */
+    int32_t weight_bits;     /* 16 (or 0): bf16 matrices.  4: the seven decoder projections are W4A16 (Sec. 4.3.2):
+                              * unsigned 4-bit codes q, two per byte along K (even k in the low nibble), and one bf16
+                              * scale s per (row, group_size consecutive k): w = (q - 8) * s.  Embedding and LM head
+                              * stay bf16.  W4 needs max_batch == 1 and no page ring in this version.              */
+    int32_t group_size;      /* W4: 32, 64 or 128 (0 = 128); must divide hidden, n_q_heads*head_dim, intermediate  */
     uint32_t spin_limit;     /* dependency-wait poll limit; 0 = library default      */
     uint32_t flags;          /* MK_F_*                                               */
 } mk_config;
@@ -89,6 +94,9 @@ typedef struct mk_weights {
     const void *const *attn_norm, *const *wq, *const *wk, *const *wv;
     const void *const *bq, *const *bk, *const *bv, *const *q_norm, *const *k_norm;
     const void *const *wo, *const *mlp_norm, *const *w_gate, *const *w_up, *const *w_down;
+    /* weight_bits == 4 only: bf16 scales [out][in / group_size] of the seven projections; the matrix
+     * pointers above then address packed codes, uint8 [out][in / 2].  Ignored (may be NULL) otherwise. */
+    const void *const *sq, *const *sk, *const *sv, *const *so, *const *s_gate, *const *s_up, *const *s_down;
 } mk_weights;
 
 typedef struct mk_stats {
@@ -151,8 +159,8 @@ int mk_bind_workspace(mk_schedule *s, void *dev_workspace, size_t bytes, void *s
 
 /* Offline weight reorder (cf. Sec. 4.3.2 "weight reorder"): copy every matrix
  * into the workspace in the tile-major order the kernel streams (1 KB chunks of
- * R rows x 512/R consecutive k, lane-major; R is chosen per matrix by the
- * schedule search).  Asynchronous on `stream`; the caller's
+ * R rows x 512/R consecutive k of bf16 -- 2048/R of 4-bit codes -- lane-major; R
+ * is chosen per matrix by the schedule search; W4 scales go to a parallel array).  Asynchronous on `stream`; the caller's
  * buffers may be freed once the stream has been synchronised. */
 int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream);
 

@@ -32,7 +32,8 @@ class mk_config(C.Structure):
         ("rope_theta", C.c_float), ("rms_eps", C.c_float)] + [
         (n, C.c_int32) for n in ("max_batch", "max_context", "n_workgroups", "device_id", "use_mfma", "ring_kb",
                                  "split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows",
-                                 "rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head")] + [
+                                 "rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "weight_bits",
+                                 "group_size")] + [
         ("spin_limit", C.c_uint32), ("flags", C.c_uint32)]
 
 
@@ -42,7 +43,7 @@ _PP = C.POINTER(C.c_void_p)
 class mk_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + [
         (n, _PP) for n in ("attn_norm", "wq", "wk", "wv", "bq", "bk", "bv", "q_norm", "k_norm", "wo", "mlp_norm",
-                           "w_gate", "w_up", "w_down")]
+                           "w_gate", "w_up", "w_down", "sq", "sk", "sv", "so", "s_gate", "s_up", "s_down")]
 
 
 class mk_stats(C.Structure):
@@ -119,7 +120,7 @@ def _chk(rc: int) -> None:
 
 _CFG_DEFAULTS = dict(n_workgroups=0, device_id=0, use_mfma=-1, ring_kb=-1, split_qkv=0, split_o=0, split_gateup=0,
                      split_down=0, attn_chunks=0, chunk_rows=0, rows_qkv=0, rows_o=0, rows_gateup=0, rows_down=0,
-                     rows_head=0, spin_limit=0, flags=0)
+                     rows_head=0, weight_bits=16, group_size=0, spin_limit=0, flags=0)
 
 
 def make_config(model: Dict, **opts) -> mk_config:
@@ -220,7 +221,7 @@ def mk_load_weights(h, w: Dict, stream=None) -> None:
     ws.lm_head = _ptr(w.get("lm_head"))
     ws.final_norm = _ptr(w["final_norm"])
     for key in ("attn_norm", "wq", "wk", "wv", "bq", "bk", "bv", "q_norm", "k_norm", "wo", "mlp_norm", "w_gate",
-                "w_up", "w_down"):
+                "w_up", "w_down", "sq", "sk", "sv", "so", "s_gate", "s_up", "s_down"):
         arrs: Optional[Sequence] = w.get(key)
         if arrs is None:
             setattr(ws, key, None)

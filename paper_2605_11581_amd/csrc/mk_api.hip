@@ -60,6 +60,7 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.max_instr = (uint32_t)s->max_instr; P.flags = s->cfg.flags;
     P.embed_chunk = s->wm.embed; P.embed_kbt = (uint32_t)s->gm.head.kbt; P.embed_rlog = (uint32_t)s->gm.head.rlog;
     P.only_seq = mk::kNone; P.act_bytes = (uint32_t)(s->am.n_floats * 4);
+    P.w4_group = s->dm.w4 ? (uint32_t)s->dm.group : 0u;
     P.ctr_stride = dbg_knob("MK_DBG_CTR_STRIDE", mk::kCounterStride, 1, mk::kCounterStrideMax);
     P.poll_sleep = dbg_knob("MK_DBG_POLL_SLEEP", 0, 0, 64);
     P.dbg = dbg_knob("MK_DBG_UNSAFE_TIMING", 0, 0, 7);
@@ -153,7 +154,8 @@ int mk_get_stats(const mk_schedule *s, mk_stats *o)
     const mk::Geom &g = s->gm;
     auto chunks = [](const mk::MatGeom &m) { return (int64_t)m.groups * m.kbt; };
     int64_t per_layer = chunks(g.qkv) + chunks(g.o) + chunks(g.gu) + chunks(g.down);
-    o->weight_bytes_per_step = (per_layer * d.L + chunks(g.head)) * mk::kChunkBytes;
+    o->weight_bytes_per_step = (per_layer * d.L + chunks(g.head)) * mk::kChunkBytes +
+                               (d.w4 ? per_layer * d.L * (2048 / d.group) * 2 : 0);
     o->rows_qkv = g.qkv.R; o->rows_o = g.o.R; o->rows_gateup = g.gu.R; o->rows_down = g.down.R; o->rows_head = g.head.R;
     o->workspace_bytes = (int64_t)s->lay.total;
     o->sim_makespan_us = s->sim.makespan_us; o->sim_duty_cycle = s->sim.duty;
@@ -268,11 +270,25 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
 }
 
 static int repack(const void *src, int n_rows, int n_cols, mk_schedule *s, uint32_t chunk0, const mk::MatGeom &m,
-                  uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups, hipStream_t st)
+                  uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups, hipStream_t st, const void *scales = nullptr)
 {
     if (!src) { mk::set_error("mk_load_weights: a required matrix pointer is NULL"); return MK_EINVAL; }
     size_t total = (size_t)n_groups * m.kbt * 64;
     mk::u32x4 *dst = (mk::u32x4 *)(s->ws + s->lay.weights) + (size_t)chunk0 * 64;
+    if (m.w4) {
+        if (!scales) { mk::set_error("mk_load_weights: weight_bits is 4 but a scale pointer is NULL"); return MK_EINVAL; }
+        hipLaunchKernelGGL(mk_repack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t *)src,
+                           n_rows, n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups);
+        HIP_TRY(hipGetLastError());
+        const uint32_t spc = 2048u / (uint32_t)s->dm.group;
+        const size_t n_s = (size_t)n_groups * m.kbt * spc;
+        uint16_t *sdst = (uint16_t *)(s->ws + s->lay.wscale) + (size_t)chunk0 * spc;
+        hipLaunchKernelGGL(mk_repack_scales_kernel, dim3((unsigned)((n_s + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t *)scales, n_rows, n_cols, sdst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0,
+                           n_groups, (uint32_t)s->dm.group);
+        HIP_TRY(hipGetLastError());
+        return MK_OK;
+    }
     hipLaunchKernelGGL(mk_repack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t *)src, n_rows,
                        n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups);
     HIP_TRY(hipGetLastError());
@@ -303,20 +319,26 @@ int mk_load_weights(mk_schedule *s, const mk_weights *w, void *stream)
     }
     if (s->cfg.qkv_bias && (!w->bq || !w->bk || !w->bv)) { mk::set_error("mk_load_weights: qkv_bias set but a bias table is NULL"); return MK_EINVAL; }
     if (s->cfg.qk_norm && (!w->q_norm || !w->k_norm)) { mk::set_error("mk_load_weights: qk_norm set but a gain table is NULL"); return MK_EINVAL; }
+    const bool w4 = s->dm.w4 != 0;
+    if (w4 && (!w->sq || !w->sk || !w->sv || !w->so || !w->s_gate || !w->s_up || !w->s_down)) {
+        mk::set_error("mk_load_weights: weight_bits is 4 but a scale table is NULL");
+        return MK_EINVAL;
+    }
+    auto sc = [&](const void *const *tab, int l) -> const void * { return w4 ? tab[l] : nullptr; };
     int rc;
 #define TRY(x) do { rc = (x); if (rc) return rc; } while (0)
     const mk::Geom &g = s->gm;
     for (int l = 0; l < d.L; ++l) {
         const uint32_t R = (uint32_t)g.qkv.R;
-        TRY(repack(w->wq[l], d.qd, d.H, s, m.qkv[l], g.qkv, R, 0, 0, d.qd / R, st));
-        TRY(repack(w->wk[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, d.qd / R, d.kvd / R, st));
-        TRY(repack(w->wv[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, (d.qd + d.kvd) / R, d.kvd / R, st));
-        TRY(repack(w->wo[l], d.H, d.qd, s, m.o[l], g.o, (uint32_t)g.o.R, 0, 0, (uint32_t)g.o.groups, st));
+        TRY(repack(w->wq[l], d.qd, d.H, s, m.qkv[l], g.qkv, R, 0, 0, d.qd / R, st, sc(w->sq, l)));
+        TRY(repack(w->wk[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, d.qd / R, d.kvd / R, st, sc(w->sk, l)));
+        TRY(repack(w->wv[l], d.kvd, d.H, s, m.qkv[l], g.qkv, R, 0, (d.qd + d.kvd) / R, d.kvd / R, st, sc(w->sv, l)));
+        TRY(repack(w->wo[l], d.H, d.qd, s, m.o[l], g.o, (uint32_t)g.o.R, 0, 0, (uint32_t)g.o.groups, st, sc(w->so, l)));
         // gate rows fill the lower half of every row group, up rows the upper half
         const uint32_t half = (uint32_t)g.gu.R / 2;
-        TRY(repack(w->w_gate[l], d.I, d.H, s, m.gu[l], g.gu, half, 0, 0, (uint32_t)g.gu.groups, st));
-        TRY(repack(w->w_up[l], d.I, d.H, s, m.gu[l], g.gu, half, half, 0, (uint32_t)g.gu.groups, st));
-        TRY(repack(w->w_down[l], d.H, d.I, s, m.down[l], g.down, (uint32_t)g.down.R, 0, 0, (uint32_t)g.down.groups, st));
+        TRY(repack(w->w_gate[l], d.I, d.H, s, m.gu[l], g.gu, half, 0, 0, (uint32_t)g.gu.groups, st, sc(w->s_gate, l)));
+        TRY(repack(w->w_up[l], d.I, d.H, s, m.gu[l], g.gu, half, half, 0, (uint32_t)g.gu.groups, st, sc(w->s_up, l)));
+        TRY(repack(w->w_down[l], d.H, d.I, s, m.down[l], g.down, (uint32_t)g.down.R, 0, 0, (uint32_t)g.down.groups, st, sc(w->s_down, l)));
         TRY(copy_vec(w->attn_norm[l], d.H, ws, vb, m.g_attn[l], st));
         TRY(copy_vec(w->mlp_norm[l], d.H, ws, vb, m.g_mlp[l], st));
         if (s->cfg.qkv_bias) {

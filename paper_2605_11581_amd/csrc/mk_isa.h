@@ -55,14 +55,19 @@ enum Flags : uint32_t {
     F_ADD_RESID = 8u,   // epilogue adds the residual row (needs S == 1): out = resid + W x
     F_SILU_EPI = 16u,   // epilogue of the fused gate/up matrix (needs S == 1): out = silu(gate) * up
     F_ARGMAX = 32u,     // LM-head task: also leave (max logit, its row) per sequence in partial slot `spare`
-    F_WAIT_PREV = 64u   // wait_ctr[0] is awaited at the PREVIOUS step's target: the first tasks of a step wait
+    F_WAIT_PREV = 64u,  // wait_ctr[0] is awaited at the PREVIOUS step's target: the first tasks of a step wait
                         // for the greedy token (and with it for every task) of the step before
+    F_W4 = 128u         // the matrix is stored as 4-bit codes: a chunk holds four times the k of a bf16 chunk
 };
 
 // Weight chunk geometry.  A chunk is one wavefront-wide 128-bit load (1 KB): R rows x (512 / R)
 // consecutive k of bf16, lane = ksub * R + r holding W[row0 + r][k0 + 8 ksub .. + 8].  R is a
 // per-matrix tiling parameter (16 for the matrix-core path); rlog = log2 R.
 __host__ __device__ inline uint32_t chunk_k(uint32_t rlog) { return 512u >> rlog; }
+// W4 chunk: R rows x (2048 / R) consecutive k of 4-bit codes, lane = ksub * R + r holding the 32 codes
+// W[row0 + r][k0 + 32 ksub .. + 32] (code of k in bits 4 (k mod 8) of dword (k / 8) mod 4).  Every chunk
+// has 2048 / group scales (bf16), index (32 ksub / group) * R + r, in a parallel array.
+__host__ __device__ inline uint32_t chunk_k_w4(uint32_t rlog) { return 2048u >> rlog; }
 
 struct Instr {                 // 32 dwords
     uint32_t op;               // 0
@@ -98,6 +103,7 @@ struct Instr {                 // 32 dwords
     uint32_t spare;            // 31  F_ARGMAX: slot of this task in the arg-max partial buffer
 };
 __host__ __device__ inline uint32_t instr_pro(const Instr &I) { return I.cfg & 15u; }
+__host__ __device__ inline uint32_t instr_ck(const Instr &I) { return ((I.flags & F_W4) ? 2048u : 512u) >> ((I.cfg >> 4) & 15u); }
 __host__ __device__ inline uint32_t instr_rlog(const Instr &I) { return (I.cfg >> 4) & 15u; }
 __host__ __device__ inline uint32_t instr_prod_rlog(const Instr &I) { return (I.cfg >> 8) & 15u; }
 __host__ __device__ inline uint32_t instr_nparts(const Instr &I) { return (I.cfg >> 16) & 255u; }
@@ -132,6 +138,7 @@ static_assert(sizeof(InstrAtt) == kInstrDwords * 4, "instruction size");
 // Byte offsets into the caller-provided workspace.
 struct Layout {
     uint64_t weights;    // repacked matrices, 1 KB chunks
+    uint64_t wscale;     // W4 only: bf16 scales, 2048 / group per chunk, for the chunks of the decoder layers
     uint64_t vecs;       // bf16 vectors: norm gains, biases
     uint64_t rope;       // float [max_context][head_dim/2][2] (cos, sin)
     uint64_t act;        // fp32 activations, partial sums, attention partials
@@ -168,6 +175,7 @@ struct Params {
     uint32_t embed_kbt, embed_rlog;
     uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
     uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
+    uint32_t w4_group;    // W4: group size along K (32, 64 or 128); 0: bf16 weights
     uint32_t ctr_stride;  // dwords between dependency counters
     uint32_t poll_sleep;  // s_sleep units between two polls of a dependency counter
     uint32_t dbg;         // development only: bit 0 skip dependency waits, bit 1 skip the store drain (both: results invalid,

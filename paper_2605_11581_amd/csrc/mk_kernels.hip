@@ -225,6 +225,10 @@ __device__ __forceinline__ void st_act4(const ActBuf &a, uint32_t float_off, f32
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), a.r, (int)(float_off * 4u), 0, kAuxSc1);
 }
 
+// byte N of a dword as a float (selected as v_cvt_f32_ubyteN)
+template <int N>
+__device__ __forceinline__ float ubyte_f(uint32_t v) { return (float)((v >> (8 * N)) & 0xffu); }
+
 // (value, index) maximum over a wavefront; equal values keep the smaller index.  All lanes end with the result.
 __device__ __forceinline__ void argmax_wave(float &v, uint32_t &i)
 {
@@ -346,7 +350,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         }
     } else {
         // PLAIN / SILU: stage chunks [xs_lo, xs_lo + xs_hi) of the input (whole-K chunk indices)
-        const uint32_t ck = chunk_k(instr_rlog(I));
+        const uint32_t ck = instr_ck(I);
         const int k0 = (int)(I.xs_lo * ck), kn = (int)(I.xs_hi * ck);
         const uint32_t plane_stride = (uint32_t)kn * 2u + 16u;
         const uint32_t prl = instr_prod_rlog(I), PR = 1u << prl;
@@ -415,6 +419,21 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         }
     }
     wg_sync(lp, lds);
+    if (!MFMA && (I.flags & F_W4)) {
+        // W4: sums of every 32 consecutive staged values, behind the vector (the zero-point term of a
+        // lane's 32 codes is 8 times such a sum)
+        const bool nk = (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM);
+        const uint32_t ks = nk ? (uint32_t)P.hidden : I.xs_hi * instr_ck(I);
+        float *xsum = (float *)(xs + (size_t)ks * 4);
+        for (uint32_t blk = tid; blk < ks / 32u; blk += kWgThreads) {
+            const f32x4 *xp = (const f32x4 *)(xs + (size_t)blk * 128);
+            f32x4 acc = xp[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) acc += xp[i];
+            xsum[blk] = (acc.x + acc.y) + (acc.z + acc.w);
+        }
+        wg_sync(lp, lds);
+    }
 }
 
 // chunks in unit u of a matrix with S splits of nkb chunks per row group (last split ragged)
@@ -525,7 +544,15 @@ struct GemvStream {
     const __attribute__((address_space(1))) u32x4 *wp;   // this lane's pointer to chunk 0 of the task
     uint32_t total;       // chunks in the task
     u32x4 buf[kPrefetch]; // direct-load path only
+    const __attribute__((address_space(1))) uint16_t *sp;   // W4: this lane's scale of chunk 0 of the task
+    uint32_t spc;                                            // W4: scales per chunk (2048 / group)
 };
+// W4 tasks keep kPrefetchW4 chunks in flight per lane; the scales that go with them live in the
+// dwords of the unused buffers behind (no extra registers in the kernel's live set).
+constexpr int kPrefetchW4 = 12;
+static_assert(kPrefetchW4 + (kPrefetchW4 + 3) / 4 <= kPrefetch, "scales must fit behind the W4 chunk buffers");
+__device__ __forceinline__ uint32_t w4_scale_get(const GemvStream &st, int j) { return st.buf[kPrefetchW4 + (j >> 2)][j & 3]; }
+__device__ __forceinline__ void w4_scale_set(GemvStream &st, int j, uint32_t v) { st.buf[kPrefetchW4 + (j >> 2)][j & 3] = v; }
 
 // Issue the first weight loads of a GEMV task.  They depend on nothing the
 // previous operator produces, so this runs before the dependency wait.
@@ -540,6 +567,28 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
     if (RING) return;
     st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
     const uint32_t last = st.total ? st.total - 1 : 0;
+    const bool w4 = (I.flags & F_W4) != 0;
+    if (w4) {
+        // scale of this lane: group (32 ksub / group) of row r of the chunk, index g * R + r
+        const uint32_t rlog = instr_rlog(I), R = 1u << rlog;
+        const uint32_t sidx = (((uint32_t)lane >> rlog) * 32u / P.w4_group) * R + ((uint32_t)lane & (R - 1));
+        st.spc = 2048u / P.w4_group;
+        st.sp = (const __attribute__((address_space(1))) uint16_t *)(uintptr_t)(P.ws + P.lay.wscale) +
+                ((size_t)I.w_chunk + first) * st.spc + sidx;
+    }
+    if (w4) {
+#pragma unroll
+        for (int j = 0; j < kPrefetchW4; ++j) {
+            uint32_t idx = min((uint32_t)wave + (uint32_t)j * kWaves, last);
+            st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)idx * 64);
+        }
+#pragma unroll
+        for (int j = 0; j < kPrefetchW4; ++j) {
+            uint32_t idx = min((uint32_t)wave + (uint32_t)j * kWaves, last);
+            w4_scale_set(st, j, st.sp[(size_t)idx * st.spc]);
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) {
         if (j >= npf) continue;
@@ -548,11 +597,12 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
     }
 }
 
-template <bool MFMA, bool RING>
+template <bool MFMA, bool RING, bool W4 = false>
 __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, Wg &lp, GemvStream &st, int batch)
 {
+    static_assert(!(W4 && (MFMA || RING)), "W4 weights: VALU path with direct loads only");
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
-    const uint32_t rlog = instr_rlog(I), R = 1u << rlog, ck = chunk_k(rlog);
+    const uint32_t rlog = instr_rlog(I), R = 1u << rlog, ck = W4 ? chunk_k_w4(rlog) : chunk_k(rlog);
     const int ksub = lane >> rlog;
     char *xs = lds + lp.xs_off;
     float *red = (float *)(lds + kLdsRed);
@@ -607,7 +657,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         }
     };
 
-    auto consume = [&](const u32x4 &w) {
+    auto consume = [&](const u32x4 &w, uint32_t sbits = 0) {
         // advance to the unit that holds this chunk, flushing finished units
         while (kbi >= cur_n) {
             kbi -= cur_n;
@@ -617,7 +667,25 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             cur_kb0 = ((u0 + ul) % S) * nkb;
         }
         const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;  // chunk inside the staged vector
-        if (!MFMA) {
+        if (W4) {
+            // 32 codes of one row against 32 staged values: sum q x in fp32, then the zero point (8 times
+            // the sum of the 32 values, precomputed by the prologue) and the group scale
+            const uint32_t k0 = kb_rel * ck + (uint32_t)ksub * 32u;
+            const f32x4 *xp = (const f32x4 *)(xs + (size_t)k0 * 4);
+            const float *xsum = (const float *)(xs + (size_t)k_stage * 4);
+            const uint32_t dw[4] = {w.x, w.y, w.z, w.w};
+            float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = dw[i] & 0x0f0f0f0fu, hi = (dw[i] >> 4) & 0x0f0f0f0fu;
+                const f32x4 xa = xp[2 * i], xb = xp[2 * i + 1];
+                p0 += ubyte_f<0>(lo) * xa.x; p1 += ubyte_f<0>(hi) * xa.y;
+                p2 += ubyte_f<1>(lo) * xa.z; p3 += ubyte_f<1>(hi) * xa.w;
+                p0 += ubyte_f<2>(lo) * xb.x; p1 += ubyte_f<2>(hi) * xb.y;
+                p2 += ubyte_f<3>(lo) * xb.z; p3 += ubyte_f<3>(hi) * xb.w;
+            }
+            a0 += bf_to_f((uint16_t)sbits) * (((p0 + p1) + (p2 + p3)) - 8.0f * xsum[k0 >> 5]);
+        } else if (!MFMA) {
             const f32x4 *xp = (const f32x4 *)(xs + ((size_t)kb_rel * ck + ksub * 8) * 4);
             f32x4 x0 = xp[0], x1 = xp[1];
             a0 += bf_lo(w.x) * x0.x; a1 += bf_hi(w.x) * x0.y;
@@ -682,6 +750,21 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         for (uint32_t g = 0; g < ng; g += 2) {
             step(w0, w1, g);
             step(w1, w0, g + 1);
+        }
+    } else if (W4) {
+        if (total) {
+            const uint32_t last = total - 1;
+            constexpr uint32_t round = (uint32_t)kPrefetchW4 * kWaves;
+            for (uint32_t base = 0; base < total; base += round) {
+#pragma unroll
+                for (int j = 0; j < kPrefetchW4; ++j) {
+                    const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+                    if (idx < total) consume(st.buf[j], w4_scale_get(st, j));
+                    const uint32_t nidx = min(idx + round, last);
+                    st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
+                    w4_scale_set(st, j, st.sp[(size_t)nidx * st.spc]);
+                }
+            }
         }
     } else if (total) {
         const uint32_t last = total - 1;
@@ -1242,7 +1325,8 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         } else {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
             if (tracing && tid == 0) t2 = wall_clock64();
-            gemv_main<false, RING>(P, I, lds, lp, st, 1);
+            if (!RING && (I.flags & F_W4)) gemv_main<false, false, true>(P, I, lds, lp, st, 1);
+            else gemv_main<false, RING>(P, I, lds, lp, st, 1);
         }
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
@@ -1407,6 +1491,61 @@ extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int
     v.x = e[0] | ((uint32_t)e[1] << 16); v.y = e[2] | ((uint32_t)e[3] << 16);
     v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
     dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v;
+}
+
+// Offline reorder of a W4 matrix: codes row-major uint8 [n_rows][n_cols / 2] (even k in the low nibble)
+// -> chunks of R rows x 2048/R k; lane = ksub * R + r takes the 16 bytes holding k0 + 32 ksub .. + 32 of
+// its row.  Same row-group placement rules as mk_repack_kernel; rows and columns beyond the source are
+// code 8 (weight zero).
+extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, int n_cols, mk::u32x4 *dst, uint32_t kbt,
+                                               uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups)
+{
+    size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)n_groups * kbt * 64;
+    if (gid >= total) return;
+    const uint32_t R = 1u << rlog, ck = 2048u >> rlog;
+    uint32_t lane = (uint32_t)(gid & 63);
+    size_t c = gid >> 6;
+    uint32_t kb = (uint32_t)(c % kbt), grp = (uint32_t)(c / kbt);
+    uint32_t r = lane & (R - 1), ksub = lane >> rlog;
+    if (r < r_off || r >= r_off + rpu) return;
+    long row = (long)grp * rpu + (r - r_off);
+    const int k0 = (int)(kb * ck + ksub * 32);
+    uint32_t d[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int k = k0 + 8 * i + 2 * b;   // byte b of dword i: codes of k and k + 1 (n_cols is even)
+            const uint32_t byte = (row < n_rows && k < n_cols) ? src[(size_t)row * (n_cols / 2) + k / 2] : 0x88u;
+            v |= byte << (8 * b);
+        }
+        d[i] = v;
+    }
+    mk::u32x4 v4 = {d[0], d[1], d[2], d[3]};
+    dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v4;
+}
+
+// The scales that go with it: src bf16 [n_rows][n_cols / group] -> per chunk 2048/group values, index
+// g * R + r for group g of the chunk's k range and row r of the chunk; absent rows / groups get 0.
+extern "C" __global__ void mk_repack_scales_kernel(const uint16_t *src, int n_rows, int n_cols, uint16_t *dst, uint32_t kbt,
+                                                   uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0,
+                                                   uint32_t n_groups, uint32_t group)
+{
+    const uint32_t R = 1u << rlog, ck = 2048u >> rlog, spc = 2048u / group;
+    size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)n_groups * kbt * spc;
+    if (gid >= total) return;
+    uint32_t si = (uint32_t)(gid % spc);
+    size_t c = gid / spc;
+    uint32_t kb = (uint32_t)(c % kbt), grp = (uint32_t)(c / kbt);
+    uint32_t r = si & (R - 1), g = si >> rlog;
+    if (r < r_off || r >= r_off + rpu) return;
+    long row = (long)grp * rpu + (r - r_off);
+    const uint32_t kg = (kb * ck) / group + g;       // group index along K
+    const uint32_t n_kg = (uint32_t)n_cols / group;
+    dst[((size_t)(g0 + grp) * kbt + kb) * spc + si] = (row < n_rows && kg < n_kg) ? src[(size_t)row * n_kg + kg] : (uint16_t)0;
 }
 
 extern "C" __global__ void mk_copy_u16_kernel(const uint16_t *src, uint16_t *dst, size_t n)

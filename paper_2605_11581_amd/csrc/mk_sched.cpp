@@ -71,13 +71,23 @@ static int derive_dims(const mk_config &c, Dims &d)
     d.L = c.n_layers; d.H = c.hidden; d.nq = c.n_q_heads; d.nkv = c.n_kv_heads; d.d = c.head_dim;
     d.I = c.intermediate; d.V = c.vocab; d.Bm = c.max_batch; d.Tm = c.max_context; d.G = d.nq / d.nkv;
     d.qd = d.nq * d.d; d.kvd = d.nkv * d.d; d.nqkv = d.qd + 2 * d.kvd;
+    if (c.weight_bits != 0 && c.weight_bits != 16 && c.weight_bits != 4) return bad("weight_bits must be 16 or 4");
+    d.w4 = c.weight_bits == 4; d.group = 0;
+    if (d.w4) {
+        d.group = c.group_size ? c.group_size : 128;
+        if (d.group != 32 && d.group != 64 && d.group != 128) return bad("group_size must be 32, 64 or 128");
+        if (d.H % d.group || d.qd % d.group || d.I % d.group) return bad("group_size must divide hidden, n_q_heads*head_dim and intermediate");
+        if (d.Bm != 1) return bad("W4 weights need max_batch == 1 in this version");
+        if (c.ring_kb > 0) return bad("W4 weights cannot be combined with the page ring in this version");
+        if (c.use_mfma > 0) return bad("W4 weights run on the VALU path only in this version");
+    }
     return MK_OK;
 }
 
-static MatGeom mat_geom(int rlog, int n_rows, int k_len)
+static MatGeom mat_geom(int rlog, int n_rows, int k_len, int w4 = 0)
 {
     MatGeom g;
-    g.rlog = rlog; g.R = 1 << rlog; g.ck = 512 >> rlog;
+    g.rlog = rlog; g.R = 1 << rlog; g.ck = (w4 ? 2048 : 512) >> rlog; g.w4 = w4;
     g.groups = ceil_div(n_rows, g.R); g.kbt = ceil_div(k_len, g.ck);
     g.n_rows = n_rows; g.k_len = k_len;
     return g;
@@ -85,12 +95,12 @@ static MatGeom mat_geom(int rlog, int n_rows, int k_len)
 
 static void derive_geom(const Dims &d, const Tiling &t, Geom &g)
 {
-    g.qkv = mat_geom(t.r_qkv, d.nqkv, d.H);
-    g.o = mat_geom(t.r_o, d.H, d.qd);
+    g.qkv = mat_geom(t.r_qkv, d.nqkv, d.H, d.w4);
+    g.o = mat_geom(t.r_o, d.H, d.qd, d.w4);
     const int half = (1 << t.r_gu) / 2;
     g.ipad = ceil_div(d.I, std::max(half, 4)) * std::max(half, 4);
-    g.gu = mat_geom(t.r_gu, 2 * g.ipad, d.H);
-    g.down = mat_geom(t.r_d, d.H, d.I);
+    g.gu = mat_geom(t.r_gu, 2 * g.ipad, d.H, d.w4);
+    g.down = mat_geom(t.r_d, d.H, d.I, d.w4);
     g.head = mat_geom(t.r_head, d.V, d.H);
 }
 
@@ -111,6 +121,7 @@ static void plan_weights(const mk_config &c, const Dims &d, const Geom &g, Weigh
         if (c.qkv_bias) w.bias[l] = takev(d.nqkv);
         if (c.qk_norm) { w.qn[l] = takev(d.d); w.kn[l] = takev(d.d); }
     }
+    w.n_layer_chunks = ch;
     w.embed = take(g.head);
     w.head = c.tie_embeddings ? w.embed : take(g.head);
     w.g_final = takev(d.H);
@@ -150,7 +161,8 @@ static uint32_t att_scratch_bytes(const Dims &d)
 static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
 {
     int nterm = d.Bm <= 5 ? 3 : 2;
-    return t.mfma ? (uint32_t)(d.Bm * nterm) * ((uint32_t)d.H * 2u + 16u) : (uint32_t)d.H * 4u;
+    if (t.mfma) return (uint32_t)(d.Bm * nterm) * ((uint32_t)d.H * 2u + 16u);
+    return (uint32_t)d.H * 4u + (d.w4 ? (uint32_t)d.H / 32u * 4u + 16u : 0u);
 }
 
 // Eq. 1: what is left of the 160 KB after the per-stage fixed areas (instruction buffer,
@@ -208,7 +220,8 @@ struct Builder {
     uint32_t stage_bytes(uint32_t k_elems) const
     {
         int nterm = d.Bm <= 5 ? 3 : 2;
-        return t.mfma ? (uint32_t)(d.Bm * nterm) * (k_elems * 2u + 16u) : k_elems * 4u;
+        if (t.mfma) return (uint32_t)(d.Bm * nterm) * (k_elems * 2u + 16u);
+        return k_elems * 4u + (d.w4 ? k_elems / 32u * 4u + 16u : 0u);   // W4: sums of every 32 staged values follow the vector
     }
 
     // Partition the units of one GEMV operator instance over the workgroups and emit its tasks.
@@ -282,7 +295,7 @@ struct Builder {
                      uint32_t prod_rlog) const
     {
         Instr I{};
-        I.op = OP_GEMV; I.flags = t.mfma ? F_MFMA : 0u; I.ref_seq = (uint32_t)l * 8 + stage; I.layer = (uint32_t)l;
+        I.op = OP_GEMV; I.flags = (t.mfma ? F_MFMA : 0u) | (m.w4 ? F_W4 : 0u); I.ref_seq = (uint32_t)l * 8 + stage; I.layer = (uint32_t)l;
         I.w_chunk = w_chunk; I.kbt = (uint32_t)m.kbt; I.S = (uint32_t)S; I.nkb = (uint32_t)ceil_div(m.kbt, S);
         I.n_rows = (uint32_t)m.n_rows; I.k_len = (uint32_t)m.k_len;
         I.cfg = make_cfg(pro, (uint32_t)m.rlog, prod_rlog, n_parts);
@@ -510,7 +523,7 @@ static SimResult simulate(const mk_schedule *s)
             if (!(I.flags & F_SKIP_PRO)) {
                 const uint32_t pr = instr_pro(I), np = instr_nparts(I);
                 const bool normk = pr == PRO_EMBED_NORM || pr == PRO_RESID_NORM;
-                double fl = normk ? (double)d.H * (1 + np) : (double)I.xs_hi * chunk_k(instr_rlog(I)) * np * (pr == PRO_SILU ? 2 : 1);
+                double fl = normk ? (double)d.H * (1 + np) : (double)I.xs_hi * instr_ck(I) * np * (pr == PRO_SILU ? 2 : 1);
                 // one memory round trip per four partials in flight, plus the bytes themselves
                 pro = 0.8 + 0.8 * ((np + 3) / 4) + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
             }
@@ -579,6 +592,7 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     Layout &L = s->lay;
     uint64_t off = 0;
     L.weights = off; off = align_up(off + s->wm.n_chunks * kChunkBytes, 4096);
+    L.wscale = off; off = align_up(off + (d.w4 ? s->wm.n_layer_chunks * (2048u / d.group) * 2 : 0), 4096);
     L.vecs = off; off = align_up(off + s->wm.n_vec * 2, 4096);
     L.rope = off; off = align_up(off + (uint64_t)d.Tm * d.d * 4, 4096);
     L.act = off; off = align_up(off + s->am.n_floats * 4, 4096);
@@ -600,7 +614,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     Dims d;
     int rc = derive_dims(cfg, d);
     if (rc) return rc;
-    const int mfma = cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
+    const int mfma = d.w4 ? 0 : cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
     if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
     if (cfg.ring_kb < -2 || (cfg.ring_kb > 0 && (cfg.ring_kb < 16 || cfg.ring_kb > 144))) { set_error("mk_config: ring_kb must be -2 (search), -1 (auto), 0 (no ring) or 16..144"); return MK_EINVAL; }
 
@@ -723,7 +737,7 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
     auto rd = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), false}); };
     auto wr = [&](uint64_t lo, uint64_t n) { if (n) out.push_back({(uint32_t)lo, (uint32_t)(lo + n), true}); };
     if (I.op == OP_GEMV) {
-        const uint32_t pro = instr_pro(I), np = instr_nparts(I), rlog = instr_rlog(I), R = 1u << rlog, ck = chunk_k(rlog);
+        const uint32_t pro = instr_pro(I), np = instr_nparts(I), rlog = instr_rlog(I), R = 1u << rlog, ck = instr_ck(I);
         if (!(I.flags & F_SKIP_PRO)) {
             for (int b = 0; b < d.Bm; ++b) {
                 if (pro == PRO_RESID_NORM) {
@@ -1034,7 +1048,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 3;
+constexpr uint32_t kVersion = 4;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)

@@ -14,6 +14,7 @@ namespace mk {
 struct Dims {
     int L, H, nq, nkv, d, I, V, Bm, Tm, G;
     int qd, kvd, nqkv;       // fused QKV rows
+    int w4, group;           // 1: the decoder projections are 4-bit codes with one scale per `group` k
 };
 
 struct Tiling {              // the searched parameters (Sec. 4.2.2 Step 3, "tiling parameter space")
@@ -30,6 +31,7 @@ struct MatGeom {             // tile-major geometry of one matrix under a tiling
     int groups;              // row groups (of R rows)
     int kbt;                 // chunks per row group
     int n_rows, k_len;       // true output rows and K
+    int w4;                  // 4-bit codes: ck = 2048 / R instead of 512 / R
 };
 
 struct Geom {
@@ -43,6 +45,7 @@ struct WeightMap {           // chunk / element offsets inside the workspace
     std::vector<uint32_t> g_attn, g_mlp, bias, qn, kn;  // bf16 element offsets per layer (kNone if absent)
     uint32_t g_final;
     uint64_t n_chunks, n_vec;
+    uint64_t n_layer_chunks;                  // chunks of the decoder layers (they come first; W4 scales cover exactly these)
 };
 
 struct ActMap {              // float offsets inside the activation region

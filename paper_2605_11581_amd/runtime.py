@@ -14,7 +14,10 @@ from . import binding as mk
 def _dev_bits(a, device) -> torch.Tensor:
     if isinstance(a, torch.Tensor):
         return a
-    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint8:          # packed 4-bit codes
+        return torch.from_numpy(a).to(device)
+    return torch.from_numpy(a.view(np.int16)).to(device)
 
 
 def stage_weights(w: Dict, device) -> Dict:

@@ -161,6 +161,16 @@ def make_quant(cfg: Dict, group: int = 128, seed: int | None = None, std: float 
     return q
 
 
+def library_weights(w: Dict, q: Dict) -> Dict:
+    """The weight dict handed to the library for a W4 schedule: codes replace the seven bf16
+    matrices, scales go under sq, sk, sv, so, s_gate, s_up, s_down."""
+    out = dict(w)
+    for name in W4_NAMES:
+        out[name] = q[name]
+        out["s" + name[1:]] = q["s_" + name]
+    return out
+
+
 def dequant(codes: np.ndarray, scale_bits: np.ndarray, group: int) -> np.ndarray:
     """fp64 weights of one W4 matrix (for tests: an independent restatement of the format)."""
     lo = (codes & 15).astype(np.int64)

@@ -306,6 +306,68 @@ def test_batched_greedy_steps_in_one_launch_and_argument_checks():
     pr.close()
 
 
+# ---- W4A16 form of the decoder projections (Sec. 4.3.2) ------------------------------------------
+
+class PairW4(Pair):
+    """Oracle and GPU decoder over the same W4 codes / scales (embedding and LM head stay bf16)."""
+
+    def __init__(self, cfg, weights, quant, **opts):
+        self.cfg = cfg
+        self.orc = oracle.Decoder(cfg, weights, quant=quant)
+        self.kv_h = self.orc.new_kv()
+        self.dec = Decoder(cfg, device=DEV, weight_bits=4, group_size=quant["group"], **opts)
+        self.dec.load_weights(synth.library_weights(weights, quant))
+        self.kv_d = self.dec.new_kv(self.kv_h)
+        self.logits = torch.zeros(cfg["max_batch"], cfg["vocab"], dtype=torch.float32, device=DEV)
+
+
+@pytest.mark.parametrize("opts", [
+    dict(), dict(group=64), dict(group=32, qkv_bias=1), dict(chunk_rows=16), dict(chunk_rows=16, split_o=2, split_down=2),
+    dict(rows_gateup=16, split_gateup=2, split_qkv=2, attn_chunks=4), dict(n_workgroups=36, rows_down=4, rows_o=8),
+], ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()) or "default")
+def test_w4_c0_greedy_steps_match_oracle(opts):
+    opts = dict(opts)
+    group = opts.pop("group", 128)
+    full = tiny(intermediate=640, qkv_bias=opts.pop("qkv_bias", 0), index=13)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    q = synth.make_quant(full, group=group)
+    pr = PairW4(cfg, w, q, **opts)
+    say("W4 schedule", {k: pr.dec.stats[k] for k in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "split_o", "split_down")})
+    prompt = synth.make_prompt(full, 37)
+    pr.prefill(prompt[:-1])
+    cur_o = cur_g = int(prompt[-1])
+    for s in range(6):
+        p = 36 + s
+        want = pr.orc.step([cur_o], [p], pr.kv_h)[0]
+        got = pr.gpu_step([cur_g], [p])[0]
+        err = rel_err(got, want)
+        say("step", s, "rel err", err)
+        assert err <= TIGHT
+        if s == 0:
+            assert np.array_equal(got, pr.gpu_step([cur_g], [p], per_op=True)[0])
+        cur_o, cur_g = oracle.argmax(want), int(got.argmax())
+        assert cur_o == cur_g
+    # and the same as greedy steps of one launch
+    want_toks, _ = _greedy_oracle(pr, [cur_o], [42], 5)
+    t = torch.tensor([cur_g], dtype=torch.int32, device=DEV)
+    p = torch.tensor([42], dtype=torch.int32, device=DEV)
+    got_toks = pr.dec.greedy(t, p, pr.kv_d, pr.logits, 5)
+    pr.dec.check()
+    assert np.array_equal(got_toks.cpu().numpy(), want_toks)
+    pr.close()
+
+
+def test_w4_rejects_what_it_does_not_cover():
+    full = tiny(intermediate=640)
+    for bad in (dict(max_batch=2), dict(ring_kb=32), dict(use_mfma=1), dict(group_size=48), dict(intermediate=688)):
+        cfg = synth.model_cfg(dict(full, **{k: v for k, v in bad.items() if k in ("max_batch", "intermediate")}))
+        opts = {k: v for k, v in bad.items() if k not in ("max_batch", "intermediate")}
+        with pytest.raises(mk.MkError) as e:
+            mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=64, weight_bits=4, **opts))
+        assert e.value.code == mk.MK_EINVAL, bad
+
+
 def test_two_runs_are_bit_identical():
     full = tiny()
     cfg = synth.model_cfg(full)
