@@ -20,17 +20,20 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(cfg, batch: int, T: float) -> float:
-    """Bytes one decode step must move: every weight once (bf16), K and V once per KV head for the
-    T attended positions (bf16), logits written (fp32)."""
+def algorithmic_bytes(cfg, batch: int, T: float, w4_group: int = 0) -> float:
+    """Bytes one decode step must move: every weight once (bf16; with W4 the seven projections are
+    half a byte per element plus one bf16 scale per group), K and V once per KV head for the T
+    attended positions (bf16), logits written (fp32)."""
     L, H, d = cfg["n_layers"], cfg["hidden"], cfg["head_dim"]
     qd, kvd, I, V = cfg["n_q_heads"] * d, cfg["n_kv_heads"] * d, cfg["intermediate"], cfg["vocab"]
-    per_layer = H * (qd + 2 * kvd) + qd * H + 3 * H * I + 2 * H
+    mats = H * (qd + 2 * kvd) + qd * H + 3 * H * I
+    vecs = 2 * H
     if cfg["qkv_bias"]:
-        per_layer += qd + 2 * kvd
+        vecs += qd + 2 * kvd
     if cfg["qk_norm"]:
-        per_layer += 2 * d
-    weights = 2.0 * (L * per_layer + V * H + H)
+        vecs += 2 * d
+    mat_bytes = mats * (0.5 + 2.0 / w4_group) if w4_group else 2.0 * mats
+    weights = L * (mat_bytes + 2.0 * vecs) + 2.0 * (V * H + H)
     kv = batch * 4.0 * L * kvd * T
     return weights + kv + 4.0 * batch * V
 
@@ -58,6 +61,7 @@ def main() -> int:
     ap.add_argument("--no-per-op", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy (counter calibration)")
     ap.add_argument("--opt", action="append", default=[], help="schedule override key=value (e.g. split_down=4)")
+    ap.add_argument("--w4", action="store_true", help="W4A16 decoder projections (group 128) instead of bf16")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -82,8 +86,15 @@ def main() -> int:
     w = synth.make_weights(full)
     kv_h = synth.make_kv_fill(cfg, ctx0, seed=synth.seed_of(full), batch=B)
     t_gen = time.time() - t0
-    dec = Decoder(cfg, device=dev, **opts)
-    dec.load_weights(w)
+    w4_group = 128 if args.w4 else 0
+    quant = None
+    if args.w4:
+        quant = synth.make_quant(full, group=w4_group)
+        dec = Decoder(cfg, device=dev, weight_bits=4, group_size=w4_group, **opts)
+        dec.load_weights(synth.library_weights(w, quant))
+    else:
+        dec = Decoder(cfg, device=dev, **opts)
+        dec.load_weights(w)
     kv_d = dec.new_kv(kv_h)
     n_all = steps + warmup
     rng = np.random.default_rng(synth.seed_of(full))
@@ -125,16 +136,17 @@ def main() -> int:
     mk.mk_set_flags(dec.h, 0)
     kern_ms = float(np.mean(durs))
     T_ev = ctx0 + warmup + (n_ev - 1) / 2.0 + 1
-    bytes_launch = algorithmic_bytes(cfg, B, T_ev)
+    bytes_launch = algorithmic_bytes(cfg, B, T_ev, w4_group)
     achieved = bytes_launch / (kern_ms * 1e-3) / 1e9
     T_run = ctx0 + warmup + (steps - 1) / 2.0 + 1
-    bytes_step = algorithmic_bytes(cfg, B, T_run)
+    bytes_step = algorithmic_bytes(cfg, B, T_run, w4_group)
 
     out = {
         "metric": "decode tokens/s at batch 1 (1.5B shape); achieved HBM GB/s vs peak",
         "value": round(tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights/KV, f32 accumulate", "data": "synthetic",
+        "dtype": ("w4 (group 128) projections, bf16 embedding/LM head/KV, f32 accumulate" if args.w4
+                  else "bf16 weights/KV, f32 accumulate"), "data": "synthetic",
         "config": {"workload": f"{args.config}: Qwen2.5-1.5B-shaped decoder, batch {B}, KV context {ctx0}+step, "
                                f"{steps} single-launch decode steps", "batch": B, "context0": ctx0,
                    "schedule": {k: dec.stats[k] for k in ("n_workgroups", "split_qkv", "split_o", "split_gateup",
@@ -142,7 +154,7 @@ def main() -> int:
                                                           "rows_down", "rows_head", "use_mfma", "ring_pages", "lds_bytes")}},
         "hbm_gbs_whole_run": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config) if B == 1 else None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.config) if B == 1 and not args.w4 else None,
                      "kernel": "mk_megakernel", "kernel_ms": round(kern_ms, 5), "algorithmic_bytes": int(bytes_launch)},
     }
 
@@ -176,7 +188,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         import oracle
-        orc = oracle.Decoder(cfg, w)
+        orc = oracle.Decoder(cfg, w, quant=quant)
         th = toks.cpu().numpy(); ph = poss.cpu().numpy()
         t3 = time.perf_counter()
         orc.step(th[0], ph[0], kv_h)

@@ -40,19 +40,19 @@ _STAT_OF = {"split_o": "split_o", "rows_down": "rows_down", "rows_gateup": "rows
             "rows_head": "rows_head", "split_gateup": "split_gateup"}
 
 
-def shape_key(model: Dict, n_workgroups: int) -> str:
+def shape_key(model: Dict, n_workgroups: int, weight_bits: int = 16) -> str:
     dims = ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "intermediate", "vocab", "max_batch")
-    return "-".join(str(int(model[k])) for k in dims) + f"-wg{int(n_workgroups)}"
+    return "-".join(str(int(model[k])) for k in dims) + f"-wg{int(n_workgroups)}-w{int(weight_bits) or 16}"
 
 
-def tuned_opts(model: Dict, n_workgroups: int) -> Dict[str, int]:
-    """Tiling overrides recorded for this model shape and grid size ({} if none)."""
+def tuned_opts(model: Dict, n_workgroups: int, weight_bits: int = 16) -> Dict[str, int]:
+    """Tiling overrides recorded for this model shape, grid size and weight format ({} if none)."""
     try:
         with open(TABLE) as f:
             table = json.load(f)
     except OSError:
         return {}
-    entry = table.get(shape_key(model, n_workgroups))
+    entry = table.get(shape_key(model, n_workgroups, weight_bits))
     return dict(entry["opts"]) if entry else {}
 
 
@@ -127,6 +127,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--steps", type=int, default=24)
     ap.add_argument("--rounds", type=int, default=2)
+    ap.add_argument("--w4", action="store_true", help="tune the W4A16 form (group 128) of the decoder projections")
     ap.add_argument("--write", action="store_true", help="record the result in tuned.json")
     args = ap.parse_args()
     import torch
@@ -136,18 +137,25 @@ def main() -> int:
     full = synth.CONFIGS[args.config]
     model = synth.model_cfg(full, max_batch=args.batch, max_context=full["ctx0"] + 512)
     dev = "cuda:0"
-    w = stage_weights(synth.make_weights(full), dev)
+    host_w = synth.make_weights(full)
+    base = {}
+    if args.w4:
+        host_w = synth.library_weights(host_w, synth.make_quant(full))
+        base = dict(weight_bits=4, group_size=128)
+    w = stage_weights(host_w, dev)
     n_wg = torch.cuda.get_device_properties(0).multi_processor_count
     pos = full["ctx0"] + 128
-    best, ms, hist = autotune(model, w, pos, device=dev, steps=args.steps, rounds=args.rounds,
+    bits = 4 if args.w4 else 16
+    best, ms, hist = autotune(model, w, pos, device=dev, steps=args.steps, rounds=args.rounds, base_opts=base,
                               log=lambda s: print(s, flush=True))
-    print(json.dumps({"config": args.config, "key": shape_key(model, n_wg), "opts": best, "ms_per_step": round(ms, 5)}))
+    key = shape_key(model, n_wg, bits)
+    print(json.dumps({"config": args.config, "key": key, "opts": best, "ms_per_step": round(ms, 5)}))
     if args.write:
         try:
             table = json.load(open(TABLE))
         except OSError:
             table = {}
-        table[shape_key(model, n_wg)] = {"opts": best, "ms_per_step": round(ms, 5), "position": pos,
+        table[key] = {"opts": best, "ms_per_step": round(ms, 5), "position": pos,
                                          "workload": args.config, "candidates_timed": len(hist)}
         with open(TABLE, "w") as f:
             json.dump(table, f, indent=1, sort_keys=True)

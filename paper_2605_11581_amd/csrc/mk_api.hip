@@ -205,6 +205,9 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_steps, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_steps_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     int per_cu = 0;
@@ -374,6 +377,9 @@ static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *po
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     if (s->tl.ring_pages && !(P.dbg & 4u))
         hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    else if (s->dm.w4)
+        hipLaunchKernelGGL(n_steps > 1 ? mk_megakernel_steps_w4 : mk_megakernel_w4, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads),
+                           s->lds_total, st, P, lp);
     else if (n_steps > 1)
         hipLaunchKernelGGL(mk_megakernel_steps, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     else
@@ -413,7 +419,7 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     for (uint32_t seq : s->ref_seqs) {
         P.only_seq = seq;
-        hipLaunchKernelGGL(mk_op_kernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+        hipLaunchKernelGGL(s->dm.w4 ? mk_op_kernel_w4 : mk_op_kernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     }
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));

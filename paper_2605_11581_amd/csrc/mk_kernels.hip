@@ -556,7 +556,7 @@ __device__ __forceinline__ void w4_scale_set(GemvStream &st, int j, uint32_t v) 
 
 // Issue the first weight loads of a GEMV task.  They depend on nothing the
 // previous operator produces, so this runs before the dependency wait.
-template <bool RING>
+template <bool RING, bool W4>
 __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st, int npf)
 {
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
@@ -567,7 +567,7 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
     if (RING) return;
     st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
     const uint32_t last = st.total ? st.total - 1 : 0;
-    const bool w4 = (I.flags & F_W4) != 0;
+    const bool w4 = W4 && (I.flags & F_W4) != 0;
     if (w4) {
         // scale of this lane: group (32 ksub / group) of row r of the chunk, index g * R + r
         const uint32_t rlog = instr_rlog(I), R = 1u << rlog;
@@ -1264,7 +1264,7 @@ __device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, u
 }
 
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
-template <bool PERSISTENT, bool RING>
+template <bool PERSISTENT, bool RING, bool W4>
 __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
                                            bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr)
 {
@@ -1281,7 +1281,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u) && !no_dep;
     GemvStream st;
     AttStream as;
-    if (I.op == OP_GEMV) gemv_issue<RING>(P, I, st, lp.npf);
+    if (I.op == OP_GEMV) gemv_issue<RING, W4>(P, I, st, lp.npf);
     else if (I.op == OP_ATT) {
         if (P.head_dim == 128) att_issue<128>(P, lp, *(const InstrAtt *)&I, as);
         else att_issue<64>(P, lp, *(const InstrAtt *)&I, as);
@@ -1318,14 +1318,14 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
 
     uint64_t t2 = 0;
     if (I.op == OP_GEMV) {
-        if (I.flags & F_MFMA) {
+        if (!W4 && (I.flags & F_MFMA)) {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
             if (tracing && tid == 0) t2 = wall_clock64();
             gemv_main<true, RING>(P, I, lds, lp, st, P.batch);
         } else {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
             if (tracing && tid == 0) t2 = wall_clock64();
-            if (!RING && (I.flags & F_W4)) gemv_main<false, false, true>(P, I, lds, lp, st, 1);
+            if (W4 && (I.flags & F_W4)) gemv_main<false, false, true>(P, I, lds, lp, st, 1);
             else gemv_main<false, RING>(P, I, lds, lp, st, 1);
         }
     } else if (I.op == OP_ATT) {
@@ -1381,7 +1381,7 @@ __device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *l
 
 // Persistent walk of this workgroup's whole list; the next instruction is fetched while the
 // current one runs.
-template <bool RING, bool MULTI>
+template <bool RING, bool MULTI, bool W4 = false>
 __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1410,7 +1410,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
             const bool more = pc + 1 < P.max_instr;
             if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
             if (RING) pin_uniform(lp);
-            exec_instr<true, RING>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
+            exec_instr<true, RING, W4>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
         }
     }
     // no DMA load may still be writing LDS when the workgroup retires
@@ -1419,6 +1419,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
 
 // One operator instance: the instructions of this workgroup whose ref_seq matches (they are
 // adjacent in the list), found with one parallel scan.
+template <bool W4>
 __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1441,7 +1442,7 @@ __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
         wg_sync(lp, lds);
         Instr I;
         read_instr(sinstr, I);
-        exec_instr<false, false>(P, lp, lds, I, pc, dead);
+        exec_instr<false, false, W4>(P, lp, lds, I, pc, dead);
     }
 }
 
@@ -1459,7 +1460,16 @@ extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
 mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true, true>(P, lp); }
 
 extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op(P, lp); }
+mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op<false>(P, lp); }
+
+// The same three walks for schedules whose decoder projections are 4-bit codes (kept apart so that
+// the bf16 kernels carry none of the W4 code).
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
+mk_megakernel_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, false, true>(P, lp); }
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
+mk_megakernel_steps_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, true, true>(P, lp); }
+extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
+mk_op_kernel_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op<true>(P, lp); }
 
 // Offline weight reorder: row-major bf16 [n_rows][n_cols] -> tile-major chunks of R = 1 << rlog rows.
 // Source row i lands in row group g0 + i / rpu at row r_off + i % rpu of the group (rpu = R and

@@ -50,7 +50,7 @@ class Decoder:
             if not (_TILING_KEYS & set(opts)):
                 from .autotune import tuned_opts
                 n_wg = opts.get("n_workgroups") or torch.cuda.get_device_properties(self.device).multi_processor_count
-                opts = {**tuned_opts(model, n_wg), **opts}
+                opts = {**tuned_opts(model, n_wg, opts.get("weight_bits", 16)), **opts}
             self.h = mk.mk_build_schedule(mk.make_config(model, device_id=self.device.index or 0, **opts))
         self.stats = mk.mk_get_stats(self.h)
         self.workspace = torch.empty(mk.mk_workspace_bytes(self.h), dtype=torch.uint8, device=self.device)

@@ -418,14 +418,19 @@ def test_error_paths_leave_the_kernel_running_to_completion():
     dec.close()
 
 
-def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, **opts):
+def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, w4=False, **opts):
     full = synth.CONFIGS[name]
     cfg = synth.model_cfg(full, max_batch=batch)
     say(name, ": generating weights")
     w = synth.make_weights(full)
     ctx0 = full["ctx0"]
     kv_h = synth.make_kv_fill(cfg, ctx0, seed=synth.seed_of(full), batch=batch)
-    pr = Pair(cfg, w, kv_host=kv_h, **opts)
+    if w4:
+        pr = PairW4(cfg, w, synth.make_quant(full), **opts)
+        pr.kv_h = kv_h
+        pr.kv_d = pr.dec.new_kv(kv_h)
+    else:
+        pr = Pair(cfg, w, kv_host=kv_h, **opts)
     say(name, ": schedule", {k: v for k, v in pr.dec.stats.items() if k.startswith(("split", "rows", "attn", "use"))})
     rng = np.random.default_rng(synth.seed_of(full))
     n = max(steps_idx) + 1
@@ -452,6 +457,11 @@ def test_c1_half_billion_shape_teacher_forced():
 def test_c2_headline_shape_in_bench_configuration():
     """Same configuration bench.py times (default schedule search, one launch per step)."""
     _teacher_forced("c2_1p5b", (0, 1, 3))
+
+
+def test_c2_headline_shape_with_w4_weights():
+    """The 1.5B shape in the precision the paper measures (Sec. 5.1: GPTQ-W4A16), as bench.py --w4 times it."""
+    _teacher_forced("c2_1p5b", (0, 2), w4=True)
 
 
 @pytest.mark.skipif(os.environ.get("MK_TEST_LARGE") != "1", reason="set MK_TEST_LARGE=1 (minutes of host-side weight generation)")

@@ -137,13 +137,14 @@ def test_recorded_profile_guided_tilings_build_and_verify():
     by_key = {}
     for name, full in synth.CONFIGS.items():
         for b in (1, 2, 4, 8):
-            by_key[autotune.shape_key(synth.model_cfg(full, max_batch=b), 256)] = (name, b)
+            for bits in (16, 4):
+                by_key[autotune.shape_key(synth.model_cfg(full, max_batch=b), 256, bits)] = (name, b, bits)
     for key, entry in table.items():
         assert key in by_key, f"{key} matches no known configuration"
-        name, b = by_key[key]
+        name, b, bits = by_key[key]
         model = synth.model_cfg(synth.CONFIGS[name], max_batch=b)
-        assert autotune.tuned_opts(model, 256) == entry["opts"]
-        h = mk.mk_build_schedule(mk.make_config(model, n_workgroups=256, **entry["opts"]))
+        assert autotune.tuned_opts(model, 256, bits) == entry["opts"]
+        h = mk.mk_build_schedule(mk.make_config(model, n_workgroups=256, weight_bits=bits, **entry["opts"]))
         mk.mk_schedule_verify(h)
         st = mk.mk_get_stats(h)
         for k, v in entry["opts"].items():
