@@ -68,6 +68,9 @@ typedef struct mk_config {
     int32_t chunk_rows;      /* rows per 1 KB weight chunk for every matrix (2,4,8,16); 0 = search per matrix */
     int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head; /* the same per matrix (overrides chunk_rows);
                               * 0 = chunk_rows / search (the LM head defaults to 16)                              */
+    int32_t fuse_combine;    /* 1: no separate combine tasks -- every O-projection task combines the attention partials of
+                              * the heads its K range covers in its own prologue (one dependency level less per layer);
+                              * 0: combine tasks; -1: auto (currently 0)                                          */
     int32_t weight_bits;     /* 16 (or 0): bf16 matrices.  4: the seven decoder projections are W4A16 (Sec. 4.3.2):
                               * unsigned 4-bit codes q, two per byte along K (even k in the low nibble), and one bf16
                               * scale s per (row, group_size consecutive k): w = (q - 8) * s.  Embedding and LM head
@@ -109,7 +112,7 @@ typedef struct mk_stats {
     double sim_duty_cycle;           /* sum of busy time / (workgroups * makespan)     */
     int32_t candidates_tried, candidates_pruned;
     int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head;  /* rows per 1 KB weight chunk, per matrix */
-    int32_t reserved;
+    int32_t fuse_combine;
 } mk_stats;
 
 /* Phase I (host only, touches no GPU unless n_workgroups == 0): build the

@@ -32,7 +32,7 @@ class mk_config(C.Structure):
         ("rope_theta", C.c_float), ("rms_eps", C.c_float)] + [
         (n, C.c_int32) for n in ("max_batch", "max_context", "n_workgroups", "device_id", "use_mfma", "ring_kb",
                                  "split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows",
-                                 "rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "weight_bits",
+                                 "rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "fuse_combine", "weight_bits",
                                  "group_size")] + [
         ("spin_limit", C.c_uint32), ("flags", C.c_uint32)]
 
@@ -53,7 +53,7 @@ class mk_stats(C.Structure):
         ("_pad", C.c_int32), ("weight_bytes_per_step", C.c_int64), ("workspace_bytes", C.c_int64),
         ("sim_makespan_us", C.c_double), ("sim_duty_cycle", C.c_double),
         ("candidates_tried", C.c_int32), ("candidates_pruned", C.c_int32)] + [
-        (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "reserved")]
+        (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "fuse_combine")]
 
 
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",
@@ -120,7 +120,7 @@ def _chk(rc: int) -> None:
 
 _CFG_DEFAULTS = dict(n_workgroups=0, device_id=0, use_mfma=-1, ring_kb=-1, split_qkv=0, split_o=0, split_gateup=0,
                      split_down=0, attn_chunks=0, chunk_rows=0, rows_qkv=0, rows_o=0, rows_gateup=0, rows_down=0,
-                     rows_head=0, weight_bits=16, group_size=0, spin_limit=0, flags=0)
+                     rows_head=0, fuse_combine=-1, weight_bits=16, group_size=0, spin_limit=0, flags=0)
 
 
 def make_config(model: Dict, **opts) -> mk_config:

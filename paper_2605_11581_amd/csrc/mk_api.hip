@@ -160,6 +160,7 @@ int mk_get_stats(const mk_schedule *s, mk_stats *o)
     o->workspace_bytes = (int64_t)s->lay.total;
     o->sim_makespan_us = s->sim.makespan_us; o->sim_duty_cycle = s->sim.duty;
     o->candidates_tried = s->cand_tried; o->candidates_pruned = s->cand_pruned;
+    o->fuse_combine = s->tl.fuse;
     return MK_OK;
 }
 

@@ -45,7 +45,10 @@ enum Pro : uint32_t {
     PRO_EMBED_NORM = 0,  // x = embedding row; store slice; RMSNorm
     PRO_RESID_NORM = 1,  // x = base + sum(partials); store slice; RMSNorm
     PRO_PLAIN = 2,       // x[k] = sum(partials)[k] over the unit's k range
-    PRO_SILU = 3         // x[k] = silu(sum gate partials[k]) * sum up partials[k]
+    PRO_SILU = 3,        // x[k] = silu(sum gate partials[k]) * sum up partials[k]
+    PRO_COMBINE = 4      // x = flash-decode combine of the n_parts attention partials of the heads that cover the
+                         // unit's k range (the O projection reading the attention partials directly);
+                         // in_base = byte offset, inside the staged-input area, of the partial-row staging
 };
 
 enum Flags : uint32_t {

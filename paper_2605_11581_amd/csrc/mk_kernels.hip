@@ -133,6 +133,13 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
 // Cross-lane sums inside a 16-lane row with DPP (no LDS crossbar traffic).  Every step pairs
 // lanes symmetrically, so all lanes of the group end with bit-identical sums.
 template <int CTRL>
@@ -356,6 +363,51 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         const uint32_t prl = instr_prod_rlog(I), PR = 1u << prl;
         for (int b = 0; b < batch; ++b) {
             const uint32_t brow = (uint32_t)b * I.in_ld;
+            if (pro == PRO_COMBINE) {
+                // The attention partials of the heads that cover this task's k range, combined here
+                // (flash-decode merge in fixed chunk order) instead of by separate combine tasks.
+                const int D = P.head_dim, RS = D + 4, nc = (int)n_parts;      // rows are [acc[D], m, l, pad, pad]
+                const int k1 = min(k0 + kn, (int)I.k_len);
+                const int h0 = k0 / D, nh = (k1 - k0) / D;
+                float *stg = (float *)(xs + I.in_base);                      // [nh][nc][RS] partial rows
+                float *wgt = stg + (size_t)nh * nc * RS;                     // [nh][nc] merge weights f_c / L
+                const uint32_t src = I.in_parts + (uint32_t)(((size_t)b * P.n_q_heads + h0) * nc) * (uint32_t)RS;
+                const int nq4 = nh * nc * RS / 4;
+                if (b) wg_sync(lp, lds);                                      // the previous sequence is done with the staging
+                for (int q0 = tid; q0 < nq4; q0 += kWgThreads * 4) {
+                    f32x4 v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int q = q0 + u * kWgThreads;
+                        v[u] = ld_act4(ab, q < nq4 ? src + 4u * q : 0xfffffff0u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int q = q0 + u * kWgThreads;
+                        if (q < nq4) *(f32x4 *)(stg + 4 * q) = v[u];
+                    }
+                }
+                wg_sync(lp, lds);
+                for (int h = wave; h < nh; h += kWaves) {                    // one wave per head, one lane per chunk
+                    const float *row = stg + ((size_t)h * nc + min(lane, nc - 1)) * RS;
+                    const float m = lane < nc ? row[D] : -INFINITY, l = lane < nc ? row[D + 1] : 0.f;
+                    const float M = wave_max(m);
+                    const float f = (m == -INFINITY) ? 0.f : __expf(m - M);
+                    const float L = wave_sum(f * l);
+                    if (lane < nc) wgt[h * nc + lane] = f / L;
+                }
+                wg_sync(lp, lds);
+                for (int q = tid; q < nh * D / 4; q += kWgThreads) {
+                    const int h = (4 * q) / D, i = (4 * q) % D;
+                    const float *rows = stg + (size_t)h * nc * RS + i;
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                    for (int c = 0; c < nc; ++c) acc += wgt[h * nc + c] * *(const f32x4 *)(rows + (size_t)c * RS);
+                    store_x4<MFMA>(xs, b, 4 * q, acc, nterm, plane_stride);
+                }
+                for (int q = nh * D / 4 + tid; q < kn / 4; q += kWgThreads)   // staged k beyond the true K are zero
+                    store_x4<MFMA>(xs, b, 4 * q, f32x4{0.f, 0.f, 0.f, 0.f}, nterm, plane_stride);
+                continue;
+            }
             if (pro == PRO_PLAIN && n_parts == 1) {
                 // common case (unsplit producer): eight 128-bit loads in flight per lane, one memory round
                 // trip for up to 8192 staged elements

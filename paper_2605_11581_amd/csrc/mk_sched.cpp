@@ -224,6 +224,14 @@ struct Builder {
         return k_elems * 4u + (d.w4 ? k_elems / 32u * 4u + 16u : 0u);   // W4: sums of every 32 staged values follow the vector
     }
 
+    // LDS bytes a PRO_COMBINE task needs behind its staged vector of k_elems values: the partial rows
+    // [head][chunk][d + pad] of the heads covering the k range (one sequence at a time) and their weights.
+    uint32_t combine_bytes(uint32_t k_elems) const
+    {
+        const uint32_t nh = (k_elems + (uint32_t)d.d - 1) / (uint32_t)d.d;
+        return nh * (uint32_t)t.nc * (uint32_t)(d.d + kPartPad + 1) * 4u + 16u;
+    }
+
     // Partition the units of one GEMV operator instance over the workgroups and emit its tasks.
     // `proto` carries everything except u0/nu/staged range/skip flag/signal.  Returns false if a task cannot fit LDS.
     bool emit_gemv(Instr proto, const MatGeom &m, uint32_t wait_ctr, uint32_t sig_ctr)
@@ -251,7 +259,7 @@ struct Builder {
                     uint32_t uu = u + nu, s = uu % S;
                     uint32_t lo = s * nkb, hi = (s == S - 1) ? kbt : lo + nkb;
                     uint32_t nlo = nu ? std::min(klo, lo) : lo, nhi = nu ? std::max(khi, hi) : hi;
-                    if (!normk && stage_bytes((nhi - nlo) * m.ck) > lb.xs_cap) break;
+                    if (!normk && stage_bytes((nhi - nlo) * m.ck) + (pro == PRO_COMBINE ? combine_bytes((nhi - nlo) * m.ck) : 0u) > lb.xs_cap) break;
                     klo = nlo; khi = nhi; ++nu;
                 }
                 if (nu == 0) return false;
@@ -277,7 +285,12 @@ struct Builder {
                     I.xs_lo = klo; I.xs_hi = khi - klo;
                     if (!first && prev_lo == I.xs_lo && prev_n == I.xs_hi) I.flags |= F_SKIP_PRO;
                     prev_lo = I.xs_lo; prev_n = I.xs_hi;
-                    max_xs_bytes = std::max(max_xs_bytes, stage_bytes((khi - klo) * m.ck));
+                    uint32_t need = stage_bytes((khi - klo) * m.ck);
+                    if (pro == PRO_COMBINE) {
+                        I.in_base = (need + 15u) & ~15u;                    // partial rows are staged behind the vector
+                        need = I.in_base + combine_bytes((khi - klo) * m.ck);
+                    }
+                    max_xs_bytes = std::max(max_xs_bytes, need);
                 }
                 if (u + nu == u_end) { I.sig_ctr = sig_ctr; if (sig_ctr != kNone) ++ctr_signals[sig_ctr]; }
                 lists[wg].push_back(I);
@@ -317,8 +330,11 @@ struct Builder {
         for (int l = 0; l < d.L; ++l) {
             const uint32_t c_qkv = new_counter(), c_comb = new_counter(), c_o = new_counter(), c_gu = new_counter(),
                            c_d = new_counter();
+            // attention tasks signal one counter per (sequence, kv head) for the combine tasks, or, when the
+            // O projection combines the partials itself, one counter per layer
             std::vector<uint32_t> c_att(d.Bm * d.nkv);
-            for (auto &c : c_att) c = new_counter();
+            const uint32_t c_att_layer = t.fuse ? new_counter() : kNone;
+            for (auto &c : c_att) c = t.fuse ? c_att_layer : new_counter();
 
             // ---- QKV projection: prologue = (embedding | residual + pending partials) -> RMSNorm
             {
@@ -354,7 +370,7 @@ struct Builder {
                         }
             }
             // ---- combine: one task per (sequence, q head)
-            {
+            if (!t.fuse) {
                 std::vector<int> order = by_load();
                 int oi = 0;
                 for (int b = 0; b < d.Bm; ++b)
@@ -373,12 +389,12 @@ struct Builder {
             }
             // ---- O projection; unsplit: the epilogue adds the residual, split: partials for the next prologue
             {
-                Instr o = gemv_proto(ST_O, l, g.o, wm.o[l], t.s_o, PRO_PLAIN, 1, 0);
-                o.in_parts = am.o; o.part_stride = 0; o.in_ld = d.qd;
+                Instr o = gemv_proto(ST_O, l, g.o, wm.o[l], t.s_o, t.fuse ? PRO_COMBINE : PRO_PLAIN, t.fuse ? t.nc : 1, 0);
+                o.in_parts = t.fuse ? am.attp : am.o; o.part_stride = 0; o.in_ld = d.qd;
                 o.out_ld = d.H;
                 if (t.s_o == 1) { o.flags |= F_ADD_RESID; o.resid = res; o.out = other(res); res = other(res); }
                 else { o.out = am.po; o.out_split_stride = d.Bm * d.H; parts_off = am.po; parts_n = t.s_o; }
-                if (!emit_gemv(o, g.o, c_comb, c_o)) return false;
+                if (!emit_gemv(o, g.o, t.fuse ? c_att_layer : c_comb, c_o)) return false;
             }
             // ---- gate/up projection: prologue = residual (+ O partials) -> RMSNorm; unsplit: SiLU * up in the epilogue
             {
@@ -526,6 +542,7 @@ static SimResult simulate(const mk_schedule *s)
                 double fl = normk ? (double)d.H * (1 + np) : (double)I.xs_hi * instr_ck(I) * np * (pr == PRO_SILU ? 2 : 1);
                 // one memory round trip per four partials in flight, plus the bytes themselves
                 pro = 0.8 + 0.8 * ((np + 3) / 4) + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
+                if (pr == PRO_COMBINE) pro = 1.6 + fl * d.Bm / 1000.0 * pro_us_per_kfloat;   // all partial rows in flight at once
             }
             // units are flushed through a cross-lane reduction: small R means more flushes per byte
             pro += 0.004 * I.nu;
@@ -661,6 +678,9 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
         if (d.nqkv % g.qkv.R || d.qd % g.qkv.R || d.kvd % g.qkv.R) return false;
         if (!split_ok(g.qkv.kbt, t.s_qkv) || !split_ok(g.o.kbt, t.s_o) || !split_ok(g.gu.kbt, t.s_gu) || !split_ok(g.down.kbt, t.s_d)) return false;
         if (t.s_gu > 1 && g.gu.R < 8) return false;
+        // a fused combine stages whole heads: every K split of the O projection must start and end on a head
+        if (t.fuse && t.s_o > 1 && (ceil_div(g.o.kbt, t.s_o) * g.o.ck) % d.d) return false;
+        if (t.fuse && t.nc > 64) return false;
         return true;
     };
 
@@ -669,6 +689,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     best.s_qkv = c_sqkv[0]; best.s_o = c_so[0]; best.s_gu = c_sgu[0]; best.s_d = c_sd[0];
     best.r_qkv = c_rq[0]; best.r_o = c_ro[0]; best.r_gu = c_rgu[0]; best.r_d = c_rd[0]; best.r_head = c_rh[0];
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
+    best.fuse = cfg.fuse_combine > 0 ? 1 : 0;   // not searched by the cost model: chosen by the caller or by on-device tuning
     best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
     // weight-page ring: a pipeline stage is 16 pages (4 per wavefront).  The depth is only searched
     // when asked for (ring_kb == -2): measured on MI355X the direct-load path is the faster one at
@@ -743,6 +764,11 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
                 if (pro == PRO_RESID_NORM) {
                     rd(I.in_base + (uint64_t)b * I.in_ld, d.H);
                     for (uint32_t p = 0; p < np; ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + (uint64_t)b * I.in_ld, d.H);
+                } else if (pro == PRO_COMBINE) {
+                    uint64_t k0 = (uint64_t)I.xs_lo * ck, k1 = std::min<uint64_t>(k0 + (uint64_t)I.xs_hi * ck, I.k_len);
+                    const uint64_t h0 = k0 / d.d, nh = (k1 - k0 + d.d - 1) / d.d, RS = d.d + kPartPad;
+                    // (the pad words of a row are loaded too but never used, and nobody writes them)
+                    for (uint64_t r = 0; k1 > k0 && r < nh * np; ++r) rd(I.in_parts + (((uint64_t)b * d.nq + h0) * np + r) * RS, d.d + 2);
                 } else if (pro == PRO_PLAIN || pro == PRO_SILU) {
                     uint64_t k0 = (uint64_t)I.xs_lo * ck, k1 = std::min<uint64_t>(k0 + (uint64_t)I.xs_hi * ck, I.k_len);
                     if (k1 > k0) {
@@ -883,7 +909,7 @@ int verify_schedule(const mk_schedule *s)
                 if (at != e.total) { snprintf(buf, sizeof buf, "operator %u of layer %d covers %u of %u units", e.st, l, at, e.total); return fail(buf); }
             }
             if (l < d.L) {
-                struct { uint32_t st; uint32_t total; } k2[] = {{ST_ATT, (uint32_t)(d.Bm * d.nkv * s->tl.nc)}, {ST_COMB, (uint32_t)(d.Bm * d.nq)}};
+                struct { uint32_t st; uint32_t total; } k2[] = {{ST_ATT, (uint32_t)(d.Bm * d.nkv * s->tl.nc)}, {ST_COMB, (uint32_t)(s->tl.fuse ? 0 : d.Bm * d.nq)}};
                 for (auto &e : k2) {
                     auto &v = keys[l * 8 + e.st];
                     std::sort(v.begin(), v.end());
@@ -968,7 +994,7 @@ int verify_schedule(const mk_schedule *s)
                 if (i == 0) return fail("first instruction skips its prologue");
                 const Instr &Pv = all[(size_t)w * mi + i - 1];
                 bool same = Pv.op == OP_GEMV && Pv.ref_seq == I.ref_seq && Pv.cfg == I.cfg;
-                if (same && (instr_pro(I) == PRO_PLAIN || instr_pro(I) == PRO_SILU)) same = Pv.xs_lo == I.xs_lo && Pv.xs_hi == I.xs_hi;
+                if (same && (instr_pro(I) == PRO_PLAIN || instr_pro(I) == PRO_SILU || instr_pro(I) == PRO_COMBINE)) same = Pv.xs_lo == I.xs_lo && Pv.xs_hi == I.xs_hi;
                 if (!same) return fail("prologue skipped although LDS does not hold this task's input");
             }
         }
@@ -1048,7 +1074,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 4;
+constexpr uint32_t kVersion = 5;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)

@@ -23,6 +23,7 @@ struct Tiling {              // the searched parameters (Sec. 4.2.2 Step 3, "til
     int nc;                      // attention chunk tasks per (sequence, kv head)
     int bs;                      // positions per attention block
     int mfma;                    // 0 VALU, 1 MFMA
+    int fuse;                    // 1: the O projection combines the attention partials itself (no combine tasks)
     int ring_pages, page_bytes, n_stage;  // Eq. 1-2 outcome (0 pages: weights go straight to registers)
 };
 

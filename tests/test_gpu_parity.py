@@ -108,6 +108,9 @@ def test_c0_greedy_32_steps_match_oracle():
     # weight-page ring (LDS-DMA stream across task boundaries): shallow, deep, ragged stages, matrix-core path
     dict(ring_kb=16), dict(ring_kb=32, attn_chunks=2), dict(ring_kb=96, chunk_rows=2), dict(ring_kb=64, n_workgroups=24),
     dict(ring_kb=48, use_mfma=1, split_o=2, split_down=2),
+    # O projection combining the attention partials itself (no combine tasks)
+    dict(fuse_combine=1), dict(fuse_combine=1, split_o=2, attn_chunks=4), dict(fuse_combine=1, use_mfma=1, attn_chunks=2),
+    dict(fuse_combine=1, split_o=4, rows_o=16, attn_chunks=8, n_workgroups=20), dict(fuse_combine=1, ring_kb=32, attn_chunks=4),
 ], ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()))
 def test_c0_variants(opts):
     say("c0 variant", opts)
@@ -324,6 +327,7 @@ class PairW4(Pair):
 @pytest.mark.parametrize("opts", [
     dict(), dict(group=64), dict(group=32, qkv_bias=1), dict(chunk_rows=16), dict(chunk_rows=16, split_o=2, split_down=2),
     dict(rows_gateup=16, split_gateup=2, split_qkv=2, attn_chunks=4), dict(n_workgroups=36, rows_down=4, rows_o=8),
+    dict(fuse_combine=1, attn_chunks=4), dict(fuse_combine=1, rows_o=16, split_o=2),
 ], ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()) or "default")
 def test_w4_c0_greedy_steps_match_oracle(opts):
     opts = dict(opts)
