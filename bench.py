@@ -62,6 +62,7 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy (counter calibration)")
     ap.add_argument("--opt", action="append", default=[], help="schedule override key=value (e.g. split_down=4)")
     ap.add_argument("--w4", action="store_true", help="W4A16 decoder projections (group 128) instead of bf16")
+    ap.add_argument("--context", type=int, default=0, help="KV context at the first timed step (default: the configuration's)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -75,7 +76,7 @@ def main() -> int:
     full = synth.CONFIGS[args.config]
     B = args.batch
     steps, warmup = args.steps, args.warmup
-    ctx0 = full["ctx0"]
+    ctx0 = args.context if args.context > 0 else full["ctx0"]
     cfg = synth.model_cfg(full, max_batch=max(B, 1), max_context=ctx0 + steps + warmup + 64)
     opts = {}
     for kv in args.opt:
