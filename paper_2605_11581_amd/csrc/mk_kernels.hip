@@ -756,6 +756,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         kbi += kWaves;
     };
 
+    // The residual row an F_ADD_RESID epilogue adds was final before this task's dependencies were
+    // met: fetch the first (usually only) value of every thread now, one memory round trip earlier.
+    float resid0 = 0.f;
+    if (!MFMA && (I.flags & F_ADD_RESID) && (uint32_t)tid < red_per_wave) {
+        const uint32_t ub = (uint32_t)tid >> rlog, uu = u0 + ub;
+        resid0 = ld_act((const float *)(P.ws + P.lay.act) + I.resid + (size_t)(uu / S) * R + ((uint32_t)tid & (R - 1)));
+    }
     const uint32_t total = st.total;
     if (RING) {
         // Weights come from this wave's LDS page ring, a stage (up to four chunks) at a time:
@@ -877,7 +884,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
                 // logit there for the arg-max pass below
                 if ((I.flags & F_ARGMAX) && P.want_tokens) red[t] = row < I.n_rows ? v : -INFINITY;
             } else {
-                if (I.flags & F_ADD_RESID) v += ld_act(actw + I.resid + (size_t)b * I.out_ld + row);
+                if (I.flags & F_ADD_RESID) v += (!MFMA && t == (uint32_t)tid) ? resid0 : ld_act(actw + I.resid + (size_t)b * I.out_ld + row);
                 st_act(actw + I.out + (size_t)s * I.out_split_stride + (size_t)b * I.out_ld + row, v);
             }
         }
