@@ -73,7 +73,15 @@ struct Wg {
     float *logits;              // where this step's logits go
 };
 
-__device__ __forceinline__ void wg_sync(Wg &, char *) { __syncthreads(); }
+// Workgroup barrier for LDS hand-offs.  __syncthreads() would also drain every outstanding global
+// access of the wave (s_waitcnt vmcnt(0)): the weight prefetch in flight, and at task boundaries the
+// acknowledgement of the signal atomic -- a memory round trip per barrier that nothing here needs.
+// Only LDS traffic has to be complete; global data that crosses waves is drained explicitly where
+// a signal publishes it.
+__device__ __forceinline__ void wg_sync(Wg &, char *)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 __device__ __forceinline__ uint32_t rfl(uint32_t v);
 template <class T>
