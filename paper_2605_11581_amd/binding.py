@@ -75,6 +75,12 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_11581_amd.build` "
                               "(there is no fallback path)")
+        # torch brings its own HIP runtime: let it load first, so that this library binds to the same one
+        # (two runtimes in one process do not see the device)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(_LIB_PATH)
         H = C.c_void_p
         L.mk_last_error.restype = C.c_char_p
