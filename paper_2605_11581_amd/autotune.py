@@ -33,6 +33,7 @@ SPACE: List[Tuple[str, List[int]]] = [
     ("attn_chunks", [16, 32, 64]),
     ("split_down", [1, 2, 4]),
     ("split_qkv", [1, 2]),
+    ("split_gateup", [1, 2]),
     ("rows_head", [8, 16]),
 ]
 _STAT_OF = {"split_o": "split_o", "rows_down": "rows_down", "rows_gateup": "rows_gateup", "rows_o": "rows_o",

@@ -33,6 +33,29 @@ int hip_fail(hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail(e_, #expr); \
     } while (0)
 
+// The kernel that walks the lists of a schedule: one per GEMV family and step count, plus the ring
+// form (any step count, bf16 only).
+typedef void (*walk_fn)(const mk::Params, const mk::LdsPlan);
+walk_fn walk_kernel(const mk_schedule *s, int n_steps, uint32_t dbg)
+{
+    if (s->tl.ring_pages && !(dbg & 4u)) return mk_megakernel_ring;
+    const bool multi = n_steps > 1;
+    if (s->dm.w4) return multi ? mk_megakernel_steps_w4 : mk_megakernel_w4;
+    if (s->tl.mfma) return multi ? mk_megakernel_steps_mfma : mk_megakernel_mfma;
+    return multi ? mk_megakernel_steps : mk_megakernel;
+}
+walk_fn op_kernel(const mk_schedule *s)
+{
+    return s->dm.w4 ? mk_op_kernel_w4 : s->tl.mfma ? mk_op_kernel_mfma : mk_op_kernel;
+}
+std::vector<const void *> all_walk_kernels()
+{
+    return {(const void *)mk_megakernel, (const void *)mk_megakernel_steps, (const void *)mk_op_kernel,
+            (const void *)mk_megakernel_mfma, (const void *)mk_megakernel_steps_mfma, (const void *)mk_op_kernel_mfma,
+            (const void *)mk_megakernel_w4, (const void *)mk_megakernel_steps_w4, (const void *)mk_op_kernel_w4,
+            (const void *)mk_megakernel_ring};
+}
+
 // Tuning knobs read from the environment (development only; defaults are the shipped values).
 uint32_t dbg_knob(const char *name, uint32_t dflt, uint32_t lo, uint32_t hi)
 {
@@ -62,6 +85,10 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.only_seq = mk::kNone; P.act_bytes = (uint32_t)(s->am.n_floats * 4);
     P.w4_group = s->dm.w4 ? (uint32_t)s->dm.group : 0u;
     P.ctr_stride = dbg_knob("MK_DBG_CTR_STRIDE", mk::kCounterStride, 1, mk::kCounterStrideMax);
+    uint32_t nsub = dbg_knob("MK_DBG_CTR_NSUB", mk::kCounterSubs, 1, 32);
+    while (nsub & (nsub - 1u)) nsub &= nsub - 1u;                                     // a power of two
+    while (nsub > 1u && nsub * P.ctr_stride > (uint32_t)mk::kCounterStrideMax) nsub >>= 1;   // inside the counter's share of the region
+    P.ctr_nsub = nsub;
     P.poll_sleep = dbg_knob("MK_DBG_POLL_SLEEP", 0, 0, 64);
     P.dbg = dbg_knob("MK_DBG_UNSAFE_TIMING", 0, 0, 7);
     return P;
@@ -204,18 +231,10 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     hipDeviceProp_t prop;
     HIP_TRY(hipGetDeviceProperties(&prop, s->device));
     if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_steps, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_steps_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel_w4, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_op_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    HIP_TRY(hipFuncSetAttribute((const void *)mk_megakernel_ring, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
+    for (const void *k : all_walk_kernels())
+        HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
     int per_cu = 0;
-    if (s->tl.ring_pages)
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel_ring, mk::kWgThreads, s->lds_total));
-    else
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)mk_megakernel, mk::kWgThreads, s->lds_total));
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)walk_kernel(s, 1, 0), mk::kWgThreads, s->lds_total));
     if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
         char buf[200];
         snprintf(buf, sizeof buf, "the device keeps only %d x %d workgroups resident, the schedule needs %d", per_cu, prop.multiProcessorCount, s->n_wg);
@@ -376,15 +395,7 @@ static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *po
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
-    if (s->tl.ring_pages && !(P.dbg & 4u))
-        hipLaunchKernelGGL(mk_megakernel_ring, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
-    else if (s->dm.w4)
-        hipLaunchKernelGGL(n_steps > 1 ? mk_megakernel_steps_w4 : mk_megakernel_w4, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads),
-                           s->lds_total, st, P, lp);
-    else if (n_steps > 1)
-        hipLaunchKernelGGL(mk_megakernel_steps, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
-    else
-        hipLaunchKernelGGL(mk_megakernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    hipLaunchKernelGGL(walk_kernel(s, n_steps, P.dbg), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
     return MK_OK;
@@ -420,7 +431,7 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
     for (uint32_t seq : s->ref_seqs) {
         P.only_seq = seq;
-        hipLaunchKernelGGL(s->dm.w4 ? mk_op_kernel_w4 : mk_op_kernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+        hipLaunchKernelGGL(op_kernel(s), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     }
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));

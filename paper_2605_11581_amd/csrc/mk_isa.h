@@ -23,8 +23,9 @@ constexpr int kInstrDwords = 32;
 constexpr uint32_t kNone = 0xffffffffu;
 constexpr int kMaxBatch = 8;
 constexpr int kMaxGroup = 8;           // q heads per kv head
-constexpr int kCounterStride = 32;     // default dwords between counters (one 128-byte line each)
-constexpr int kCounterStrideMax = 1088; // the counter region is sized for strides up to this
+constexpr int kCounterStride = 32;     // default dwords between sub-counters (one 128-byte line each)
+constexpr int kCounterSubs = 16;       // default sub-counters per dependency counter
+constexpr int kCounterStrideMax = 1088; // the counter region holds this many dwords per dependency counter
 constexpr int kPrefetch = 16;          // 128-bit weight loads a lane keeps in flight (direct-load path)
 
 // LDS map of a workgroup:
@@ -179,7 +180,8 @@ struct Params {
     uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
     uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
     uint32_t w4_group;    // W4: group size along K (32, 64 or 128); 0: bf16 weights
-    uint32_t ctr_stride;  // dwords between dependency counters
+    uint32_t ctr_stride;  // dwords between dependency (sub-)counters
+    uint32_t ctr_nsub;    // sub-counters per dependency counter (power of two, 1..32; ctr_nsub * ctr_stride <= kCounterStrideMax)
     uint32_t poll_sleep;  // s_sleep units between two polls of a dependency counter
     uint32_t dbg;         // development only: bit 0 skip dependency waits, bit 1 skip the store drain (both: results invalid,
                           // timing experiments), bit 2 run a ring schedule with the direct-load kernel

@@ -175,17 +175,33 @@ __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
     __hip_atomic_store(e + slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Poll a dependency counter until it has received `target` signals (wrap-safe).
-// Bounded: after `limit` polls the wait gives up and reports failure, so every
-// wave always reaches the end of its instruction list.
-__device__ __forceinline__ bool wait_counter(const uint32_t *ctr, uint32_t target, uint32_t limit, uint32_t nap,
+// A dependency counter is kept as `nsub` sub-counters on separate 128-byte lines: a producer adds to
+// the one picked by its workgroup id, so the read-modify-writes of a level with hundreds of producers
+// spread over `nsub` lines instead of queueing on one.  The count is the sum of the sub-counters
+// (each only grows, so a sum of reads taken at different times can only under-count).
+__device__ __forceinline__ const uint32_t *sub_counter(const Params &P, const uint32_t *counters, uint32_t idx, uint32_t j)
+{
+    return counters + ((size_t)idx * P.ctr_nsub + j) * P.ctr_stride;
+}
+
+// Wave-wide poll of a dependency counter until it has received `target` signals (wrap-safe); lane j
+// reads sub-counter j.  Bounded: after `limit` polls the wait gives up and reports failure, so every
+// wave always reaches the end of its instruction list.  All 64 lanes call it and get the same result.
+__device__ __forceinline__ bool wait_counter(const Params &P, const uint32_t *counters, uint32_t idx, uint32_t target,
                                              uint32_t *polls = nullptr)
 {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t *mine = sub_counter(P, counters, idx, lane & (P.ctr_nsub - 1u));
     uint32_t it = 0;
     bool ok = true;
-    while ((int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-        if (++it > limit) { ok = false; break; }
-        for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(2);
+    for (;;) {
+        uint32_t v = lane < P.ctr_nsub ? __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);   // nsub <= 32
+        v = rfl(v);
+        if ((int32_t)(v - target) >= 0) break;
+        if (++it > P.spin_limit) { ok = false; break; }
+        for (uint32_t z = 0; z < P.poll_sleep; ++z) __builtin_amdgcn_s_sleep(2);
     }
     if (polls) *polls += it + 1;
     return ok;
@@ -282,6 +298,188 @@ __device__ __forceinline__ int nterm_of(int batch) { return batch <= 5 ? 3 : 2; 
 
 constexpr int kQuadsPerThread = 4;   // hidden <= 4 * 4 * 256
 
+// Matrix-core path, several sequences: the same staging as gemv_prologue, organised so that the loads
+// of ALL sequences are in flight together.  A lane walks the flattened (sequence, quad) items in
+// groups of kItems; one memory round trip then covers kItems quads per lane instead of one sequence.
+// The normalising forms park the summed rows as fp32 inside each sequence's own (larger) plane region,
+// take the sum of squares with one wave per sequence, and rewrite the region as bf16 planes.
+// Returns false for the forms it does not cover (the caller's per-sequence code handles those).
+constexpr int kItems = 8;
+
+__device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Instr &I, char *lds, Wg &lp, int batch)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
+    char *xs = lds + lp.xs_off;
+    float *misc = (float *)(lds + kLdsMisc);
+    const ActBuf ab = act_buf(P);
+    const int nterm = nterm_of(batch);
+    const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
+    constexpr uint32_t kNone = 0xfffffff0u;            // beyond the descriptor: the load returns zeros
+
+    if (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM) {
+        const int H = P.hidden, nq4 = H >> 2, total = batch * nq4;
+        const uint32_t plane_stride = (uint32_t)H * 2u + 16u, seq_stride = (uint32_t)nterm * plane_stride;
+        const uint16_t *gain = (const uint16_t *)(P.ws + P.lay.vecs) + I.gain;
+        for (int e0 = tid; e0 < total; e0 += kWgThreads * kItems) {
+            f32x4 v[kItems];
+            uint32_t off[kItems];                        // b * in_ld + 4 q of the item, kNone past the end
+            int bq[kItems];                              // b << 16 | q
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                const int e = e0 + u * kWgThreads;
+                const int b = e / nq4, q = e - b * nq4;
+                off[u] = e < total ? (uint32_t)b * I.in_ld + 4u * (uint32_t)q : kNone;
+                bq[u] = (b << 16) | q;
+            }
+            if (pro == PRO_EMBED_NORM) {
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) {
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (off[u] != kNone) {
+                        const int tok = token_of(P, lp, bq[u] >> 16), k = 4 * (bq[u] & 0xffff);
+                        x.x = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k);
+                        x.y = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 1);
+                        x.z = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 2);
+                        x.w = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 3);
+                    }
+                    v[u] = x;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) v[u] = ld_act4(ab, off[u] != kNone ? I.in_base + off[u] : kNone);
+                // the producer's partial sums, two partials of every item in flight, added in order
+                for (uint32_t s0 = 0; s0 < n_parts; s0 += 2) {
+                    f32x4 t0[kItems], t1[kItems];
+                    const uint32_t p0 = I.in_parts + s0 * I.part_stride, p1 = p0 + I.part_stride;
+                    const bool two = s0 + 1 < n_parts;
+#pragma unroll
+                    for (int u = 0; u < kItems; ++u) {
+                        t0[u] = ld_act4(ab, off[u] != kNone ? p0 + off[u] : kNone);
+                        t1[u] = ld_act4(ab, (two && off[u] != kNone) ? p1 + off[u] : kNone);
+                    }
+#pragma unroll
+                    for (int u = 0; u < kItems; ++u) { v[u] += t0[u]; v[u] += t1[u]; }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                if (off[u] == kNone) continue;
+                const int b = bq[u] >> 16, q = bq[u] & 0xffff;
+                if ((uint32_t)(4 * q) >= I.xs_lo && (uint32_t)(4 * q) < I.xs_hi) st_act4(ab, I.xs_out + off[u], v[u]);
+                *(f32x4 *)(xs + (size_t)b * seq_stride + (size_t)q * 16) = v[u];
+            }
+        }
+        wg_sync(lp, lds);
+        for (int b = wave; b < batch; b += kWaves) {         // one wave per sequence
+            const f32x4 *vp = (const f32x4 *)(xs + (size_t)b * seq_stride);
+            float ss = 0.f;
+            for (int q = lane; q < nq4; q += 64) {
+                const f32x4 x = vp[q];
+                ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+            }
+            ss = wave_sum(ss);
+            if (lane == 0) misc[b] = 1.0f / sqrtf(ss / (float)H + P.rms_eps);
+        }
+        for (int b = 0; b < batch; ++b) {
+            const f32x4 *vp = (const f32x4 *)(xs + (size_t)b * seq_stride);
+            f32x4 v[kQuadsPerThread];
+#pragma unroll
+            for (int j = 0; j < kQuadsPerThread; ++j) {
+                const int q = tid + j * kWgThreads;
+                v[j] = q < nq4 ? vp[q] : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            wg_sync(lp, lds);      // every lane holds its part of sequence b: the planes may overwrite the parked row
+            const float inv = misc[b];
+#pragma unroll
+            for (int j = 0; j < kQuadsPerThread; ++j) {
+                const int q = tid + j * kWgThreads;
+                if (q < nq4) {
+                    uint2 gw = *(const uint2 *)(gain + 4 * q);
+                    f32x4 y;
+                    y.x = v[j].x * inv * bf_lo(gw.x); y.y = v[j].y * inv * bf_hi(gw.x);
+                    y.z = v[j].z * inv * bf_lo(gw.y); y.w = v[j].w * inv * bf_hi(gw.y);
+                    store_x4<true>(xs, b, 4 * q, y, nterm, plane_stride);
+                }
+            }
+        }
+        return true;
+    }
+
+    const bool plain1 = pro == PRO_PLAIN && n_parts == 1;
+    if (!plain1 && pro != PRO_SILU) return false;
+    const uint32_t ck = instr_ck(I);
+    const int k0 = (int)(I.xs_lo * ck), kn = (int)(I.xs_hi * ck), nq = kn >> 2, total = batch * nq;
+    const uint32_t plane_stride = (uint32_t)kn * 2u + 16u;
+    if (plain1) {
+        for (int e0 = tid; e0 < total; e0 += kWgThreads * kItems) {
+            f32x4 y[kItems];
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                const int e = e0 + u * kWgThreads;
+                const int b = e / nq, i = 4 * (e - b * nq);
+                const uint32_t k = (uint32_t)(k0 + i);
+                y[u] = ld_act4(ab, (e < total && k < I.k_len) ? I.in_parts + (uint32_t)b * I.in_ld + k : kNone);
+            }
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                const int e = e0 + u * kWgThreads;
+                const int b = e / nq, i = 4 * (e - b * nq);
+                const uint32_t k = (uint32_t)(k0 + i);
+                if (k + 1 >= I.k_len) y[u].y = 0.f;      // elements at or beyond the true K are zero
+                if (k + 2 >= I.k_len) y[u].z = 0.f;
+                if (k + 3 >= I.k_len) y[u].w = 0.f;
+                if (e < total) store_x4<true>(xs, b, i, y[u], nterm, plane_stride);
+            }
+        }
+        return true;
+    }
+    // SILU over the fused gate/up output: row group j holds PR/2 gate rows then PR/2 up rows (PR >= 8)
+    constexpr int kIt = kItems / 2;                      // gate and up of two partials: 4 loads per item in flight
+    const uint32_t PR = 1u << instr_prod_rlog(I), half = PR >> 1;
+    for (int e0 = tid; e0 < total; e0 += kWgThreads * kIt) {
+        f32x4 gs[kIt], us[kIt];
+        uint32_t src[kIt];
+#pragma unroll
+        for (int u = 0; u < kIt; ++u) {
+            const int e = e0 + u * kWgThreads;
+            const int b = e / nq, i = 4 * (e - b * nq);
+            const uint32_t k = (uint32_t)(k0 + i);
+            src[u] = (e < total && k < I.k_len) ? (uint32_t)b * I.in_ld + (k / half) * PR + (k % half) : kNone;
+            gs[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            us[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        for (uint32_t s0 = 0; s0 < n_parts; s0 += 2) {
+            f32x4 g0[kIt], u0[kIt], g1[kIt], u1[kIt];
+            const uint32_t p0 = I.in_parts + s0 * I.part_stride, p1 = p0 + I.part_stride;
+            const bool two = s0 + 1 < n_parts;
+#pragma unroll
+            for (int u = 0; u < kIt; ++u) {
+                const bool ok = src[u] != kNone;
+                g0[u] = ld_act4(ab, ok ? p0 + src[u] : kNone);
+                u0[u] = ld_act4(ab, ok ? p0 + src[u] + half : kNone);
+                g1[u] = ld_act4(ab, (ok && two) ? p1 + src[u] : kNone);
+                u1[u] = ld_act4(ab, (ok && two) ? p1 + src[u] + half : kNone);
+            }
+#pragma unroll
+            for (int u = 0; u < kIt; ++u) { gs[u] += g0[u]; us[u] += u0[u]; gs[u] += g1[u]; us[u] += u1[u]; }
+        }
+#pragma unroll
+        for (int u = 0; u < kIt; ++u) {
+            const int e = e0 + u * kWgThreads;
+            const int b = e / nq, i = 4 * (e - b * nq);
+            const uint32_t k = (uint32_t)(k0 + i);
+            f32x4 acc;
+            acc.x = gs[u].x / (1.0f + __expf(-gs[u].x)) * us[u].x; acc.y = gs[u].y / (1.0f + __expf(-gs[u].y)) * us[u].y;
+            acc.z = gs[u].z / (1.0f + __expf(-gs[u].z)) * us[u].z; acc.w = gs[u].w / (1.0f + __expf(-gs[u].w)) * us[u].w;
+            if (k + 1 >= I.k_len) acc.y = 0.f;
+            if (k + 2 >= I.k_len) acc.z = 0.f;
+            if (k + 3 >= I.k_len) acc.w = 0.f;
+            if (e < total) store_x4<true>(xs, b, i, acc, nterm, plane_stride);
+        }
+    }
+    return true;
+}
+
 template <bool MFMA>
 __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, char *lds, Wg &lp, int batch)
 {
@@ -292,6 +490,12 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
     const int nterm = nterm_of(batch);
     const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
 
+    if constexpr (MFMA) {
+        if (batch > 1 && gemv_prologue_batched(P, I, lds, lp, batch)) {
+            wg_sync(lp, lds);
+            return;
+        }
+    }
     if (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM) {
         const int H = P.hidden, nq4 = H >> 2;
         const uint32_t plane_stride = (uint32_t)H * 2u + 16u;
@@ -1330,8 +1534,17 @@ __device__ __forceinline__ void fetch_instr(const uint32_t *list, uint32_t pc, u
     if (threadIdx.x < kInstrDwords) slot[threadIdx.x] = list[(size_t)pc * kInstrDwords + threadIdx.x];
 }
 
+// Which GEMV bodies a kernel carries.  A schedule uses one family throughout, so each kernel is
+// compiled with only the code it can reach (smaller code, fewer live registers).
+enum Path : int {
+    kPathValu = 0,    // bf16 weights, VALU dot products (batch 1)
+    kPathMfma = 1,    // bf16 weights, matrix cores (any batch)
+    kPathW4 = 2,      // 4-bit decoder projections (VALU), bf16 LM head
+    kPathAny16 = 3,   // bf16 weights, VALU or matrix cores by the instruction's flag
+};
+
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
-template <bool PERSISTENT, bool RING, bool W4>
+template <bool PERSISTENT, bool RING, int PATH>
 __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
                                            bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr)
 {
@@ -1348,6 +1561,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u) && !no_dep;
     GemvStream st;
     AttStream as;
+    constexpr bool W4 = PATH == kPathW4;
     if (I.op == OP_GEMV) gemv_issue<RING, W4>(P, I, st, lp.npf);
     else if (I.op == OP_ATT) {
         if (P.head_dim == 128) att_issue<128>(P, lp, *(const InstrAtt *)&I, as);
@@ -1356,22 +1570,22 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
 
     if (PERSISTENT && I.op == OP_GEMV) trace_mark(P, pc, 0);
     if (PERSISTENT) {
-        if (tid == 0) {
+        if (tid < 64) {   // the first wave polls
             uint32_t ok = 1, polls = 0;
             if (waiting) {
                 if (I.wait_ctr[0] != kNone)
-                    ok = wait_counter(counters + (size_t)I.wait_ctr[0] * P.ctr_stride,
-                                      (lp.epoch - ((I.flags & F_WAIT_PREV) ? 1u : 0u)) * I.wait_cnt[0],
-                                      P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
+                    ok = wait_counter(P, counters, I.wait_ctr[0], (lp.epoch - ((I.flags & F_WAIT_PREV) ? 1u : 0u)) * I.wait_cnt[0],
+                                      &polls) ? 1u : 0u;
                 if (ok && I.wait_ctr[1] != kNone)
-                    ok = wait_counter(counters + (size_t)I.wait_ctr[1] * P.ctr_stride, lp.epoch * I.wait_cnt[1],
-                                      P.spin_limit, P.poll_sleep, &polls) ? 1u : 0u;
+                    ok = wait_counter(P, counters, I.wait_ctr[1], lp.epoch * I.wait_cnt[1], &polls) ? 1u : 0u;
             }
-            if (!ok) set_err(P, 0, 1u + pc);
-            sflag[0] = ok;
-            if (I.op == OP_GEMV) {
-                trace_mark(P, pc, 1);
-                if (tracing) ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 6] = polls;   // mark 2: polls issued
+            if (tid == 0) {
+                if (!ok) set_err(P, 0, 1u + pc);
+                sflag[0] = ok;
+                if (I.op == OP_GEMV) {
+                    trace_mark(P, pc, 1);
+                    if (tracing) ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 6] = polls;   // mark 2: polls issued
+                }
             }
         }
         // The next instruction (loaded by the caller before this task began) has certainly arrived
@@ -1385,7 +1599,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
 
     uint64_t t2 = 0;
     if (I.op == OP_GEMV) {
-        if (!W4 && (I.flags & F_MFMA)) {
+        if (PATH == kPathMfma || (PATH == kPathAny16 && (I.flags & F_MFMA))) {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
             if (tracing && tid == 0) t2 = wall_clock64();
             gemv_main<true, RING>(P, I, lds, lp, st, P.batch);
@@ -1411,8 +1625,8 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         if (!(P.dbg & 2u)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_sync(lp, lds);
         if (tid == 0)
-            __hip_atomic_fetch_add((uint32_t *)counters + (size_t)I.sig_ctr * P.ctr_stride, 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add((uint32_t *)sub_counter(P, counters, I.sig_ctr, blockIdx.x & (P.ctr_nsub - 1u)), 1u,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tracing && tid == 0) {
         uint64_t *r = (uint64_t *)(P.ws + P.lay.trace) + ((size_t)blockIdx.x * P.max_instr + pc) * 8;
@@ -1448,7 +1662,7 @@ __device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *l
 
 // Persistent walk of this workgroup's whole list; the next instruction is fetched while the
 // current one runs.
-template <bool RING, bool MULTI, bool W4 = false>
+template <bool RING, bool MULTI, int PATH>
 __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1477,7 +1691,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
             const bool more = pc + 1 < P.max_instr;
             if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
             if (RING) pin_uniform(lp);
-            exec_instr<true, RING, W4>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
+            exec_instr<true, RING, PATH>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
         }
     }
     // no DMA load may still be writing LDS when the workgroup retires
@@ -1486,7 +1700,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
 
 // One operator instance: the instructions of this workgroup whose ref_seq matches (they are
 // adjacent in the list), found with one parallel scan.
-template <bool W4>
+template <int PATH>
 __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1509,34 +1723,29 @@ __device__ __forceinline__ void run_one_op(const Params &P, const LdsPlan plan)
         wg_sync(lp, lds);
         Instr I;
         read_instr(sinstr, I);
-        exec_instr<false, false, W4>(P, lp, lds, I, pc, dead);
+        exec_instr<false, false, PATH>(P, lp, lds, I, pc, dead);
     }
 }
 
 }  // namespace mk
 
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, false>(P, lp); }
+#define MK_KERNEL(name, body) \
+    extern "C" __global__ void __launch_bounds__(mk::kWgThreads) name(const mk::Params P, const mk::LdsPlan lp) { body; }
 
-// The same walk repeated once per decode step of the launch (greedy token feedback on the device).
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel_steps(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, true>(P, lp); }
-
-// Same walk with the per-wave LDS page ring carrying the weight stream.
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel_ring(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<true, true>(P, lp); }
-
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_op_kernel(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op<false>(P, lp); }
-
-// The same three walks for schedules whose decoder projections are 4-bit codes (kept apart so that
-// the bf16 kernels carry none of the W4 code).
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, false, true>(P, lp); }
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_megakernel_steps_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_persistent<false, true, true>(P, lp); }
-extern "C" __global__ void __launch_bounds__(mk::kWgThreads)
-mk_op_kernel_w4(const mk::Params P, const mk::LdsPlan lp) { mk::run_one_op<true>(P, lp); }
+// One walk of the lists (one decode step) / the walk repeated once per decode step of the launch
+// (greedy token feedback on the device) / one operator instance per launch, for each GEMV family.
+// The families are kept apart so that the batch-1 bf16 kernels carry none of the matrix-core or W4 code.
+MK_KERNEL(mk_megakernel, (mk::run_persistent<false, false, mk::kPathValu>(P, lp)))
+MK_KERNEL(mk_megakernel_steps, (mk::run_persistent<false, true, mk::kPathValu>(P, lp)))
+MK_KERNEL(mk_op_kernel, (mk::run_one_op<mk::kPathValu>(P, lp)))
+MK_KERNEL(mk_megakernel_mfma, (mk::run_persistent<false, false, mk::kPathMfma>(P, lp)))
+MK_KERNEL(mk_megakernel_steps_mfma, (mk::run_persistent<false, true, mk::kPathMfma>(P, lp)))
+MK_KERNEL(mk_op_kernel_mfma, (mk::run_one_op<mk::kPathMfma>(P, lp)))
+MK_KERNEL(mk_megakernel_w4, (mk::run_persistent<false, false, mk::kPathW4>(P, lp)))
+MK_KERNEL(mk_megakernel_steps_w4, (mk::run_persistent<false, true, mk::kPathW4>(P, lp)))
+MK_KERNEL(mk_op_kernel_w4, (mk::run_one_op<mk::kPathW4>(P, lp)))
+// Any step count, with the per-wave LDS page ring carrying the weight stream (bf16, either GEMV body).
+MK_KERNEL(mk_megakernel_ring, (mk::run_persistent<true, true, mk::kPathAny16>(P, lp)))
 
 // Offline weight reorder: row-major bf16 [n_rows][n_cols] -> tile-major chunks of R = 1 << rlog rows.
 // Source row i lands in row group g0 + i / rpu at row r_off + i % rpu of the group (rpu = R and

@@ -9,7 +9,7 @@ the median and the slowest task.  It is the measurement behind the "where the ti
 of the design notes and the feedback signal for the profile-guided tiling search (paper Sec.
 4.2.2 Step 4: offline profiling of candidate traces).
 
-    python -m paper_2605_11581_amd.trace_report --config c2_1p5b [--layer 13] [--w4] [--opt k=v ...]
+    python -m paper_2605_11581_amd.trace_report --config c2_1p5b [--layer 13] [--w4] [--batch B] [--opt k=v ...]
 """
 from __future__ import annotations
 
@@ -77,6 +77,7 @@ def main() -> int:
     ap.add_argument("--config", default="c2_1p5b")
     ap.add_argument("--layer", type=int, default=13)
     ap.add_argument("--w4", action="store_true")
+    ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--opt", action="append", default=[])
     args = ap.parse_args()
     import torch
@@ -84,7 +85,7 @@ def main() -> int:
     from .runtime import Decoder
 
     full = synth.CONFIGS[args.config]
-    cfg = synth.model_cfg(full, max_batch=1)
+    cfg = synth.model_cfg(full, max_batch=args.batch)
     opts = {k: int(v) for k, v in (kv.split("=") for kv in args.opt)}
     w = synth.make_weights(full)
     if args.w4:
@@ -94,9 +95,10 @@ def main() -> int:
     print("schedule:", {k: v for k, v in dec.stats.items() if k.startswith(("split", "rows", "attn", "fuse", "ring", "lds"))})
     dec.load_weights(w)
     kv = dec.new_kv(synth.make_kv_fill(cfg, full["ctx0"], seed=synth.seed_of(full)))
-    tok = torch.tensor([5], dtype=torch.int32, device="cuda")
-    pos = torch.tensor([full["ctx0"]], dtype=torch.int32, device="cuda")
-    logits = torch.empty(1, cfg["vocab"], dtype=torch.float32, device="cuda")
+    B = args.batch
+    tok = torch.full((B,), 5, dtype=torch.int32, device="cuda")
+    pos = torch.full((B,), full["ctx0"], dtype=torch.int32, device="cuda")
+    logits = torch.empty(B, cfg["vocab"], dtype=torch.float32, device="cuda")
     tr, _, seq = collect(dec, tok, pos, kv, logits)
     report(tr, seq, args.layer)
     dec.close()
