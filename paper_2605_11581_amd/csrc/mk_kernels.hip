@@ -1454,38 +1454,44 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
     const ActBuf ab = act_buf(P);
     float *stage = (float *)(lds + lp.xs_off);
     float *o = (float *)(P.ws + P.lay.act) + I.o_out + (size_t)b * I.o_ld;
+    const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
+    constexpr int U = 5;   // 128-bit loads in flight per lane: one round trip for 32 partial rows of a 128-wide head
     for (int hh = 0; hh < (int)I.nh; ++hh) {
         const int h = (int)I.h0 + hh;
         const uint32_t src = I.out + (uint32_t)(((size_t)b * P.n_q_heads + h) * nc) * (uint32_t)RS;
         const int nq4 = nc * RS / 4;
+        float *wgt = stage + (size_t)nc * RS;                    // [nc] merge weights f_c / L
         if (hh) wg_sync(lp, lds);
-        for (int q0 = threadIdx.x; q0 < nq4; q0 += kWgThreads * 4) {
-            f32x4 v[4];
+        for (int q0 = threadIdx.x; q0 < nq4; q0 += kWgThreads * U) {
+            f32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int q = q0 + u * kWgThreads;
                 v[u] = ld_act4(ab, q < nq4 ? src + 4u * q : 0xfffffff0u);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int q = q0 + u * kWgThreads;
                 if (q < nq4) *(f32x4 *)(stage + 4 * q) = v[u];
             }
         }
         wg_sync(lp, lds);
-        for (int i = threadIdx.x; i < D; i += kWgThreads) {
+        if (wave == 0) {
+            // merge weights once per chunk (lane c, c + 64, ...), in fixed order
             float M = -INFINITY;
+            for (int c = lane; c < nc; c += 64) M = fmaxf(M, stage[c * RS + D]);
+            M = wave_max(M);
+            float L = 0.f;
+            for (int c = lane; c < nc; c += 64) L += stage[c * RS + D + 1] * safe_exp_diff(stage[c * RS + D], M);
+            L = wave_sum(L);
+            for (int c = lane; c < nc; c += 64) wgt[c] = safe_exp_diff(stage[c * RS + D], M) / L;
+        }
+        wg_sync(lp, lds);
+        for (int i = threadIdx.x; i < D; i += kWgThreads) {
+            float A = 0.f;
 #pragma unroll 8
-            for (int c = 0; c < nc; ++c) M = fmaxf(M, stage[c * RS + D]);
-            float L = 0.f, A = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < nc; ++c) {
-                const float *s = stage + c * RS;
-                float f = safe_exp_diff(s[D], M);
-                L += s[D + 1] * f;
-                A += s[i] * f;
-            }
-            st_act(o + (size_t)h * D + i, A / L);
+            for (int c = 0; c < nc; ++c) A += stage[c * RS + i] * wgt[c];
+            st_act(o + (size_t)h * D + i, A);
         }
     }
 }

@@ -443,7 +443,7 @@ struct Builder {
             }
         }
         max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d));
-        max_xs_bytes = std::max(max_xs_bytes, (uint32_t)(t.nc * (d.d + kPartPad) * 4));
+        max_xs_bytes = std::max(max_xs_bytes, (uint32_t)(t.nc * (d.d + kPartPad + 1) * 4));   // combine task: partial rows + merge weights
         return true;
     }
 };
