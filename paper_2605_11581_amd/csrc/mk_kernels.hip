@@ -15,6 +15,7 @@
 // chunks of each task are loaded into registers before the wait.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "mk_isa.h"
 
@@ -1313,17 +1314,27 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
     const int npos = as.npos;
 
-    // Online softmax over batches of three positions per lane group: one running-max update and one
-    // rescale of the accumulators per batch instead of per position (wave64 VALU ops cost four
-    // cycles each, and this loop is VALU-bound).
-    auto batch3 = [&](const u32x4 &k0, const u32x4 &v0, bool ok0, const u32x4 &k1, const u32x4 &v1, bool ok1,
+    // this lane's 8-dim slice of every (rotated, pre-scaled) q head, read from LDS once
+    f32x4 qreg[kMaxGroup][2];
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) {
+        const f32x4 *qp = (const f32x4 *)(sq + (h < G ? h : 0) * D + dl * 8);
+        qreg[h][0] = qp[0];
+        qreg[h][1] = qp[1];
+    }
+
+    // Online softmax over batches of up to three positions per lane group: one running-max update and
+    // one rescale of the accumulators per batch instead of per position (wave64 VALU ops cost four
+    // cycles each, and this loop is VALU-bound).  N = positions actually present in the batch.
+    auto batchN = [&](auto nn, const u32x4 &k0, const u32x4 &v0, bool ok0, const u32x4 &k1, const u32x4 &v1, bool ok1,
                       const u32x4 &k2, const u32x4 &v2, bool ok2) {
+        constexpr int N = decltype(nn)::value;
         const u32x4 kw[3] = {k0, k1, k2};
         const u32x4 vw[3] = {v0, v1, v2};
         const bool ok[3] = {ok0, ok1, ok2};
-        float vf[3][8];
+        float vf[N][8];
 #pragma unroll
-        for (int u = 0; u < 3; ++u) {
+        for (int u = 0; u < N; ++u) {
             // a masked position contributes exactly zero whatever its (possibly never written) row holds
             const u32x4 vv = ok[u] ? vw[u] : u32x4{0u, 0u, 0u, 0u};
             vf[u][0] = bf_lo(vv.x); vf[u][1] = bf_hi(vv.x); vf[u][2] = bf_lo(vv.y); vf[u][3] = bf_hi(vv.y);
@@ -1332,24 +1343,29 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 #pragma unroll
         for (int h = 0; h < kMaxGroup; ++h)
             if (h < G) {
-                // q stays in LDS (all lanes of a position group read the same 32 bytes: broadcast)
-                const f32x4 *qp = (const f32x4 *)(sq + h * D + dl * 8);
-                const f32x4 q0 = qp[0], q1 = qp[1];
-                float sc3[3];
+                const f32x4 q0 = qreg[h][0], q1 = qreg[h][1];
+                float sc[N];
+                float mn = st.m[h];
 #pragma unroll
-                for (int u = 0; u < 3; ++u) {
+                for (int u = 0; u < N; ++u) {
                     float d = q0.x * bf_lo(kw[u].x) + q0.y * bf_hi(kw[u].x) + q0.z * bf_lo(kw[u].y) + q0.w * bf_hi(kw[u].y) +
                               q1.x * bf_lo(kw[u].z) + q1.y * bf_hi(kw[u].z) + q1.z * bf_lo(kw[u].w) + q1.w * bf_hi(kw[u].w);
                     d = (LPP == 16) ? row_sum16(d) : row_sum8(d);
-                    sc3[u] = ok[u] ? d : -INFINITY;
+                    sc[u] = ok[u] ? d : -INFINITY;
+                    mn = fmaxf(mn, sc[u]);
                 }
-                const float mn = fmaxf(fmaxf(st.m[h], sc3[0]), fmaxf(sc3[1], sc3[2]));
                 const float rs = safe_exp_diff(st.m[h], mn);
-                const float p0 = safe_exp_diff(sc3[0], mn), p1 = safe_exp_diff(sc3[1], mn), p2 = safe_exp_diff(sc3[2], mn);
-                st.l[h] = st.l[h] * rs + (p0 + p1 + p2);
+                float pr[N], psum = 0.f;
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    st.acc[h][j] = st.acc[h][j] * rs + (p0 * vf[0][j] + p1 * vf[1][j] + p2 * vf[2][j]);
+                for (int u = 0; u < N; ++u) { pr[u] = safe_exp_diff(sc[u], mn); psum += pr[u]; }
+                st.l[h] = st.l[h] * rs + psum;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    float a = pr[0] * vf[0][j];
+#pragma unroll
+                    for (int u = 1; u < N; ++u) a += pr[u] * vf[u][j];
+                    st.acc[h][j] = st.acc[h][j] * rs + a;
+                }
                 st.m[h] = mn;
             }
     };
@@ -1366,7 +1382,8 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                 ok[u] = grp < npos && att_pos(grp + sub, bs, nc, c) < p;
             }
             if ((base + wave + j0 * kWaves) * PPW < npos)
-                batch3(as.kbuf[j0], as.vbuf[j0], ok[0], as.kbuf[j0 + 1], as.vbuf[j0 + 1], ok[1], as.kbuf[j0 + 2], as.vbuf[j0 + 2], ok[2]);
+                batchN(std::integral_constant<int, 3>{}, as.kbuf[j0], as.vbuf[j0], ok[0], as.kbuf[j0 + 1], as.vbuf[j0 + 1], ok[1],
+                       as.kbuf[j0 + 2], as.vbuf[j0 + 2], ok[2]);
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int ngrp = (base + wave + (j0 + u) * kWaves) * PPW + kAttPrefetch * kWaves * PPW;
@@ -1391,7 +1408,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         vw.y = (uint32_t)f_to_bf(vn[2]) | ((uint32_t)f_to_bf(vn[3]) << 16);
         vw.z = (uint32_t)f_to_bf(vn[4]) | ((uint32_t)f_to_bf(vn[5]) << 16);
         vw.w = (uint32_t)f_to_bf(vn[6]) | ((uint32_t)f_to_bf(vn[7]) << 16);
-        batch3(kw, vw, sub == 0, zero4, zero4, false, zero4, zero4, false);
+        batchN(std::integral_constant<int, 1>{}, kw, vw, sub == 0, zero4, zero4, false, zero4, zero4, false);
     }
 
     trace_mark(P, pc, 1);

@@ -66,6 +66,13 @@ def report(tr, seq, layer: int, out=sys.stdout) -> None:
               f"{np.median(t1):7.1f} {t1.max():7.1f} | {t3.min():7.1f} {np.median(t3):7.1f} {t3.max():7.1f} | "
               f"{(t1 - t0).mean():5.2f} {(t2 - t1).mean():5.2f} {(t3 - t2).mean():6.2f} | {gap}", file=out)
         prev_end = t3.max()
+    # inside the attention tasks (task-internal marks): q/k/v prologue, history loop, slot merge, store
+    m = valid & (seq % 8 == 1) & (seq // 8 == layer)
+    if m.any():
+        t1, t3 = us(tr[..., 1][m]), us(tr[..., 3][m])
+        k0, k1, k2 = (us(tr[..., 4 + k][m]) for k in range(3))
+        print(f"L{layer:02d} ATT inside a task (mean us): prologue {np.mean(k0 - t1):.2f}, history loop {np.mean(k1 - k0):.2f}, "
+              f"slot merge {np.mean(k2 - k1):.2f}, weights + store + signal {np.mean(t3 - k2):.2f}", file=out)
     print("mean over all layers: level span (first begin to last end), wait, prologue, body [us]", file=out)
     for st in sorted(per_stage):
         a = np.array(per_stage[st]).mean(0)
