@@ -53,6 +53,7 @@ struct Wg {
     uint32_t red_bytes, xs_off;
     bool ring;            // weights come through the page ring (else: straight into registers)
     int npf;              // 128-bit weight loads a lane keeps in flight (direct-load path), <= kPrefetch
+    uint32_t pc;          // index of the instruction being executed (task trace)
     uint32_t wave;
     uint32_t ring_off;    // byte offset of this wave's page 0 from the LDS base
     uint32_t ring_lds;    // LDS address of this wave's page 0
@@ -1024,34 +1025,52 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             step(w1, w0, g + 1);
         }
     } else if (W4) {
+        // Rounds of kPrefetchW4 slots per wave: a slot is consumed, then refilled with the chunk one round
+        // ahead.  The last round refills nothing, so no load is outstanding when the task ends (the
+        // store drain before the task's signal would wait for it).
         if (total) {
             const uint32_t last = total - 1;
             constexpr uint32_t round = (uint32_t)kPrefetchW4 * kWaves;
-            for (uint32_t base = 0; base < total; base += round) {
+            uint32_t base = 0;
+            for (; base + round < total; base += round) {
 #pragma unroll
                 for (int j = 0; j < kPrefetchW4; ++j) {
                     const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
-                    if (idx < total) consume(st.buf[j], w4_scale_get(st, j));
+                    consume(st.buf[j], w4_scale_get(st, j));
                     const uint32_t nidx = min(idx + round, last);
                     st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
                     w4_scale_set(st, j, st.sp[(size_t)nidx * st.spc]);
                 }
             }
+#pragma unroll
+            for (int j = 0; j < kPrefetchW4; ++j) {
+                const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+                if (idx < total) consume(st.buf[j], w4_scale_get(st, j));
+            }
         }
     } else if (total) {
         const uint32_t last = total - 1;
         const uint32_t round = (uint32_t)lp.npf * kWaves;
-        for (uint32_t base = 0; base < total; base += round) {
+        uint32_t base = 0;
+        for (; base + round < total; base += round) {
 #pragma unroll
             for (int j = 0; j < kPrefetch; ++j) {
                 if (j >= lp.npf) continue;
                 const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
-                if (idx < total) consume(st.buf[j]);
+                consume(st.buf[j]);
                 // refill the slot: always a load (clamped to the task's last chunk), so the slot's
                 // registers are written by exactly one instruction and nothing waits on it here
                 const uint32_t nidx = min(idx + round, last);
                 st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
             }
+        }
+        // last round: nothing to refill, so no load is outstanding when the task ends (the store
+        // drain before the task's signal would wait for it)
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j) {
+            if (j >= lp.npf) continue;
+            const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+            if (idx < total) consume(st.buf[j]);
         }
     }
     // flush the current unit and any trailing units this wave had no chunk in
@@ -1060,6 +1079,8 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         ++ul;
     }
     wg_sync(lp, lds);
+    if ((P.flags & 1u) && tid == 0 && P.only_seq == kNone)   // task trace, mark 3: weights consumed, partial sums in LDS
+        ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + lp.pc) * 8 + 7] = wall_clock64();
 
     // cross-wave sum in fixed wave order, then the epilogue
     const ActBuf ab = act_buf(P);
@@ -1572,6 +1593,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
                                            bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr)
 {
     const int tid = threadIdx.x;
+    lp.pc = pc;
     uint32_t *sflag = (uint32_t *)(lds + kLdsMisc + 128);
     const uint32_t *counters = (const uint32_t *)(P.ws + P.lay.counters);
     uint64_t t0 = 0, t1 = 0;

@@ -73,6 +73,13 @@ def report(tr, seq, layer: int, out=sys.stdout) -> None:
         k0, k1, k2 = (us(tr[..., 4 + k][m]) for k in range(3))
         print(f"L{layer:02d} ATT inside a task (mean us): prologue {np.mean(k0 - t1):.2f}, history loop {np.mean(k1 - k0):.2f}, "
               f"slot merge {np.mean(k2 - k1):.2f}, weights + store + signal {np.mean(t3 - k2):.2f}", file=out)
+    # inside the GEMV bodies: weights consumed (partial sums in LDS), then cross-wave sum + epilogue + store drain + signal
+    for st in (0, 3, 4, 5):
+        m = valid & (seq % 8 == st) & (seq // 8 == layer)
+        if m.any() and (tr[..., 7][m] > 0).all():
+            t2, t3, k3 = us(tr[..., 2][m]), us(tr[..., 3][m]), us(tr[..., 7][m])
+            print(f"L{layer:02d} {STAGES[st]:5s} inside a body (mean us): weight loop + flush {np.mean(k3 - t2):.2f}, "
+                  f"reduce + epilogue + drain + signal {np.mean(t3 - k3):.2f}", file=out)
     print("mean over all layers: level span (first begin to last end), wait, prologue, body [us]", file=out)
     for st in sorted(per_stage):
         a = np.array(per_stage[st]).mean(0)
