@@ -26,7 +26,9 @@ constexpr int kMaxGroup = 8;           // q heads per kv head
 constexpr int kCounterStride = 32;     // default dwords between sub-counters (one 128-byte line each)
 constexpr int kCounterSubs = 16;       // default sub-counters per dependency counter
 constexpr int kCounterStrideMax = 1088; // the counter region holds this many dwords per dependency counter
-constexpr int kPrefetch = 16;          // 128-bit weight loads a lane keeps in flight (direct-load path)
+constexpr int kPrefetch = 6;           // 128-bit bf16 weight loads a lane keeps in flight (direct-load path): 24 KB per
+                                       // workgroup; measured best of 4..32 on every shape (deeper bursts delay the
+                                       // dependency polls and activation loads queued behind them)
 
 // LDS map of a workgroup:
 //   [0, 256)    current instruction

@@ -806,17 +806,19 @@ __device__ __forceinline__ void ring_fill_stage(const Params &P, Wg &wg)
     wg.hst = wg.hst + 1 == wg.nst ? 0 : wg.hst + 1;
 }
 
+// W4 tasks keep kPrefetchW4 chunks in flight per lane (their dequantisation is VALU work that more
+// loads in flight cover); the scales that go with them are packed four to a slot behind the chunks.
+constexpr int kPrefetchW4 = 12;
+constexpr int kW4Slots = kPrefetchW4 + (kPrefetchW4 + 3) / 4;
+constexpr int kBufSlots = kPrefetch > kW4Slots ? kPrefetch : kW4Slots;
+
 struct GemvStream {
     const __attribute__((address_space(1))) u32x4 *wp;   // this lane's pointer to chunk 0 of the task
     uint32_t total;       // chunks in the task
-    u32x4 buf[kPrefetch]; // direct-load path only
+    u32x4 buf[kBufSlots]; // direct-load path only: bf16 tasks use the first kPrefetch slots, W4 tasks kPrefetchW4 + scales
     const __attribute__((address_space(1))) uint16_t *sp;   // W4: this lane's scale of chunk 0 of the task
     uint32_t spc;                                            // W4: scales per chunk (2048 / group)
 };
-// W4 tasks keep kPrefetchW4 chunks in flight per lane; the scales that go with them live in the
-// dwords of the unused buffers behind (no extra registers in the kernel's live set).
-constexpr int kPrefetchW4 = 12;
-static_assert(kPrefetchW4 + (kPrefetchW4 + 3) / 4 <= kPrefetch, "scales must fit behind the W4 chunk buffers");
 __device__ __forceinline__ uint32_t w4_scale_get(const GemvStream &st, int j) { return st.buf[kPrefetchW4 + (j >> 2)][j & 3]; }
 __device__ __forceinline__ void w4_scale_set(GemvStream &st, int j, uint32_t v) { st.buf[kPrefetchW4 + (j >> 2)][j & 3] = v; }
 
@@ -1604,46 +1606,47 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     // and an arg-max task whose result nobody takes only has to signal.
     const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens);
     const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u) && !no_dep;
-    GemvStream st;
-    AttStream as;
     constexpr bool W4 = PATH == kPathW4;
-    if (I.op == OP_GEMV) gemv_issue<RING, W4>(P, I, st, lp.npf);
-    else if (I.op == OP_ATT) {
-        if (P.head_dim == 128) att_issue<128>(P, lp, *(const InstrAtt *)&I, as);
-        else att_issue<64>(P, lp, *(const InstrAtt *)&I, as);
-    }
+    uint64_t t2 = 0;
 
-    if (PERSISTENT && I.op == OP_GEMV) trace_mark(P, pc, 0);
-    if (PERSISTENT) {
-        if (tid < 64) {   // the first wave polls
-            uint32_t ok = 1, polls = 0;
-            if (waiting) {
-                if (I.wait_ctr[0] != kNone)
-                    ok = wait_counter(P, counters, I.wait_ctr[0], (lp.epoch - ((I.flags & F_WAIT_PREV) ? 1u : 0u)) * I.wait_cnt[0],
-                                      &polls) ? 1u : 0u;
-                if (ok && I.wait_ctr[1] != kNone)
-                    ok = wait_counter(P, counters, I.wait_ctr[1], lp.epoch * I.wait_cnt[1], &polls) ? 1u : 0u;
-            }
-            if (tid == 0) {
-                if (!ok) set_err(P, 0, 1u + pc);
-                sflag[0] = ok;
-                if (I.op == OP_GEMV) {
-                    trace_mark(P, pc, 1);
-                    if (tracing) ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 6] = polls;   // mark 2: polls issued
+    // The dependency wait of the task; called once, after the task's prefetch has been issued.
+    auto await = [&]() {
+        if (PERSISTENT) {
+            if (tid < 64) {   // the first wave polls
+                uint32_t ok = 1, polls = 0;
+                if (waiting) {
+                    if (I.wait_ctr[0] != kNone)
+                        ok = wait_counter(P, counters, I.wait_ctr[0], (lp.epoch - ((I.flags & F_WAIT_PREV) ? 1u : 0u)) * I.wait_cnt[0],
+                                          &polls) ? 1u : 0u;
+                    if (ok && I.wait_ctr[1] != kNone)
+                        ok = wait_counter(P, counters, I.wait_ctr[1], lp.epoch * I.wait_cnt[1], &polls) ? 1u : 0u;
+                }
+                if (tid == 0) {
+                    if (!ok) set_err(P, 0, 1u + pc);
+                    sflag[0] = ok;
+                    if (I.op == OP_GEMV) {
+                        trace_mark(P, pc, 1);
+                        if (tracing) ((uint64_t *)(P.ws + P.lay.trace))[((size_t)blockIdx.x * P.max_instr + pc) * 8 + 6] = polls;   // mark 2: polls issued
+                    }
                 }
             }
+            // The next instruction (loaded by the caller before this task began) has certainly arrived
+            // by now; parking it in its LDS slot here means nothing waits on memory between the end
+            // of this task and the start of the next one.
+            if (nxt_slot && tid < kInstrDwords) nxt_slot[tid] = nxt;
+            wg_sync(lp, lds);
+            if (sflag[0] == 0) dead = true;
         }
-        // The next instruction (loaded by the caller before this task began) has certainly arrived
-        // by now; parking it in its LDS slot here means nothing waits on memory between the end
-        // of this task and the start of the next one.
-        if (nxt_slot && tid < kInstrDwords) nxt_slot[tid] = nxt;
-        wg_sync(lp, lds);
-        if (sflag[0] == 0) dead = true;
-    }
-    if (tracing && tid == 0) t1 = wall_clock64();
+        if (tracing && tid == 0) t1 = wall_clock64();
+    };
 
-    uint64_t t2 = 0;
+    // Each kind of task is one straight path (prefetch, wait, work), so that the prefetch registers
+    // of one kind are not kept alive across the code of another.
     if (I.op == OP_GEMV) {
+        GemvStream st;
+        gemv_issue<RING, W4>(P, I, st, lp.npf);
+        if (PERSISTENT) trace_mark(P, pc, 0);
+        await();
         if (PATH == kPathMfma || (PATH == kPathAny16 && (I.flags & F_MFMA))) {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
             if (tracing && tid == 0) t2 = wall_clock64();
@@ -1656,12 +1659,20 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         }
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
-        if (P.head_dim == 128) att_task<128>(P, A, lds, lp, as, pc);
-        else att_task<64>(P, A, lds, lp, as, pc);
-    } else if (I.op == OP_COMB) {
-        comb_task(P, *(const InstrAtt *)&I, lds, lp);
-    } else if (I.op == OP_ARGMAX) {
-        argmax_task(P, *(const InstrAtt *)&I, lds, lp);
+        AttStream as;
+        if (P.head_dim == 128) {
+            att_issue<128>(P, lp, A, as);
+            await();
+            att_task<128>(P, A, lds, lp, as, pc);
+        } else {
+            att_issue<64>(P, lp, A, as);
+            await();
+            att_task<64>(P, A, lds, lp, as, pc);
+        }
+    } else {
+        await();
+        if (I.op == OP_COMB) comb_task(P, *(const InstrAtt *)&I, lds, lp);
+        else if (I.op == OP_ARGMAX) argmax_task(P, *(const InstrAtt *)&I, lds, lp);
     }
 
     if (PERSISTENT && I.sig_ctr != kNone) {
