@@ -171,6 +171,20 @@ __device__ __forceinline__ float row_sum16(float v)   // over a 16-lane row
     return v;
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true)));
+}
+__device__ __forceinline__ float row_max16(float v)   // over a 16-lane row (all 16 lanes active)
+{
+    v = dpp_max<0xB1>(v);
+    v = dpp_max<0x4E>(v);
+    v = dpp_max<0x141>(v);
+    v = dpp_max<0x140>(v);
+    return v;
+}
+
 __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
 {
     uint32_t *e = (uint32_t *)(P.ws + P.lay.err);
@@ -1453,34 +1467,33 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     wg_sync(lp, lds);
     trace_mark(P, pc, 2);
 
-    // merged max, denominators and per-slot weights of every head, computed once per (head, slot)
+    // merged max, denominator and per-slot weights of every head: thread (head, slot), the slots of a
+    // head in adjacent lanes (NSLOT is 16 or 32, so rows of 16 lanes are all active or all idle)
     float *sfac = smerge + (size_t)NSLOT * G * (D + 2);     // [G][NSLOT] weights, then [G] max, [G] denominators
+    static_assert(NSLOT == 16 || NSLOT == 32, "slot reduction works on rows of 16 lanes");
     if (tid < G * NSLOT) {
         const int h = tid / NSLOT, w = tid % NSLOT;
-        float M = -INFINITY;
-#pragma unroll
-        for (int x = 0; x < NSLOT; ++x) M = fmaxf(M, smerge[((size_t)x * G + h) * (D + 2) + D]);
         const float *src = smerge + ((size_t)w * G + h) * (D + 2);
-        sfac[h * NSLOT + w] = safe_exp_diff(src[D], M);
-        if (w == 0) sfac[G * NSLOT + h] = M;
+        const float m = src[D], l = src[D + 1];
+        float M = row_max16(m);
+        if (NSLOT == 32) M = fmaxf(M, __shfl_xor(M, 16, 64));
+        const float f = safe_exp_diff(m, M);
+        float L = row_sum16(f * l);
+        if (NSLOT == 32) L += __shfl_xor(L, 16, 64);
+        sfac[h * NSLOT + w] = f;
+        if (w == 0) { sfac[G * NSLOT + h] = M; sfac[G * NSLOT + G + h] = L; }
     }
     wg_sync(lp, lds);
     float *outp = (float *)(P.ws + P.lay.act) + I.out;
     for (int e = tid; e < G * D; e += kWgThreads) {
         int h = e / D, i = e % D;
-        const float M = sfac[G * NSLOT + h];
-        float L = 0.f, A = 0.f;
+        float A = 0.f;
 #pragma unroll
-        for (int w = 0; w < NSLOT; ++w) {
-            const float *src = smerge + ((size_t)w * G + h) * (D + 2);
-            const float f = sfac[h * NSLOT + w];
-            L += src[D + 1] * f;
-            A += src[i] * f;
-        }
+        for (int w = 0; w < NSLOT; ++w) A += smerge[((size_t)w * G + h) * (D + 2) + i] * sfac[h * NSLOT + w];
         // partial layout [b][head][nc][D + kPartStride]
         float *dst = outp + ((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc) + I.c) * (D + kPartStride);
         st_act(dst + i, A);
-        if (i == 0) { st_act(dst + D, M); st_act(dst + D + 1, L); }
+        if (i == 0) { st_act(dst + D, sfac[G * NSLOT + h]); st_act(dst + D + 1, sfac[G * NSLOT + G + h]); }
     }
 }
 
@@ -1495,7 +1508,7 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
     float *stage = (float *)(lds + lp.xs_off);
     float *o = (float *)(P.ws + P.lay.act) + I.o_out + (size_t)b * I.o_ld;
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
-    constexpr int U = 5;   // 128-bit loads in flight per lane: one round trip for 32 partial rows of a 128-wide head
+    constexpr int U = 9;   // 128-bit loads in flight per lane: one round trip for 64 partial rows of a 128-wide head
     for (int hh = 0; hh < (int)I.nh; ++hh) {
         const int h = (int)I.h0 + hh;
         const uint32_t src = I.out + (uint32_t)(((size_t)b * P.n_q_heads + h) * nc) * (uint32_t)RS;
