@@ -336,6 +336,12 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
         const int H = P.hidden, nq4 = H >> 2, total = batch * nq4;
         const uint32_t plane_stride = (uint32_t)H * 2u + 16u, seq_stride = (uint32_t)nterm * plane_stride;
         const uint16_t *gain = (const uint16_t *)(P.ws + P.lay.vecs) + I.gain;
+        uint2 gw[kQuadsPerThread];                       // constants: fetched with the input loads
+#pragma unroll
+        for (int j = 0; j < kQuadsPerThread; ++j) {
+            const int q = tid + j * kWgThreads;
+            gw[j] = q < nq4 ? *(const uint2 *)(gain + 4 * q) : uint2{0u, 0u};
+        }
         for (int e0 = tid; e0 < total; e0 += kWgThreads * kItems) {
             f32x4 v[kItems];
             uint32_t off[kItems];                        // b * in_ld + 4 q of the item, kNone past the end
@@ -410,10 +416,9 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
             for (int j = 0; j < kQuadsPerThread; ++j) {
                 const int q = tid + j * kWgThreads;
                 if (q < nq4) {
-                    uint2 gw = *(const uint2 *)(gain + 4 * q);
                     f32x4 y;
-                    y.x = v[j].x * inv * bf_lo(gw.x); y.y = v[j].y * inv * bf_hi(gw.x);
-                    y.z = v[j].z * inv * bf_lo(gw.y); y.w = v[j].w * inv * bf_hi(gw.y);
+                    y.x = v[j].x * inv * bf_lo(gw[j].x); y.y = v[j].y * inv * bf_hi(gw[j].x);
+                    y.z = v[j].z * inv * bf_lo(gw[j].y); y.w = v[j].w * inv * bf_hi(gw[j].y);
                     store_x4<true>(xs, b, 4 * q, y, nterm, plane_stride);
                 }
             }
@@ -516,6 +521,13 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         const int H = P.hidden, nq4 = H >> 2;
         const uint32_t plane_stride = (uint32_t)H * 2u + 16u;
         const uint16_t *gain = (const uint16_t *)(P.ws + P.lay.vecs) + I.gain;
+        // the gains are constants: fetch them first, so that they travel with the input loads
+        uint2 gw[kQuadsPerThread];
+#pragma unroll
+        for (int j = 0; j < kQuadsPerThread; ++j) {
+            const int q = tid + j * kWgThreads;
+            gw[j] = q < nq4 ? *(const uint2 *)(gain + 4 * q) : uint2{0u, 0u};
+        }
         for (int b = 0; b < batch; ++b) {
             f32x4 v[kQuadsPerThread];
             if (pro == PRO_EMBED_NORM) {
@@ -575,10 +587,9 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
             for (int j = 0; j < kQuadsPerThread; ++j) {
                 const int q = tid + j * kWgThreads;
                 if (q < nq4) {
-                    uint2 gw = *(const uint2 *)(gain + 4 * q);
                     f32x4 y;
-                    y.x = v[j].x * inv * bf_lo(gw.x); y.y = v[j].y * inv * bf_hi(gw.x);
-                    y.z = v[j].z * inv * bf_lo(gw.y); y.w = v[j].w * inv * bf_hi(gw.y);
+                    y.x = v[j].x * inv * bf_lo(gw[j].x); y.y = v[j].y * inv * bf_hi(gw[j].x);
+                    y.z = v[j].z * inv * bf_lo(gw[j].y); y.w = v[j].w * inv * bf_hi(gw[j].y);
                     store_x4<MFMA>(xs, b, 4 * q, y, nterm, plane_stride);
                 }
             }
@@ -993,6 +1004,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         const uint32_t ub = (uint32_t)tid >> rlog, uu = u0 + ub;
         resid0 = ld_act((const float *)(P.ws + P.lay.act) + I.resid + (size_t)(uu / S) * R + ((uint32_t)tid & (R - 1)));
     }
+    // Likewise the bias of this thread's first output (a constant).
+    float bias0 = 0.f;
+    if (I.bias != kNone && (uint32_t)tid < red_per_wave) {
+        const uint32_t nb0 = (uint32_t)(MFMA ? batch : 1);
+        const uint32_t uu = u0 + ((uint32_t)tid >> rlog) / nb0, row = (uu / S) * R + ((uint32_t)tid & (R - 1));
+        if (uu % S == 0 && row < I.n_rows) bias0 = bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
+    }
     const uint32_t total = st.total;
     if (RING) {
         // Weights come from this wave's LDS page ring, a stage (up to four chunks) at a time:
@@ -1127,7 +1145,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             uint32_t rg = uu / S, s = uu % S;
             uint32_t row = rg * R + r;
             if (I.bias != kNone && s == 0 && row < I.n_rows)
-                v += bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
+                v += t == (uint32_t)tid ? bias0 : bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
             if (I.flags & F_LOGITS) {
                 if (row < I.n_rows) lp.logits[(size_t)b * P.vocab + row] = v;
                 // this thread is the only reader of index t of the reduction area: keep the finished
