@@ -1121,10 +1121,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     float *actw = (float *)(P.ws + P.lay.act);
     const uint32_t nb = (uint32_t)(MFMA ? batch : 1);
     auto rsum = [&](uint32_t t) {
-        float v = red[t];
         constexpr int kSlots = MFMA ? kWaves : kWaves * 4;   // VALU path: one slot per (wave, 16-lane row)
+        float p[kSlots];                                     // all LDS reads first, then the sum in slot order
 #pragma unroll
-        for (int w = 1; w < kSlots; ++w) v += red[w * red_per_wave + t];
+        for (int w = 0; w < kSlots; ++w) p[w] = red[w * red_per_wave + t];
+        float v = p[0];
+#pragma unroll
+        for (int w = 1; w < kSlots; ++w) v += p[w];
         return v;
     };
     if (I.flags & F_SILU_EPI) {
@@ -1505,14 +1508,22 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     float *outp = (float *)(P.ws + P.lay.act) + I.out;
     for (int e = tid; e < G * D; e += kWgThreads) {
         int h = e / D, i = e % D;
+        // all LDS reads first, then the sum in slot order (the reads overlap instead of each waiting for the last)
+        float sv[NSLOT], fv[NSLOT];
+#pragma unroll
+        for (int w = 0; w < NSLOT; ++w) {
+            sv[w] = smerge[((size_t)w * G + h) * (D + 2) + i];
+            fv[w] = sfac[h * NSLOT + w];
+        }
         float A = 0.f;
 #pragma unroll
-        for (int w = 0; w < NSLOT; ++w) A += smerge[((size_t)w * G + h) * (D + 2) + i] * sfac[h * NSLOT + w];
+        for (int w = 0; w < NSLOT; ++w) A += sv[w] * fv[w];
         // partial layout [b][head][nc][D + kPartStride]
         float *dst = outp + ((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc) + I.c) * (D + kPartStride);
         st_act(dst + i, A);
         if (i == 0) { st_act(dst + D, sfac[G * NSLOT + h]); st_act(dst + D + 1, sfac[G * NSLOT + G + h]); }
     }
+    trace_mark(P, pc, 3);
 }
 
 // Combine the nc flash-decode partials of q heads h0 .. h0+nh of sequence b: the partial rows
@@ -1560,8 +1571,15 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
         wg_sync(lp, lds);
         for (int i = threadIdx.x; i < D; i += kWgThreads) {
             float A = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < nc; ++c) A += stage[c * RS + i] * wgt[c];
+            int c = 0;
+            for (; c + 8 <= nc; c += 8) {      // eight rows' reads in flight, summed in chunk order
+                float sv[8], fv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { sv[u] = stage[(c + u) * RS + i]; fv[u] = wgt[c + u]; }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) A += sv[u] * fv[u];
+            }
+            for (; c < nc; ++c) A += stage[c * RS + i] * wgt[c];
             st_act(o + (size_t)h * D + i, A);
         }
     }

@@ -70,9 +70,10 @@ def report(tr, seq, layer: int, out=sys.stdout) -> None:
     m = valid & (seq % 8 == 1) & (seq // 8 == layer)
     if m.any():
         t1, t3 = us(tr[..., 1][m]), us(tr[..., 3][m])
-        k0, k1, k2 = (us(tr[..., 4 + k][m]) for k in range(3))
+        k0, k1, k2, k3 = (us(tr[..., 4 + k][m]) for k in range(4))
         print(f"L{layer:02d} ATT inside a task (mean us): prologue {np.mean(k0 - t1):.2f}, history loop {np.mean(k1 - k0):.2f}, "
-              f"slot merge {np.mean(k2 - k1):.2f}, weights + store + signal {np.mean(t3 - k2):.2f}", file=out)
+              f"slots to LDS {np.mean(k2 - k1):.2f}, merge + stores issued {np.mean(k3 - k2):.2f}, "
+              f"store drain + signal {np.mean(t3 - k3):.2f}", file=out)
     # inside the GEMV bodies: weights consumed (partial sums in LDS), then cross-wave sum + epilogue + store drain + signal
     for st in (0, 3, 4, 5):
         m = valid & (seq % 8 == st) & (seq // 8 == layer)
