@@ -1289,7 +1289,8 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     // LDS scratch inside the xs region
     float *sq = (float *)(lds + lp.xs_off);              // [G][D] rotated, pre-scaled q
     float *snew = sq + kMaxGroup * D;                    // [2][D] new k (rotated, bf16-rounded) and v
-    float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][D + 2]
+    float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][MS]: acc[D], m, l, pad (rows 16-byte aligned)
+    constexpr int MS = D + 4;
     const int jb_new = p >> kAttBlockLog;
     const bool owner = (jb_new % (int)I.nc) == (int)I.c;
 
@@ -1477,7 +1478,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 #pragma unroll
         for (int h = 0; h < kMaxGroup; ++h)
             if (h < G) {
-                float *dst = smerge + ((size_t)slot * G + h) * (D + 2);
+                float *dst = smerge + ((size_t)slot * G + h) * MS;
                 f32x4 lo4 = {st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]};
                 f32x4 hi4 = {st.acc[h][4], st.acc[h][5], st.acc[h][6], st.acc[h][7]};
                 *(f32x4 *)(dst + dl * 8) = lo4;
@@ -1490,11 +1491,11 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 
     // merged max, denominator and per-slot weights of every head: thread (head, slot), the slots of a
     // head in adjacent lanes (NSLOT is 16 or 32, so rows of 16 lanes are all active or all idle)
-    float *sfac = smerge + (size_t)NSLOT * G * (D + 2);     // [G][NSLOT] weights, then [G] max, [G] denominators
+    float *sfac = smerge + (size_t)NSLOT * G * MS;     // [G][NSLOT] weights, then [G] max, [G] denominators
     static_assert(NSLOT == 16 || NSLOT == 32, "slot reduction works on rows of 16 lanes");
     if (tid < G * NSLOT) {
         const int h = tid / NSLOT, w = tid % NSLOT;
-        const float *src = smerge + ((size_t)w * G + h) * (D + 2);
+        const float *src = smerge + ((size_t)w * G + h) * MS;
         const float m = src[D], l = src[D + 1];
         float M = row_max16(m);
         if (NSLOT == 32) M = fmaxf(M, __shfl_xor(M, 16, 64));
@@ -1505,23 +1506,28 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         if (w == 0) { sfac[G * NSLOT + h] = M; sfac[G * NSLOT + G + h] = L; }
     }
     wg_sync(lp, lds);
-    float *outp = (float *)(P.ws + P.lay.act) + I.out;
-    for (int e = tid; e < G * D; e += kWgThreads) {
-        int h = e / D, i = e % D;
-        // all LDS reads first, then the sum in slot order (the reads overlap instead of each waiting for the last)
-        float sv[NSLOT], fv[NSLOT];
+    const ActBuf ab = act_buf(P);
+    for (int e = tid; e < G * D / 4; e += kWgThreads) {       // four adjacent outputs per thread
+        const int h = (4 * e) / D, i = (4 * e) % D;
+        // all LDS reads first, then the sums in slot order (the reads overlap instead of each waiting for the last)
+        f32x4 sv[NSLOT];
+        float fv[NSLOT];
 #pragma unroll
         for (int w = 0; w < NSLOT; ++w) {
-            sv[w] = smerge[((size_t)w * G + h) * (D + 2) + i];
+            sv[w] = *(const f32x4 *)(smerge + ((size_t)w * G + h) * MS + i);
             fv[w] = sfac[h * NSLOT + w];
         }
-        float A = 0.f;
+        f32x4 A = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < NSLOT; ++w) A += sv[w] * fv[w];
         // partial layout [b][head][nc][D + kPartStride]
-        float *dst = outp + ((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc) + I.c) * (D + kPartStride);
-        st_act(dst + i, A);
-        if (i == 0) { st_act(dst + D, sfac[G * NSLOT + h]); st_act(dst + D + 1, sfac[G * NSLOT + G + h]); }
+        const uint32_t dst = I.out + (uint32_t)((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc + I.c) * (D + kPartStride));
+        st_act4(ab, dst + (uint32_t)i, A);
+        if (i == 0) {
+            float *ml = (float *)(P.ws + P.lay.act) + dst + D;
+            st_act(ml, sfac[G * NSLOT + h]);
+            st_act(ml + 1, sfac[G * NSLOT + G + h]);
+        }
     }
     trace_mark(P, pc, 3);
 }

@@ -155,7 +155,7 @@ struct LdsBudget {
 
 static uint32_t att_scratch_bytes(const Dims &d)
 {
-    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 2 + 1) + 2 * kMaxGroup) * 4u;   // q, new k/v, per-slot merge, merge weights
+    return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 4 + 1) + 2 * kMaxGroup) * 4u;   // q, new k/v, per-slot merge rows (d + 4), merge weights
 }
 
 static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
