@@ -648,9 +648,9 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
                 continue;
             }
             if (pro == PRO_PLAIN && n_parts == 1) {
-                // common case (unsplit producer): eight 128-bit loads in flight per lane, one memory round
-                // trip for up to 8192 staged elements
-                constexpr int U = 8;
+                // common case (unsplit producer): nine 128-bit loads in flight per lane, one memory round
+                // trip for up to 9216 staged elements (the 8960-wide MLP of the 1.5B shape fits)
+                constexpr int U = 9;
                 for (int i0 = tid * 4; i0 < kn; i0 += kWgThreads * 4 * U) {
                     f32x4 y[U];
 #pragma unroll
