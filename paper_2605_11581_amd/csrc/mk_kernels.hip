@@ -1246,7 +1246,7 @@ __device__ __forceinline__ void att_issue(const Params &P, const Wg &lp, const I
     if (b >= P.batch) return;
     const int p = position_of(P, lp, b);
     const int bs = (int)I.bs, nc = (int)I.nc, c = (int)I.c;
-    const int nblk_all = (p + bs - 1) >> kAttBlockLog;            // blocks containing positions < p
+    const int nblk_all = (p + bs) >> kAttBlockLog;                // blocks containing positions <= p (the new one included)
     const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
     st.p = p; st.npos = my_blocks * bs;
     const size_t head_elems = (size_t)P.max_context * D;
@@ -1264,7 +1264,7 @@ __device__ __forceinline__ void att_issue(const Params &P, const Wg &lp, const I
         t = t < p ? t : p - 1;
         st.kbuf[j] = u32x4{0u, 0u, 0u, 0u};
         st.vbuf[j] = u32x4{0u, 0u, 0u, 0u};
-        if (grp < st.npos) {
+        if (grp < st.npos && p > 0) {
             st.kbuf[j] = __builtin_nontemporal_load(st.kp + (size_t)t * LPP);
             st.vbuf[j] = __builtin_nontemporal_load(st.vp + (size_t)t * LPP);
         }
@@ -1429,24 +1429,42 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
             }
     };
     static_assert(kAttPrefetch % 3 == 0, "the prefetch slots are consumed three at a time");
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    // The new position p sits in the owner task's last block like any history position; its K and V
+    // rows come from LDS (this lane's 8-dim slice, bf16-rounded like the rows in the cache) instead
+    // of from the load, which went to row p - 1.
+    u32x4 knew = {0u, 0u, 0u, 0u}, vnew = {0u, 0u, 0u, 0u};
+    if (owner) {
+        const float *kn = snew + dl * 8, *vn = snew + D + dl * 8;
+        knew.x = (uint32_t)f_to_bf(kn[0]) | ((uint32_t)f_to_bf(kn[1]) << 16);
+        knew.y = (uint32_t)f_to_bf(kn[2]) | ((uint32_t)f_to_bf(kn[3]) << 16);
+        knew.z = (uint32_t)f_to_bf(kn[4]) | ((uint32_t)f_to_bf(kn[5]) << 16);
+        knew.w = (uint32_t)f_to_bf(kn[6]) | ((uint32_t)f_to_bf(kn[7]) << 16);
+        vnew.x = (uint32_t)f_to_bf(vn[0]) | ((uint32_t)f_to_bf(vn[1]) << 16);
+        vnew.y = (uint32_t)f_to_bf(vn[2]) | ((uint32_t)f_to_bf(vn[3]) << 16);
+        vnew.z = (uint32_t)f_to_bf(vn[4]) | ((uint32_t)f_to_bf(vn[5]) << 16);
+        vnew.w = (uint32_t)f_to_bf(vn[6]) | ((uint32_t)f_to_bf(vn[7]) << 16);
+    }
 
     for (int base = 0; base * PPW < npos; base += kAttPrefetch * kWaves) {
 #pragma unroll
         for (int j0 = 0; j0 < kAttPrefetch; j0 += 3) {
             bool ok[3];
+            u32x4 kk[3], vv[3];
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int grp = (base + wave + (j0 + u) * kWaves) * PPW;
-                ok[u] = grp < npos && att_pos(grp + sub, bs, nc, c) < p;
+                const int t = att_pos(grp + sub, bs, nc, c);
+                ok[u] = grp < npos && t <= p;
+                const bool fresh = t == p;        // only ever true in the owner task
+                kk[u] = fresh ? knew : as.kbuf[j0 + u];
+                vv[u] = fresh ? vnew : as.vbuf[j0 + u];
             }
             if ((base + wave + j0 * kWaves) * PPW < npos)
-                batchN(std::integral_constant<int, 3>{}, as.kbuf[j0], as.vbuf[j0], ok[0], as.kbuf[j0 + 1], as.vbuf[j0 + 1], ok[1],
-                       as.kbuf[j0 + 2], as.vbuf[j0 + 2], ok[2]);
+                batchN(std::integral_constant<int, 3>{}, kk[0], vv[0], ok[0], kk[1], vv[1], ok[1], kk[2], vv[2], ok[2]);
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int ngrp = (base + wave + (j0 + u) * kWaves) * PPW + kAttPrefetch * kWaves * PPW;
-                if (ngrp < npos) {
+                if (ngrp < npos) {   // (a second round implies p > 0)
                     int t = att_pos(ngrp + sub, bs, nc, c);
                     t = t < p ? t : p - 1;
                     as.kbuf[j0 + u] = __builtin_nontemporal_load(as.kp + (size_t)t * LPP);
@@ -1454,20 +1472,6 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
                 }
             }
         }
-    }
-    // the new position, from LDS, by the first position slot of wave 0 of the owner task
-    if (owner && wave == 0) {
-        const float *kn = snew + dl * 8, *vn = snew + D + dl * 8;
-        u32x4 kw, vw;
-        kw.x = (uint32_t)f_to_bf(kn[0]) | ((uint32_t)f_to_bf(kn[1]) << 16);
-        kw.y = (uint32_t)f_to_bf(kn[2]) | ((uint32_t)f_to_bf(kn[3]) << 16);
-        kw.z = (uint32_t)f_to_bf(kn[4]) | ((uint32_t)f_to_bf(kn[5]) << 16);
-        kw.w = (uint32_t)f_to_bf(kn[6]) | ((uint32_t)f_to_bf(kn[7]) << 16);
-        vw.x = (uint32_t)f_to_bf(vn[0]) | ((uint32_t)f_to_bf(vn[1]) << 16);
-        vw.y = (uint32_t)f_to_bf(vn[2]) | ((uint32_t)f_to_bf(vn[3]) << 16);
-        vw.z = (uint32_t)f_to_bf(vn[4]) | ((uint32_t)f_to_bf(vn[5]) << 16);
-        vw.w = (uint32_t)f_to_bf(vn[6]) | ((uint32_t)f_to_bf(vn[7]) << 16);
-        batchN(std::integral_constant<int, 1>{}, kw, vw, sub == 0, zero4, zero4, false, zero4, zero4, false);
     }
 
     trace_mark(P, pc, 1);
