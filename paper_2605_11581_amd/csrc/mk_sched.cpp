@@ -172,7 +172,7 @@ static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
 static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
 {
     // reduction area: one slot per wave (matrix-core path) or per (wave, 16-lane row) (VALU path)
-    b.cap_outs = t.mfma ? 1024 : 256;
+    b.cap_outs = t.mfma ? 1024 : 640;   // VALU: a workgroup's whole share of the LM head (about 600 rows at 256 workgroups) is one task
     b.red_bytes = (uint32_t)(kWaves * (t.mfma ? 1 : 4) * b.cap_outs * 4);
     const int64_t fixed = kLdsRed + b.red_bytes;
     // pages are the 1 KB chunk slots of the ring; a pipeline stage is 16 of them
