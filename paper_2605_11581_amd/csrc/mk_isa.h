@@ -22,6 +22,7 @@ constexpr int kChunkBytes = 1024;      // one wavefront-wide 128-bit load: 16 ro
 constexpr int kInstrDwords = 32;
 constexpr uint32_t kNone = 0xffffffffu;
 constexpr int kMaxBatch = 8;
+constexpr int kActTerms = 2;           // bf16 terms (hi + lo) of an fp32 activation on the matrix-core path
 constexpr int kMaxGroup = 8;           // q heads per kv head
 constexpr int kCounterStride = 32;     // default dwords between sub-counters (one 128-byte line each)
 constexpr int kCounterSubs = 16;       // default sub-counters per dependency counter

@@ -310,7 +310,10 @@ __device__ __forceinline__ void store_x4(char *xs, int b, int i, f32x4 y, int nt
     }
 }
 
-__device__ __forceinline__ int nterm_of(int batch) { return batch <= 5 ? 3 : 2; }
+// bf16 terms an fp32 activation is split into on the matrix-core path: hi + lo keeps 16 mantissa
+// bits (relative error 2^-17 per activation, far inside the tolerance), and up to 8 sequences x 2
+// terms fill the 16 columns of the instruction.  A third term measured 7 % slower at batch 4.
+__device__ __forceinline__ int nterm_of(int) { return kActTerms; }
 
 constexpr int kQuadsPerThread = 4;   // hidden <= 4 * 4 * 256
 
@@ -328,7 +331,7 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
     char *xs = lds + lp.xs_off;
     float *misc = (float *)(lds + kLdsMisc);
     const ActBuf ab = act_buf(P);
-    const int nterm = nterm_of(batch);
+    const int nterm = nterm_of(P.max_batch);
     const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
     constexpr uint32_t kNone = 0xfffffff0u;            // beyond the descriptor: the load returns zeros
 
@@ -508,7 +511,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
     char *xs = lds + lp.xs_off;
     float *misc = (float *)(lds + kLdsMisc);
     const ActBuf ab = act_buf(P);
-    const int nterm = nterm_of(batch);
+    const int nterm = nterm_of(P.max_batch);
     const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
 
     if constexpr (MFMA) {
@@ -899,7 +902,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     const int ksub = lane >> rlog;
     char *xs = lds + lp.xs_off;
     float *red = (float *)(lds + kLdsRed);
-    const int nterm = nterm_of(batch);
+    const int nterm = nterm_of(P.max_batch);
     const int ncols = MFMA ? batch * nterm : 1;
     const uint32_t S = I.S, nkb = I.nkb, kbt = I.kbt, nu = I.nu, u0 = I.u0;
     const uint32_t pro = instr_pro(I);

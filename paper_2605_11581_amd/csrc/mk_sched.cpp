@@ -160,7 +160,7 @@ static uint32_t att_scratch_bytes(const Dims &d)
 
 static uint32_t norm_stage_bytes(const Dims &d, const Tiling &t)
 {
-    int nterm = d.Bm <= 5 ? 3 : 2;
+    int nterm = kActTerms;
     if (t.mfma) return (uint32_t)(d.Bm * nterm) * ((uint32_t)d.H * 2u + 16u);
     return (uint32_t)d.H * 4u + (d.w4 ? (uint32_t)d.H / 32u * 4u + 16u : 0u);
 }
@@ -219,7 +219,7 @@ struct Builder {
 
     uint32_t stage_bytes(uint32_t k_elems) const
     {
-        int nterm = d.Bm <= 5 ? 3 : 2;
+        int nterm = kActTerms;
         if (t.mfma) return (uint32_t)(d.Bm * nterm) * (k_elems * 2u + 16u);
         return k_elems * 4u + (d.w4 ? k_elems / 32u * 4u + 16u : 0u);   // W4: sums of every 32 staged values follow the vector
     }
