@@ -292,6 +292,16 @@ __device__ __forceinline__ void argmax_wave(float &v, uint32_t &i)
 //   VALU path (batch 1): fp32 x[k]
 //   MFMA path: bf16 planes [col][k], col = b * nterm + term, x = sum of its nterm bf16 terms;
 //              plane stride = k_stage * 2 + 16 bytes (bank skew)
+// Two fp32 values to a packed pair of bf16 (round to nearest even) with the hardware conversion
+// (v_cvt_pk_bf16_f32).  Used for the activation split only: the KV rows are rounded by f_to_bf,
+// whose integer arithmetic is the same on every input as the oracle's.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+
 template <bool MFMA>
 __device__ __forceinline__ void store_x4(char *xs, int b, int i, f32x4 y, int nterm, uint32_t plane_stride)
 {
@@ -300,12 +310,11 @@ __device__ __forceinline__ void store_x4(char *xs, int b, int i, f32x4 y, int nt
     } else {
         f32x4 r = y;
         for (int t = 0; t < nterm; ++t) {
-            uint16_t h0 = f_to_bf(r.x), h1 = f_to_bf(r.y), h2 = f_to_bf(r.z), h3 = f_to_bf(r.w);
             uint2 pk;
-            pk.x = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            pk.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
+            pk.x = pack_bf16x2(r.x, r.y);
+            pk.y = pack_bf16x2(r.z, r.w);
             *(uint2 *)(xs + (size_t)(b * nterm + t) * plane_stride + (size_t)i * 2) = pk;
-            r.x -= bf_to_f(h0); r.y -= bf_to_f(h1); r.z -= bf_to_f(h2); r.w -= bf_to_f(h3);
+            r.x -= bf_lo(pk.x); r.y -= bf_hi(pk.x); r.z -= bf_lo(pk.y); r.w -= bf_hi(pk.y);
         }
     }
 }
