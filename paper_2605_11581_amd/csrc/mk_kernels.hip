@@ -212,8 +212,12 @@ __device__ __forceinline__ bool wait_counter(const Params &P, const uint32_t *co
     bool ok = true;
     for (;;) {
         uint32_t v = lane < P.ctr_nsub ? __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-#pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);   // nsub <= 32
+        // sum over the first 32 lanes: DPP inside the 16-lane rows (integer adds), one cross-row step
+        v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);    // quad_perm [1,0,3,2]
+        v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);    // quad_perm [2,3,0,1]
+        v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);   // row_half_mirror
+        v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true);   // row_mirror
+        if (P.ctr_nsub > 16u) v += (uint32_t)__shfl_xor((int)v, 16, 64);                 // nsub <= 32
         v = rfl(v);
         if ((int32_t)(v - target) >= 0) break;
         if (++it > P.spin_limit) { ok = false; break; }
