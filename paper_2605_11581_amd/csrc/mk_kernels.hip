@@ -136,20 +136,6 @@ __device__ __forceinline__ void st_act(float *p, float v)
     __hip_atomic_store((gptr)(uintptr_t)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
 // Cross-lane sums inside a 16-lane row with DPP (no LDS crossbar traffic).  Every step pairs
 // lanes symmetrically, so all lanes of the group end with bit-identical sums.
 template <int CTRL>
@@ -183,6 +169,24 @@ __device__ __forceinline__ float row_max16(float v)   // over a 16-lane row (all
     v = dpp_max<0x141>(v);
     v = dpp_max<0x140>(v);
     return v;
+}
+
+// Whole-wavefront reductions without LDS-crossbar shuffles (all 64 lanes active): the 16-lane rows
+// first, then the row totals travel down the wave with the two row-broadcast DPP steps (lane 15 of
+// a row into the next row, lane 31 into the upper half); the last lane's value goes to every lane.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = row_sum16(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xa, 0xf, false));   // row_bcast:15
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xc, 0xf, false));   // row_bcast:31
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = row_max16(v);
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x142, 0xa, 0xf, false)));
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x143, 0xc, 0xf, false)));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
