@@ -1377,7 +1377,8 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         const int which = tid / (D / 2), j = tid % (D / 2);
         const size_t base = ((((size_t)I.layer * 2 + which) * P.max_batch + b) * P.n_kv_heads + g) *
                                 (size_t)P.max_context * D + (size_t)p * D;
-        const uint32_t pk = (uint32_t)f_to_bf(snew[which * D + 2 * j]) | ((uint32_t)f_to_bf(snew[which * D + 2 * j + 1]) << 16);
+        // (the staged values are already rounded to bf16: their upper halves are the codes)
+        const uint32_t pk = (__float_as_uint(snew[which * D + 2 * j]) >> 16) | (__float_as_uint(snew[which * D + 2 * j + 1]) & 0xffff0000u);
         __hip_atomic_store((gptr)(uintptr_t)(P.kv + base + 2 * j), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
@@ -1455,14 +1456,10 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     u32x4 knew = {0u, 0u, 0u, 0u}, vnew = {0u, 0u, 0u, 0u};
     if (owner) {
         const float *kn = snew + dl * 8, *vn = snew + D + dl * 8;
-        knew.x = (uint32_t)f_to_bf(kn[0]) | ((uint32_t)f_to_bf(kn[1]) << 16);
-        knew.y = (uint32_t)f_to_bf(kn[2]) | ((uint32_t)f_to_bf(kn[3]) << 16);
-        knew.z = (uint32_t)f_to_bf(kn[4]) | ((uint32_t)f_to_bf(kn[5]) << 16);
-        knew.w = (uint32_t)f_to_bf(kn[6]) | ((uint32_t)f_to_bf(kn[7]) << 16);
-        vnew.x = (uint32_t)f_to_bf(vn[0]) | ((uint32_t)f_to_bf(vn[1]) << 16);
-        vnew.y = (uint32_t)f_to_bf(vn[2]) | ((uint32_t)f_to_bf(vn[3]) << 16);
-        vnew.z = (uint32_t)f_to_bf(vn[4]) | ((uint32_t)f_to_bf(vn[5]) << 16);
-        vnew.w = (uint32_t)f_to_bf(vn[6]) | ((uint32_t)f_to_bf(vn[7]) << 16);
+        auto pair = [](float lo, float hi) { return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u); };
+        const f32x4 k0 = *(const f32x4 *)kn, k1 = *(const f32x4 *)(kn + 4), v0 = *(const f32x4 *)vn, v1 = *(const f32x4 *)(vn + 4);
+        knew = u32x4{pair(k0.x, k0.y), pair(k0.z, k0.w), pair(k1.x, k1.y), pair(k1.z, k1.w)};
+        vnew = u32x4{pair(v0.x, v0.y), pair(v0.z, v0.w), pair(v1.x, v1.y), pair(v1.z, v1.w)};
     }
 
     for (int base = 0; base * PPW < npos; base += kAttPrefetch * kWaves) {
