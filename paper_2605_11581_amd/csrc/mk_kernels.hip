@@ -1465,19 +1465,20 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     for (int base = 0; base * PPW < npos; base += kAttPrefetch * kWaves) {
 #pragma unroll
         for (int j0 = 0; j0 < kAttPrefetch; j0 += 3) {
-            bool ok[3];
-            u32x4 kk[3], vv[3];
+            if ((base + wave + j0 * kWaves) * PPW < npos) {   // (wave-uniform) this batch has at least one group
+                bool ok[3];
+                u32x4 kk[3], vv[3];
 #pragma unroll
-            for (int u = 0; u < 3; ++u) {
-                const int grp = (base + wave + (j0 + u) * kWaves) * PPW;
-                const int t = att_pos(grp + sub, bs, nc, c);
-                ok[u] = grp < npos && t <= p;
-                const bool fresh = t == p;        // only ever true in the owner task
-                kk[u] = fresh ? knew : as.kbuf[j0 + u];
-                vv[u] = fresh ? vnew : as.vbuf[j0 + u];
-            }
-            if ((base + wave + j0 * kWaves) * PPW < npos)
+                for (int u = 0; u < 3; ++u) {
+                    const int grp = (base + wave + (j0 + u) * kWaves) * PPW;
+                    const int t = att_pos(grp + sub, bs, nc, c);
+                    ok[u] = grp < npos && t <= p;
+                    const bool fresh = t == p;        // only ever true in the owner task
+                    kk[u] = fresh ? knew : as.kbuf[j0 + u];
+                    vv[u] = fresh ? vnew : as.vbuf[j0 + u];
+                }
                 batchN(std::integral_constant<int, 3>{}, kk[0], vv[0], ok[0], kk[1], vv[1], ok[1], kk[2], vv[2], ok[2]);
+            }
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int ngrp = (base + wave + (j0 + u) * kWaves) * PPW + kAttPrefetch * kWaves * PPW;
