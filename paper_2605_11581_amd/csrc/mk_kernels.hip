@@ -738,9 +738,12 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         float *xsum = (float *)(xs + (size_t)ks * 4);
         for (uint32_t blk = tid; blk < ks / 32u; blk += kWgThreads) {
             const f32x4 *xp = (const f32x4 *)(xs + (size_t)blk * 128);
-            f32x4 acc = xp[0];
+            f32x4 xv[8];                                   // the eight reads in flight, then the sum in order
 #pragma unroll
-            for (int i = 1; i < 8; ++i) acc += xp[i];
+            for (int i = 0; i < 8; ++i) xv[i] = xp[i];
+            f32x4 acc = xv[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) acc += xv[i];
             xsum[blk] = (acc.x + acc.y) + (acc.z + acc.w);
         }
         wg_sync(lp, lds);
@@ -988,16 +991,20 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             const float *xsum = (const float *)(xs + (size_t)k_stage * 4);
             const uint32_t dw[4] = {w.x, w.y, w.z, w.w};
             float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+            f32x4 xv[8];                                   // all eight LDS reads in flight before the arithmetic
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[i] = xp[i];
+            const float zsum = xsum[k0 >> 5];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t lo = dw[i] & 0x0f0f0f0fu, hi = (dw[i] >> 4) & 0x0f0f0f0fu;
-                const f32x4 xa = xp[2 * i], xb = xp[2 * i + 1];
+                const f32x4 xa = xv[2 * i], xb = xv[2 * i + 1];
                 p0 += ubyte_f<0>(lo) * xa.x; p1 += ubyte_f<0>(hi) * xa.y;
                 p2 += ubyte_f<1>(lo) * xa.z; p3 += ubyte_f<1>(hi) * xa.w;
                 p0 += ubyte_f<2>(lo) * xb.x; p1 += ubyte_f<2>(hi) * xb.y;
                 p2 += ubyte_f<3>(lo) * xb.z; p3 += ubyte_f<3>(hi) * xb.w;
             }
-            a0 += bf_to_f((uint16_t)sbits) * (((p0 + p1) + (p2 + p3)) - 8.0f * xsum[k0 >> 5]);
+            a0 += bf_to_f((uint16_t)sbits) * (((p0 + p1) + (p2 + p3)) - 8.0f * zsum);
         } else if (!MFMA) {
             const f32x4 *xp = (const f32x4 *)(xs + ((size_t)kb_rel * ck + ksub * 8) * 4);
             f32x4 x0 = xp[0], x1 = xp[1];
