@@ -5,9 +5,9 @@ Every task records four device wall-clock stamps (begin, dependencies met, prolo
 last one back through the C ABI and prints, for one layer and for the whole step, how long each
 dependency level (operator instance) takes and what the time is spent on: the gap between the
 last producer's signal and the consumers' start, prologues, task bodies, and the spread between
-the median and the slowest task.  It is the measurement behind the "where the time goes" section
-of the design notes and the feedback signal for the profile-guided tiling search (paper Sec.
-4.2.2 Step 4: offline profiling of candidate traces).
+the median and the slowest task.  It shows where the time of a step goes beyond its memory
+traffic, and is the feedback signal for the profile-guided tiling search (paper Sec. 4.2.2 Step 4:
+offline profiling of candidate traces).
 
     python -m paper_2605_11581_amd.trace_report --config c2_1p5b [--layer 13] [--w4] [--batch B] [--opt k=v ...]
 """
