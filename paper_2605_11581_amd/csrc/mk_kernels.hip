@@ -1306,7 +1306,8 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     const int b = (int)I.b, g = (int)I.g;
     if (b >= P.batch) return;
-    const int G = P.n_q_heads / P.n_kv_heads;
+    // The task covers heads [hb, hb + G) of the GG query heads that share KV head g.
+    const int GG = P.n_q_heads / P.n_kv_heads, hb = (int)I.h0, G = (int)I.nh;
     const int p = as.p;
     const int qd = P.n_q_heads * D, kvd = P.n_kv_heads * D;
     const float *act = (const float *)(P.ws + P.lay.act);
@@ -1333,7 +1334,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         const int vi = wave + r * kWaves;
         pa[r] = 0.f; pb[r] = 0.f;
         if (vi < nvec && i < D / 2) {
-            const int row0 = vi < G ? (g * G + vi) * D : (vi == G ? qd + g * D : qd + kvd + g * D);
+            const int row0 = vi < G ? (g * GG + hb + vi) * D : (vi == G ? qd + g * D : qd + kvd + g * D);
             for (uint32_t s = 0; s < I.n_parts; ++s) {
                 const float *pp = act + I.in_parts + (size_t)s * I.part_stride + (size_t)b * I.in_ld + row0;
                 float u0 = ld_act(pp + i), u1 = ld_act(pp + i + D / 2);
@@ -1379,7 +1380,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     wg_sync(lp, lds);
     trace_mark(P, pc, 0);
     // append the new K and V rows (bf16 pairs, write-through: the next step of the same launch reads them)
-    if (owner && tid < D) {
+    if (owner && hb == 0 && tid < D) {   // (of the tasks that share this chunk, the one with the group's first heads appends)
         typedef __attribute__((address_space(1))) uint32_t *gptr;
         const int which = tid / (D / 2), j = tid % (D / 2);
         const size_t base = ((((size_t)I.layer * 2 + which) * P.max_batch + b) * P.n_kv_heads + g) *
@@ -1550,7 +1551,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 #pragma unroll
         for (int w = 0; w < NSLOT; ++w) A += sv[w] * fv[w];
         // partial layout [b][head][nc][D + kPartStride]
-        const uint32_t dst = I.out + (uint32_t)((((size_t)b * P.n_q_heads + (g * G + h)) * I.nc + I.c) * (D + kPartStride));
+        const uint32_t dst = I.out + (uint32_t)((((size_t)b * P.n_q_heads + (g * GG + hb + h)) * I.nc + I.c) * (D + kPartStride));
         st_act4(ab, dst + (uint32_t)i, A);
         if (i == 0) {
             float *ml = (float *)(P.ws + P.lay.act) + dst + D;

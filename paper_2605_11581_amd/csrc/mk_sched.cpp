@@ -17,6 +17,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <numeric>
@@ -152,6 +153,17 @@ struct LdsBudget {
     uint32_t red_bytes;
     uint32_t xs_cap;      // bytes left for the staged input vector
 };
+
+// Attention tasks split over the query heads of a group as well as over positions when that still
+// leaves at most one task per workgroup: the score / value arithmetic of a task is proportional to
+// its heads, the K/V rows are read once more (they are small next to the weights).
+static int att_head_splits(const Dims &d, const Tiling &t, int n_wg)
+{
+    const char *e = getenv("MK_DBG_HEAD_SPLIT");   // development: 1 = never split
+    if (e && *e == '1') return 1;
+    if (t.fuse || d.G < 2) return 1;
+    return 2 * (int64_t)d.Bm * d.nkv * t.nc <= n_wg ? 2 : 1;
+}
 
 static uint32_t att_scratch_bytes(const Dims &d)
 {
@@ -352,10 +364,15 @@ struct Builder {
             {
                 std::vector<int> order = by_load();
                 int oi = 0;
+                const int hs = att_head_splits(d, t, n_wg);
                 for (int b = 0; b < d.Bm; ++b)
                     for (int gh = 0; gh < d.nkv; ++gh)
-                        for (int c = 0; c < t.nc; ++c) {
+                        for (int c = 0; c < t.nc; ++c)
+                        for (int hp = 0; hp < hs; ++hp) {
                             InstrAtt a{};
+                            // heads [h0, h0 + nh) of the group: the first part takes the extra head of an odd group
+                            const int h_lo = hp == 0 ? 0 : (d.G + 1) / 2, h_n = hs == 1 ? d.G : hp == 0 ? (d.G + 1) / 2 : d.G / 2;
+                            a.h0 = (uint32_t)h_lo; a.nh = (uint32_t)h_n;
                             a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l;
                             a.wait_ctr[0] = c_qkv; a.wait_cnt[0] = ctr_signals[c_qkv]; a.wait_ctr[1] = kNone;
                             a.sig_ctr = c_att[b * d.nkv + gh]; ++ctr_signals[a.sig_ctr];
@@ -801,11 +818,11 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
         const InstrAtt &A = *(const InstrAtt *)&I;
         for (uint32_t p = 0; p < A.n_parts; ++p) {
             uint64_t base = A.in_parts + (uint64_t)p * A.part_stride + (uint64_t)A.b * A.in_ld;
-            rd(base + (uint64_t)A.g * d.G * d.d, (uint64_t)d.G * d.d);
+            rd(base + ((uint64_t)A.g * d.G + A.h0) * d.d, (uint64_t)A.nh * d.d);
             rd(base + d.qd + (uint64_t)A.g * d.d, d.d);
             rd(base + d.qd + d.kvd + (uint64_t)A.g * d.d, d.d);
         }
-        for (int h = 0; h < d.G; ++h)
+        for (uint32_t h = A.h0; h < A.h0 + A.nh; ++h)
             wr(A.out + (((uint64_t)A.b * d.nq + A.g * d.G + h) * A.nc + A.c) * (d.d + kPartPad), d.d + 2);
     } else if (I.op == OP_COMB) {
         const InstrAtt &A = *(const InstrAtt *)&I;
@@ -866,6 +883,7 @@ int verify_schedule(const mk_schedule *s)
     {
         std::map<uint32_t, std::vector<std::pair<uint32_t, uint32_t>>> units;   // ref_seq -> [u0, u1)
         std::map<uint32_t, std::vector<uint32_t>> keys;
+        std::map<uint32_t, uint64_t> att_heads;   // heads covered by the attention tasks of an operator instance
         std::vector<uint32_t> slots, argmax_slots;
         for (int w = 0; w < n_wg; ++w)
             for (int i = 0; i < cnt[w]; ++i) {
@@ -876,7 +894,9 @@ int verify_schedule(const mk_schedule *s)
                     if (I.flags & F_ARGMAX) slots.push_back(I.spare);
                 } else {
                     const InstrAtt &A = *(const InstrAtt *)&I;
-                    keys[I.ref_seq].push_back(I.op == OP_ATT ? (A.b * d.nkv + A.g) * A.nc + A.c : I.op == OP_COMB ? A.b * d.nq + A.h0 : A.b);
+                    if (I.op == OP_ATT && (A.nh == 0 || A.h0 + A.nh > (uint32_t)d.G)) return fail("attention task with an empty or out-of-group head range");
+                    keys[I.ref_seq].push_back(I.op == OP_ATT ? ((A.b * d.nkv + A.g) * A.nc + A.c) * d.G + A.h0 : I.op == OP_COMB ? A.b * d.nq + A.h0 : A.b);
+                    if (I.op == OP_ATT) att_heads[I.ref_seq] += A.nh;
                     if (I.op == OP_ARGMAX) argmax_slots.push_back(A.n_slots);
                 }
             }
@@ -909,7 +929,16 @@ int verify_schedule(const mk_schedule *s)
                 if (at != e.total) { snprintf(buf, sizeof buf, "operator %u of layer %d covers %u of %u units", e.st, l, at, e.total); return fail(buf); }
             }
             if (l < d.L) {
-                struct { uint32_t st; uint32_t total; } k2[] = {{ST_ATT, (uint32_t)(d.Bm * d.nkv * s->tl.nc)}, {ST_COMB, (uint32_t)(s->tl.fuse ? 0 : d.Bm * d.nq)}};
+                // attention: the head ranges of the tasks of every (sequence, kv head, chunk) tile the group
+                // exactly (distinct first heads, d.G heads in all: the write-overlap check below rules out overlaps)
+                {
+                    auto &v = keys[l * 8 + ST_ATT];
+                    std::sort(v.begin(), v.end());
+                    if (std::adjacent_find(v.begin(), v.end()) != v.end()) return fail("attention task missing or duplicated");
+                    const uint64_t want = (uint64_t)d.Bm * d.nkv * s->tl.nc * d.G;
+                    if (att_heads[l * 8 + ST_ATT] != want) { snprintf(buf, sizeof buf, "attention of layer %d covers %llu of %llu (chunk, head) pairs", l, (unsigned long long)att_heads[l * 8 + ST_ATT], (unsigned long long)want); return fail(buf); }
+                }
+                struct { uint32_t st; uint32_t total; } k2[] = {{ST_COMB, (uint32_t)(s->tl.fuse ? 0 : d.Bm * d.nq)}};
                 for (auto &e : k2) {
                     auto &v = keys[l * 8 + e.st];
                     std::sort(v.begin(), v.end());
@@ -1074,7 +1103,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 5;
+constexpr uint32_t kVersion = 6;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)
