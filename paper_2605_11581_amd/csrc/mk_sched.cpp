@@ -162,7 +162,10 @@ static int att_head_splits(const Dims &d, const Tiling &t, int n_wg)
     const char *e = getenv("MK_DBG_HEAD_SPLIT");   // development: 1 = never split
     if (e && *e == '1') return 1;
     if (t.fuse || d.G < 2) return 1;
-    return 2 * (int64_t)d.Bm * d.nkv * t.nc <= n_wg ? 2 : 1;
+    const int64_t base = (int64_t)d.Bm * d.nkv * t.nc;   // tasks without a head split
+    const char *m = getenv("MK_DBG_HEAD_SPLIT_MAX");      // development: upper bound of the split
+    const int cap = m && *m ? std::max(1, atoi(m)) : d.G;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(cap, d.G), n_wg / base));
 }
 
 static uint32_t att_scratch_bytes(const Dims &d)
@@ -370,8 +373,9 @@ struct Builder {
                         for (int c = 0; c < t.nc; ++c)
                         for (int hp = 0; hp < hs; ++hp) {
                             InstrAtt a{};
-                            // heads [h0, h0 + nh) of the group: the first part takes the extra head of an odd group
-                            const int h_lo = hp == 0 ? 0 : (d.G + 1) / 2, h_n = hs == 1 ? d.G : hp == 0 ? (d.G + 1) / 2 : d.G / 2;
+                            // heads [h0, h0 + nh) of the group: G / hs each, the first G % hs parts one more
+                            const int h_base = d.G / hs, h_rem = d.G % hs;
+                            const int h_lo = hp * h_base + std::min(hp, h_rem), h_n = h_base + (hp < h_rem ? 1 : 0);
                             a.h0 = (uint32_t)h_lo; a.nh = (uint32_t)h_n;
                             a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l;
                             a.wait_ctr[0] = c_qkv; a.wait_cnt[0] = ctr_signals[c_qkv]; a.wait_ctr[1] = kNone;
