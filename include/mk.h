@@ -131,8 +131,8 @@ int mk_build_schedule(const mk_config *cfg, mk_schedule **out);
  * waits/signals.  Returns MK_OK or MK_ESCHED (text in mk_last_error). */
 int mk_schedule_verify(const mk_schedule *s);
 
-/* Serialise / restore a schedule ("the trace is serialised for runtime
- * invocation", Sec. 3).  dump: if buf is NULL only *bytes is written. */
+/* Serialise / restore a schedule (the hand-over from offline synthesis to
+ * online execution, Sec. 3).  dump: if buf is NULL only *bytes is written. */
 int mk_schedule_dump(const mk_schedule *s, void *host_buf, size_t *bytes);
 int mk_schedule_load(const void *host_buf, size_t bytes, mk_schedule **out);
 
@@ -157,7 +157,7 @@ size_t mk_workspace_bytes(const mk_schedule *s);
 /* Hand the library its workspace (dev pointer, 256-byte aligned, caller-owned,
  * must outlive the handle's use).  Uploads the instruction lists and the RoPE
  * table and zeroes the counters on `stream`.  Checks that the bound device
- * can keep n_workgroups workgroups co-resident. */
+ * can keep n_workgroups workgroups co-resident for every kernel the handle may launch. */
 int mk_bind_workspace(mk_schedule *s, void *dev_workspace, size_t bytes, void *stream);
 
 /* Offline weight reorder (cf. Sec. 4.3.2 "weight reorder"): copy every matrix

@@ -36,9 +36,9 @@ int hip_fail(hipError_t e, const char *what)
 // The kernel that walks the lists of a schedule: one per GEMV family and step count, plus the ring
 // form (any step count, bf16 only).
 typedef void (*walk_fn)(const mk::Params, const mk::LdsPlan);
-walk_fn walk_kernel(const mk_schedule *s, int n_steps, uint32_t dbg)
+walk_fn walk_kernel(const mk_schedule *s, int n_steps)
 {
-    if (s->tl.ring_pages && !(dbg & 4u)) return mk_megakernel_ring;
+    if (s->tl.ring_pages) return mk_megakernel_ring;
     const bool multi = n_steps > 1;
     if (s->dm.w4) return multi ? mk_megakernel_steps_w4 : mk_megakernel_w4;
     if (s->tl.mfma) return multi ? mk_megakernel_steps_mfma : mk_megakernel_mfma;
@@ -71,9 +71,9 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
                        float *logits, int batch, int32_t *next_tokens = nullptr, int n_steps = 1)
 {
     mk::Params P{};
-    P.ws = s->ws; P.lay = s->lay;
+    P.ws = s->ws; P.scr = s->ws; P.lay = s->lay;
     P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
-    P.next_tokens = next_tokens ? next_tokens : (int32_t *)(s->ws + s->lay.tokens);
+    P.next_tokens = next_tokens ? next_tokens : (int32_t *)(P.scr + P.lay.tokens);
     P.n_steps = n_steps; P.amax = s->am.amax; P.want_tokens = next_tokens != nullptr;
     P.batch = batch; P.max_batch = s->dm.Bm; P.max_context = s->dm.Tm;
     P.n_layers = s->dm.L; P.hidden = s->dm.H; P.n_q_heads = s->dm.nq; P.n_kv_heads = s->dm.nkv;
@@ -84,13 +84,6 @@ mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_
     P.embed_chunk = s->wm.embed; P.embed_kbt = (uint32_t)s->gm.head.kbt; P.embed_rlog = (uint32_t)s->gm.head.rlog;
     P.only_seq = mk::kNone; P.act_bytes = (uint32_t)(s->am.n_floats * 4);
     P.w4_group = s->dm.w4 ? (uint32_t)s->dm.group : 0u;
-    P.ctr_stride = dbg_knob("MK_DBG_CTR_STRIDE", mk::kCounterStride, 1, mk::kCounterStrideMax);
-    uint32_t nsub = dbg_knob("MK_DBG_CTR_NSUB", mk::kCounterSubs, 1, 32);
-    while (nsub & (nsub - 1u)) nsub &= nsub - 1u;                                     // a power of two
-    while (nsub > 1u && nsub * P.ctr_stride > (uint32_t)mk::kCounterStrideMax) nsub >>= 1;   // inside the counter's share of the region
-    P.ctr_nsub = nsub;
-    P.poll_sleep = dbg_knob("MK_DBG_POLL_SLEEP", 0, 0, 64);
-    P.dbg = dbg_knob("MK_DBG_UNSAFE_TIMING", 0, 0, 7);
     return P;
 }
 
@@ -114,7 +107,7 @@ int fill_u32(void *dst, uint32_t v, size_t n, hipStream_t st)
 
 int reset_sync_state(mk_schedule *s, hipStream_t st)
 {
-    int rc = fill_u32(s->ws + s->lay.counters, 0u, (size_t)s->n_counters * mk::kCounterStrideMax, st);
+    int rc = fill_u32(s->ws + s->lay.counters, 0u, (size_t)s->n_counters * mk::kCounterDwords, st);
     if (rc) return rc;
     rc = fill_u32(s->ws + s->lay.err, 0u, 16, st);
     s->epoch = 0;
@@ -233,13 +226,17 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
     if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0) { mk::set_error(std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950"); return MK_EHIP; }
     for (const void *k : all_walk_kernels())
         HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s->lds_total));
-    int per_cu = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)walk_kernel(s, 1, 0), mk::kWgThreads, s->lds_total));
-    if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
-        char buf[200];
-        snprintf(buf, sizeof buf, "the device keeps only %d x %d workgroups resident, the schedule needs %d", per_cu, prop.multiProcessorCount, s->n_wg);
-        mk::set_error(buf);
-        return MK_EINFEASIBLE;
+    // every kernel this handle can launch spins on dependency counters (or is launched with the same grid):
+    // all of its workgroups must be resident at once
+    for (const void *k : {(const void *)walk_kernel(s, 1), (const void *)walk_kernel(s, 2), (const void *)op_kernel(s)}) {
+        int per_cu = 0;
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, mk::kWgThreads, s->lds_total));
+        if ((int64_t)per_cu * prop.multiProcessorCount < s->n_wg) {
+            char buf[200];
+            snprintf(buf, sizeof buf, "the device keeps only %d x %d workgroups resident, the schedule needs %d", per_cu, prop.multiProcessorCount, s->n_wg);
+            mk::set_error(buf);
+            return MK_EINFEASIBLE;
+        }
     }
     s->ws = (char *)dev; s->ws_bytes = bytes;
     // instruction lists
@@ -395,7 +392,7 @@ static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *po
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
-    hipLaunchKernelGGL(walk_kernel(s, n_steps, P.dbg), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    hipLaunchKernelGGL(walk_kernel(s, n_steps), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
     return MK_OK;

@@ -24,9 +24,10 @@ constexpr uint32_t kNone = 0xffffffffu;
 constexpr int kMaxBatch = 8;
 constexpr int kActTerms = 2;           // bf16 terms (hi + lo) of an fp32 activation on the matrix-core path
 constexpr int kMaxGroup = 8;           // q heads per kv head
-constexpr int kCounterStride = 32;     // default dwords between sub-counters (one 128-byte line each)
-constexpr int kCounterSubs = 16;       // default sub-counters per dependency counter
-constexpr int kCounterStrideMax = 1088; // the counter region holds this many dwords per dependency counter
+constexpr int kCounterStride = 32;     // dwords between sub-counters (one 128-byte line each)
+constexpr int kCounterSubs = 16;       // sub-counters per dependency counter (a power of two, at most 16: one poll reads them
+                                       // with the first 16 lanes); measured best of 1..64 on MI355X
+constexpr int kCounterDwords = kCounterStride * kCounterSubs;   // dwords of the counter region per dependency counter
 constexpr int kPrefetch = 6;           // 128-bit bf16 weight loads a lane keeps in flight (direct-load path): 24 KB per
                                        // workgroup; measured best of 4..32 on every shape (deeper bursts delay the
                                        // dependency polls and activation loads queued behind them)
@@ -160,7 +161,9 @@ struct Layout {
 };
 
 struct Params {
-    char *ws;
+    char *ws;             // the bound workspace: weights, vectors, RoPE table, instruction lists, trace, stream table
+    char *scr;            // base of the scratch regions (lay.act, lay.counters, lay.err, lay.tokens are offsets from it):
+                          // the workspace itself, or the library's static device array (allocation-free entry point)
     Layout lay;
     const int32_t *tokens;
     const int32_t *positions;
@@ -183,11 +186,6 @@ struct Params {
     uint32_t only_seq;    // per-operator launches: run only instructions with this ref_seq (kNone: all)
     uint32_t act_bytes;   // size of the activation region (buffer-descriptor bound)
     uint32_t w4_group;    // W4: group size along K (32, 64 or 128); 0: bf16 weights
-    uint32_t ctr_stride;  // dwords between dependency (sub-)counters
-    uint32_t ctr_nsub;    // sub-counters per dependency counter (power of two, 1..32; ctr_nsub * ctr_stride <= kCounterStrideMax)
-    uint32_t poll_sleep;  // s_sleep units between two polls of a dependency counter
-    uint32_t dbg;         // development only: bit 0 skip dependency waits, bit 1 skip the store drain (both: results invalid,
-                          // timing experiments), bit 2 run a ring schedule with the direct-load kernel
 };
 
 }  // namespace mk

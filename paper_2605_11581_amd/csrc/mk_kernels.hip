@@ -191,17 +191,18 @@ __device__ __forceinline__ float wave_max(float v)
 
 __device__ __forceinline__ void set_err(const Params &P, int slot, uint32_t v)
 {
-    uint32_t *e = (uint32_t *)(P.ws + P.lay.err);
+    uint32_t *e = (uint32_t *)(P.scr + P.lay.err);
     __hip_atomic_store(e + slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A dependency counter is kept as `nsub` sub-counters on separate 128-byte lines: a producer adds to
+// A dependency counter is kept as kCounterSubs sub-counters on separate 128-byte lines: a producer adds to
 // the one picked by its workgroup id, so the read-modify-writes of a level with hundreds of producers
-// spread over `nsub` lines instead of queueing on one.  The count is the sum of the sub-counters
+// spread over that many lines instead of queueing on one.  The count is the sum of the sub-counters
 // (each only grows, so a sum of reads taken at different times can only under-count).
 __device__ __forceinline__ const uint32_t *sub_counter(const Params &P, const uint32_t *counters, uint32_t idx, uint32_t j)
 {
-    return counters + ((size_t)idx * P.ctr_nsub + j) * P.ctr_stride;
+    (void)P;
+    return counters + ((size_t)idx * kCounterSubs + j) * kCounterStride;
 }
 
 // Wave-wide poll of a dependency counter until it has received `target` signals (wrap-safe); lane j
@@ -211,21 +212,19 @@ __device__ __forceinline__ bool wait_counter(const Params &P, const uint32_t *co
                                              uint32_t *polls = nullptr)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t *mine = sub_counter(P, counters, idx, lane & (P.ctr_nsub - 1u));
+    const uint32_t *mine = sub_counter(P, counters, idx, lane & (kCounterSubs - 1u));
     uint32_t it = 0;
     bool ok = true;
     for (;;) {
-        uint32_t v = lane < P.ctr_nsub ? __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        uint32_t v = lane < (uint32_t)kCounterSubs ? __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
         // sum over the first 32 lanes: DPP inside the 16-lane rows (integer adds), one cross-row step
         v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);    // quad_perm [1,0,3,2]
         v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);    // quad_perm [2,3,0,1]
         v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);   // row_half_mirror
         v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true);   // row_mirror
-        if (P.ctr_nsub > 16u) v += (uint32_t)__shfl_xor((int)v, 16, 64);                 // nsub <= 32
         v = rfl(v);
         if ((int32_t)(v - target) >= 0) break;
         if (++it > P.spin_limit) { ok = false; break; }
-        for (uint32_t z = 0; z < P.poll_sleep; ++z) __builtin_amdgcn_s_sleep(2);
     }
     if (polls) *polls += it + 1;
     return ok;
@@ -267,7 +266,7 @@ struct ActBuf {
 __device__ __forceinline__ ActBuf act_buf(const Params &P)
 {
     ActBuf a;
-    a.r = __builtin_amdgcn_make_buffer_rsrc((void *)(P.ws + P.lay.act), 0, (int)P.act_bytes, 0x00020000);
+    a.r = __builtin_amdgcn_make_buffer_rsrc((void *)(P.scr + P.lay.act), 0, (int)P.act_bytes, 0x00020000);
     return a;
 }
 constexpr int kAuxSc1 = 16;
@@ -1029,7 +1028,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     float resid0 = 0.f;
     if (!MFMA && (I.flags & F_ADD_RESID) && (uint32_t)tid < red_per_wave) {
         const uint32_t ub = (uint32_t)tid >> rlog, uu = u0 + ub;
-        resid0 = ld_act((const float *)(P.ws + P.lay.act) + I.resid + (size_t)(uu / S) * R + ((uint32_t)tid & (R - 1)));
+        resid0 = ld_act((const float *)(P.scr + P.lay.act) + I.resid + (size_t)(uu / S) * R + ((uint32_t)tid & (R - 1)));
     }
     // Likewise the bias of this thread's first output (a constant).
     float bias0 = 0.f;
@@ -1145,7 +1144,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
 
     // cross-wave sum in fixed wave order, then the epilogue
     const ActBuf ab = act_buf(P);
-    float *actw = (float *)(P.ws + P.lay.act);
+    float *actw = (float *)(P.scr + P.lay.act);
     const uint32_t nb = (uint32_t)(MFMA ? batch : 1);
     auto rsum = [&](uint32_t t) {
         constexpr int kSlots = MFMA ? kWaves : kWaves * 4;   // VALU path: one slot per (wave, 16-lane row)
@@ -1310,7 +1309,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     const int GG = P.n_q_heads / P.n_kv_heads, hb = (int)I.h0, G = (int)I.nh;
     const int p = as.p;
     const int qd = P.n_q_heads * D, kvd = P.n_kv_heads * D;
-    const float *act = (const float *)(P.ws + P.lay.act);
+    const float *act = (const float *)(P.scr + P.lay.act);
     const uint16_t *vecs = (const uint16_t *)(P.ws + P.lay.vecs);
     const float *rope = (const float *)(P.ws + P.lay.rope) + (size_t)p * D;  // [D/2][2]
 
@@ -1554,7 +1553,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         const uint32_t dst = I.out + (uint32_t)((((size_t)b * P.n_q_heads + (g * GG + hb + h)) * I.nc + I.c) * (D + kPartStride));
         st_act4(ab, dst + (uint32_t)i, A);
         if (i == 0) {
-            float *ml = (float *)(P.ws + P.lay.act) + dst + D;
+            float *ml = (float *)(P.scr + P.lay.act) + dst + D;
             st_act(ml, sfac[G * NSLOT + h]);
             st_act(ml + 1, sfac[G * NSLOT + G + h]);
         }
@@ -1571,7 +1570,7 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
     const int D = P.head_dim, nc = (int)I.nc, RS = D + kPartStride;
     const ActBuf ab = act_buf(P);
     float *stage = (float *)(lds + lp.xs_off);
-    float *o = (float *)(P.ws + P.lay.act) + I.o_out + (size_t)b * I.o_ld;
+    float *o = (float *)(P.scr + P.lay.act) + I.o_out + (size_t)b * I.o_ld;
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
     constexpr int U = 9;   // 128-bit loads in flight per lane: one round trip for 64 partial rows of a 128-wide head
     for (int hh = 0; hh < (int)I.nh; ++hh) {
@@ -1628,7 +1627,7 @@ __device__ __forceinline__ void argmax_task(const Params &P, const InstrAtt &I, 
 {
     const int b = (int)I.b, tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     if (b >= P.batch || !P.want_tokens) return;
-    const float *part = (const float *)(P.ws + P.lay.act) + I.out;
+    const float *part = (const float *)(P.scr + P.lay.act) + I.out;
     float bv = -INFINITY;
     uint32_t bi = 0xffffffffu;
     for (uint32_t s0 = tid; s0 < I.n_slots; s0 += kWgThreads * 4) {
@@ -1682,7 +1681,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     const int tid = threadIdx.x;
     lp.pc = pc;
     uint32_t *sflag = (uint32_t *)(lds + kLdsMisc + 128);
-    const uint32_t *counters = (const uint32_t *)(P.ws + P.lay.counters);
+    const uint32_t *counters = (const uint32_t *)(P.scr + P.lay.counters);
     uint64_t t0 = 0, t1 = 0;
     const bool tracing = PERSISTENT && (P.flags & 1u);
     if (tracing && tid == 0) t0 = wall_clock64();
@@ -1690,7 +1689,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     // Nothing to wait for: the first step of a launch follows the previous launch in stream order,
     // and an arg-max task whose result nobody takes only has to signal.
     const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens);
-    const bool waiting = PERSISTENT && !dead && !(P.dbg & 1u) && !no_dep;
+    const bool waiting = PERSISTENT && !dead && !no_dep;
     constexpr bool W4 = PATH == kPathW4;
     uint64_t t2 = 0;
 
@@ -1763,10 +1762,10 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     if (PERSISTENT && I.sig_ctr != kNone) {
         // each wave drains its write-through stores, the barrier collects all waves, then one
         // thread publishes the task with the counter increment
-        if (!(P.dbg & 2u)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_sync(lp, lds);
         if (tid == 0)
-            __hip_atomic_fetch_add((uint32_t *)sub_counter(P, counters, I.sig_ctr, blockIdx.x & (P.ctr_nsub - 1u)), 1u,
+            __hip_atomic_fetch_add((uint32_t *)sub_counter(P, counters, I.sig_ctr, blockIdx.x & (kCounterSubs - 1u)), 1u,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tracing && tid == 0) {

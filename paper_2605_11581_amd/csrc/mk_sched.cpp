@@ -159,13 +159,9 @@ struct LdsBudget {
 // its heads, the K/V rows are read once more (they are small next to the weights).
 static int att_head_splits(const Dims &d, const Tiling &t, int n_wg)
 {
-    const char *e = getenv("MK_DBG_HEAD_SPLIT");   // development: 1 = never split
-    if (e && *e == '1') return 1;
     if (t.fuse || d.G < 2) return 1;
     const int64_t base = (int64_t)d.Bm * d.nkv * t.nc;   // tasks without a head split
-    const char *m = getenv("MK_DBG_HEAD_SPLIT_MAX");      // development: upper bound of the split
-    const int cap = m && *m ? std::max(1, atoi(m)) : d.G;
-    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(cap, d.G), n_wg / base));
+    return (int)std::max<int64_t>(1, std::min<int64_t>(d.G, n_wg / base));
 }
 
 static uint32_t att_scratch_bytes(const Dims &d)
@@ -634,7 +630,7 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     L.vecs = off; off = align_up(off + s->wm.n_vec * 2, 4096);
     L.rope = off; off = align_up(off + (uint64_t)d.Tm * d.d * 4, 4096);
     L.act = off; off = align_up(off + s->am.n_floats * 4, 4096);
-    L.counters = off; off = align_up(off + (uint64_t)s->n_counters * kCounterStrideMax * 4, 4096);
+    L.counters = off; off = align_up(off + (uint64_t)s->n_counters * kCounterDwords * 4, 4096);
     L.instr = off; off = align_up(off + s->instr.size() * 4, 4096);
     L.err = off; off = align_up(off + 64, 4096);
     L.trace = off; off = align_up(off + ((cfg.flags & MK_F_TRACE) ? (uint64_t)s->n_wg * s->max_instr * 64 : 0), 4096);
@@ -881,6 +877,69 @@ int verify_schedule(const mk_schedule *s)
                         return fail(buf);
                     }
                 }
+        }
+
+    // (1b) the fields that address weights, vectors, the KV cache and the attention buffers are not covered
+    //      by the activation-footprint walk below: they must equal what the memory maps plan for the
+    //      task's (layer, stage), so that a corrupted list cannot reach outside its buffers.
+    for (int w = 0; w < n_wg; ++w)
+        for (int i = 0; i < cnt[w]; ++i) {
+            const Instr &I = all[(size_t)w * mi + i];
+            const uint32_t l = I.ref_seq / 8, st = I.ref_seq % 8;
+            auto bad = [&](const char *what) {
+                snprintf(buf, sizeof buf, "workgroup %d instruction %d (ref_seq %u): %s", w, i, I.ref_seq, what);
+                return fail(buf);
+            };
+            if (I.layer != l) return bad("layer field does not match the operator instance");
+            const bool tail = st == ST_HEAD || st == ST_ARGMAX;
+            if (tail ? l != (uint32_t)d.L : l >= (uint32_t)d.L) return bad("layer out of range");
+            if (I.op == OP_GEMV) {
+                const MatGeom *m = nullptr;
+                uint32_t chunk = 0, gain = kNone, bias = kNone;
+                int S = 1;
+                switch (st) {
+                case ST_QKV: m = &s->gm.qkv; chunk = s->wm.qkv[l]; S = s->tl.s_qkv; gain = s->wm.g_attn[l]; bias = s->wm.bias[l]; break;
+                case ST_O: m = &s->gm.o; chunk = s->wm.o[l]; S = s->tl.s_o; break;
+                case ST_GU: m = &s->gm.gu; chunk = s->wm.gu[l]; S = s->tl.s_gu; gain = s->wm.g_mlp[l]; break;
+                case ST_DOWN: m = &s->gm.down; chunk = s->wm.down[l]; S = s->tl.s_d; break;
+                case ST_HEAD: m = &s->gm.head; chunk = s->wm.head; S = 1; gain = s->wm.g_final; break;
+                default: return bad("a GEMV task at a stage that has none");
+                }
+                if (I.w_chunk != chunk) return bad("weight chunk offset differs from the planned matrix");
+                if (I.kbt != (uint32_t)m->kbt || I.S != (uint32_t)S || I.nkb != (uint32_t)ceil_div(m->kbt, S) ||
+                    instr_rlog(I) != (uint32_t)m->rlog || I.n_rows != (uint32_t)m->n_rows || I.k_len != (uint32_t)m->k_len ||
+                    ((I.flags & F_W4) != 0) != (m->w4 != 0) || ((I.flags & F_MFMA) != 0) != (s->tl.mfma != 0))
+                    return bad("matrix geometry differs from the planned matrix");
+                const uint32_t pro = instr_pro(I);
+                const bool normk = pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM;
+                if (normk != (gain != kNone)) return bad("prologue kind does not fit the operator");
+                if (normk && I.gain != gain) return bad("norm gain offset differs from the planned vector");
+                if (I.bias != bias) return bad("bias offset differs from the planned vector");
+                if ((uint64_t)I.u0 + I.nu > (uint64_t)m->groups * S) return bad("units beyond the matrix");
+            } else if (I.op == OP_ATT || I.op == OP_COMB) {
+                const InstrAtt &A = *(const InstrAtt *)&I;
+                if (st != (I.op == OP_ATT ? ST_ATT : ST_COMB)) return bad("attention task at the wrong stage");
+                if (A.b >= (uint32_t)d.Bm) return bad("sequence index beyond max_batch");
+                if (A.nc != (uint32_t)s->tl.nc) return bad("chunk count differs from the tiling");
+                if (A.out != s->am.attp) return bad("attention partial buffer offset differs from the plan");
+                if (I.op == OP_ATT) {
+                    if (A.g >= (uint32_t)d.nkv) return bad("kv head out of range");
+                    if (A.c >= A.nc) return bad("chunk index out of range");
+                    if (A.bs != (uint32_t)s->tl.bs || A.bs != 16u) return bad("block size differs from the tiling");
+                    if (A.in_parts != s->am.pqkv || A.n_parts != (uint32_t)s->tl.s_qkv || A.in_ld != (uint32_t)d.nqkv ||
+                        A.part_stride != (uint32_t)(d.Bm * d.nqkv))
+                        return bad("QKV input description differs from the plan");
+                    if (A.qn_gain != s->wm.qn[l] || A.kn_gain != s->wm.kn[l]) return bad("q/k norm gain offset differs from the planned vector");
+                } else {
+                    if (A.nh == 0 || (uint64_t)A.h0 + A.nh > (uint64_t)d.nq) return bad("combine task with an empty or out-of-range head range");
+                    if (A.o_out != s->am.o || A.o_ld != (uint32_t)d.qd) return bad("attention output description differs from the plan");
+                }
+            } else {   // OP_ARGMAX
+                const InstrAtt &A = *(const InstrAtt *)&I;
+                if (st != ST_ARGMAX) return bad("arg-max task at the wrong stage");
+                if (A.b >= (uint32_t)d.Bm) return bad("sequence index beyond max_batch");
+                if (A.out != s->am.amax) return bad("arg-max partial buffer offset differs from the plan");
+            }
         }
 
     // (2) every tile of every operator exactly once

@@ -11,7 +11,9 @@ Qwen3 decoder family and stand in for them with random-init weights.
 """
 from __future__ import annotations
 
+import os
 import zlib
+from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List
 
 import numpy as np
@@ -105,26 +107,36 @@ def make_weights(cfg: Dict, seed: int | None = None, gain_jitter: float = 0.0,
             return np.full(n, 0x3F80, dtype=np.uint16)  # bf16(1.0)
         return normal_bf16(seed, name, (n,), gain_jitter, 1.0)
 
-    w: Dict = {"embed": normal_bf16(seed, "embed", (V, H), std),
-               "final_norm": gain("final_norm", H)}
-    w["lm_head"] = None if cfg["tie_embeddings"] else normal_bf16(seed, "lm_head", (V, H), std)
+    # every tensor has a random stream of its own, so the tensors can be drawn side by side (numpy's
+    # generators release the interpreter lock); the values do not depend on the number of workers
+    jobs: Dict[str, tuple] = {"embed": ((V, H), std)}
+    if not cfg["tie_embeddings"]:
+        jobs["lm_head"] = ((V, H), std)
+    mats = {"wq": (qd, H), "wk": (kvd, H), "wv": (kvd, H), "wo": (H, qd), "w_gate": (I, H), "w_up": (I, H), "w_down": (H, I)}
+    for l in range(L):
+        for k, shp in mats.items():
+            jobs[f"l{l}.{k}"] = (shp, std)
+        if cfg["qkv_bias"]:
+            for k, n in (("bq", qd), ("bk", kvd), ("bv", kvd)):
+                jobs[f"l{l}.{k}"] = ((n,), std)
+    workers = max(1, min(16, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))))
+    with ThreadPoolExecutor(workers) as pool:
+        futs = {name: pool.submit(normal_bf16, seed, name, shp, sd) for name, (shp, sd) in jobs.items()}
+        drawn = {name: f.result() for name, f in futs.items()}
+
+    w: Dict = {"embed": drawn["embed"], "final_norm": gain("final_norm", H)}
+    w["lm_head"] = drawn.get("lm_head")
     per: Dict[str, List] = {k: [] for k in ("attn_norm", "wq", "wk", "wv", "bq", "bk", "bv",
                                             "q_norm", "k_norm", "wo", "mlp_norm", "w_gate", "w_up",
                                             "w_down")}
     for l in range(L):
         per["attn_norm"].append(gain(f"l{l}.attn_norm", H))
         per["mlp_norm"].append(gain(f"l{l}.mlp_norm", H))
-        per["wq"].append(normal_bf16(seed, f"l{l}.wq", (qd, H), std))
-        per["wk"].append(normal_bf16(seed, f"l{l}.wk", (kvd, H), std))
-        per["wv"].append(normal_bf16(seed, f"l{l}.wv", (kvd, H), std))
-        per["wo"].append(normal_bf16(seed, f"l{l}.wo", (H, qd), std))
-        per["w_gate"].append(normal_bf16(seed, f"l{l}.w_gate", (I, H), std))
-        per["w_up"].append(normal_bf16(seed, f"l{l}.w_up", (I, H), std))
-        per["w_down"].append(normal_bf16(seed, f"l{l}.w_down", (H, I), std))
+        for k in mats:
+            per[k].append(drawn[f"l{l}.{k}"])
         if cfg["qkv_bias"]:
-            per["bq"].append(normal_bf16(seed, f"l{l}.bq", (qd,), std))
-            per["bk"].append(normal_bf16(seed, f"l{l}.bk", (kvd,), std))
-            per["bv"].append(normal_bf16(seed, f"l{l}.bv", (kvd,), std))
+            for k in ("bq", "bk", "bv"):
+                per[k].append(drawn[f"l{l}.{k}"])
         if cfg["qk_norm"]:
             per["q_norm"].append(gain(f"l{l}.q_norm", d))
             per["k_norm"].append(gain(f"l{l}.k_norm", d))
@@ -169,15 +181,6 @@ def library_weights(w: Dict, q: Dict) -> Dict:
         out[name] = q[name]
         out["s" + name[1:]] = q["s_" + name]
     return out
-
-
-def dequant(codes: np.ndarray, scale_bits: np.ndarray, group: int) -> np.ndarray:
-    """fp64 weights of one W4 matrix (for tests: an independent restatement of the format)."""
-    lo = (codes & 15).astype(np.int64)
-    hi = (codes >> 4).astype(np.int64)
-    qv = np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1) - 8
-    s = bf16_bits_to_f32(scale_bits).astype(np.float64)
-    return qv * np.repeat(s, group, axis=1)
 
 
 def make_prompt(cfg: Dict, n: int, seed: int | None = None, name: str = "prompt") -> np.ndarray:

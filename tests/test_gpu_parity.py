@@ -438,20 +438,31 @@ def test_error_paths_leave_the_kernel_running_to_completion():
     dec.load_weights(w)
     kv = dec.new_kv()
     dec.step(tok, pos, kv, logits)
-    try:
+    with pytest.raises(mk.MkError) as e:              # one poll never sees 256 producers finished: the waits give up
         dec.check()
-    except mk.MkError as e2:
-        assert e2.code == mk.MK_ETIMEOUT
-    dec.step(tok, pos, kv, logits)                    # counters were re-armed: still terminates
+    assert e.value.code == mk.MK_ETIMEOUT
+    dec.step(tok, pos, kv, logits)                    # counters were re-armed: the launch still terminates
     torch.cuda.synchronize()
     dec.close()
+
+
+_WEIGHTS = {}
+
+
+def _weights_of(name):
+    """Host weights of one configuration, kept for the tests that follow (one configuration at a time:
+    the 7B shape alone is 14 GB)."""
+    if name not in _WEIGHTS:
+        _WEIGHTS.clear()
+        say(name, ": generating weights")
+        _WEIGHTS[name] = synth.make_weights(synth.CONFIGS[name])
+    return _WEIGHTS[name]
 
 
 def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, w4=False, **opts):
     full = synth.CONFIGS[name]
     cfg = synth.model_cfg(full, max_batch=batch)
-    say(name, ": generating weights")
-    w = synth.make_weights(full)
+    w = _weights_of(name)
     ctx0 = full["ctx0"]
     kv_h = synth.make_kv_fill(cfg, ctx0, seed=synth.seed_of(full), batch=batch)
     if w4:
@@ -471,12 +482,14 @@ def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, w4=False, **opts):
             got = pr.gpu_step(toks[s], poss)
             for b in range(batch):
                 e = rel_err(got[b], want[b])
-                say(f"{name} step {s} seq {b}: rel err {e:.2e}")
+                say(f"{name} batch {batch} step {s} seq {b}: rel err {e:.2e}")
                 assert e <= tol and int(got[b].argmax()) == oracle.argmax(want[b])
         else:   # advance both caches without comparing
             pr.orc.step(toks[s], poss, pr.kv_h, want_logits=False)
             pr.gpu_step(toks[s], poss)
     pr.close()
+    del pr
+    torch.cuda.empty_cache()
 
 
 def test_c1_half_billion_shape_teacher_forced():
@@ -484,7 +497,7 @@ def test_c1_half_billion_shape_teacher_forced():
 
 
 def test_c2_headline_shape_in_bench_configuration():
-    """Same configuration bench.py times (default schedule search, one launch per step)."""
+    """Same configuration bench.py times (the library's own schedule choice, one launch per step)."""
     _teacher_forced("c2_1p5b", (0, 1, 3))
 
 
@@ -493,11 +506,15 @@ def test_c2_headline_shape_with_w4_weights():
     _teacher_forced("c2_1p5b", (0, 2), w4=True)
 
 
-@pytest.mark.skipif(os.environ.get("MK_TEST_LARGE") != "1", reason="set MK_TEST_LARGE=1 (minutes of host-side weight generation)")
 def test_c3_qwen3_4b_shape():
+    """Per-head QK-norm at full size, 8 KV heads, context 4096."""
     _teacher_forced("c3_4b", (0, 1))
 
 
-@pytest.mark.skipif(os.environ.get("MK_TEST_LARGE") != "1", reason="set MK_TEST_LARGE=1 (minutes of host-side weight generation)")
-def test_c4_7b_shape_batch_4():
-    _teacher_forced("c4_7b", (0,), batch=4)
+@pytest.mark.parametrize("batch", [1, 4, 8])
+def test_c4_7b_shape(batch):
+    """Batch 1 on the VALU path; batch 4 and 8 as thin GEMMs on the matrix cores (at batch 8 the staged
+    activations no longer fit LDS whole: the K range of a task is staged in slices)."""
+    _teacher_forced("c4_7b", (0,), batch=batch, tol=TIGHT if batch == 1 else 1e-3)
+    if batch == 8:
+        _WEIGHTS.clear()

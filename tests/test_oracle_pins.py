@@ -15,6 +15,7 @@ import pytest
 import torch
 
 import oracle
+from w4_format import dequant
 from paper_2605_11581_amd import synth
 
 ONE = np.uint16(0x3F80)  # bf16(1.0)
@@ -349,7 +350,7 @@ def test_w4_gemv_matches_unpacked_dequantised_matmul():
         scales = synth.to_bf16_bits(rng.normal(0.01, 0.003, size=(n_out, n_in // group)).astype(np.float32))
         x = rng.normal(size=n_in).astype(np.float32)
         bias = synth.to_bf16_bits(rng.normal(size=n_out).astype(np.float32))
-        want = synth.dequant(codes, scales, group) @ x.astype(np.float64) + synth.bf16_bits_to_f32(bias)
+        want = dequant(codes, scales, group) @ x.astype(np.float64) + synth.bf16_bits_to_f32(bias)
         got = oracle.gemv_w4(codes, scales, group, x, bias)
         assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
 
@@ -381,7 +382,7 @@ def test_w4_step_equals_bf16_step_when_the_dequantised_weights_are_bf16_values()
         for l in range(cfg["n_layers"]):
             exps = rng.integers(-9, -6, size=q["s_" + name][l].shape)
             q["s_" + name][l] = synth.to_bf16_bits(np.ldexp(1.0, exps).astype(np.float32))
-            w[name][l] = synth.to_bf16_bits(synth.dequant(q[name][l], q["s_" + name][l], 64).astype(np.float32))
+            w[name][l] = synth.to_bf16_bits(dequant(q[name][l], q["s_" + name][l], 64).astype(np.float32))
     a = oracle.Decoder(cfg, w)
     b = oracle.Decoder(cfg, w, quant=q)
     kva, kvb = a.new_kv(), b.new_kv()

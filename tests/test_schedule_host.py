@@ -291,6 +291,48 @@ def test_verifier_rejects_missing_or_duplicated_tile():
     _expect_rejected(h, "unit")
 
 
+def _anywhere(h, pred, n_wg=256):
+    for wg in range(n_wg):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if pred(w):
+                return wg, i, w
+    raise AssertionError("no such instruction")
+
+
+# dword indices of the fields that address weights, vectors and the KV cache (mk_isa.h)
+LAYER, W_CHUNK, KBT, GAIN, BIAS = 3, 9, 10, 25, 29
+ATT_B, ATT_G, ATT_C, ATT_NC, ATT_BS, ATT_QN, ATT_OUT = 9, 10, 11, 12, 13, 18, 20
+
+
+@pytest.mark.parametrize("what,pred,field,value,needle", [
+    ("attention layer", lambda w: w[OP] == 2, LAYER, 1000, "layer"),
+    ("attention kv head", lambda w: w[OP] == 2, ATT_G, 2, "kv head"),
+    ("attention sequence", lambda w: w[OP] == 2, ATT_B, 1, "sequence"),
+    ("attention chunk index", lambda w: w[OP] == 2, ATT_C, 1 << 20, "chunk"),
+    ("attention chunk count", lambda w: w[OP] == 2, ATT_NC, 3, "chunk count"),
+    ("attention block size", lambda w: w[OP] == 2, ATT_BS, 32, "block size"),
+    ("attention q-norm gain", lambda w: w[OP] == 2, ATT_QN, 12345, "gain"),
+    ("attention partial buffer", lambda w: w[OP] == 2, ATT_OUT, 7, "partial buffer"),
+    ("combine sequence", lambda w: w[OP] == 3, ATT_B, 5, "sequence"),
+    ("GEMV layer", lambda w: w[OP] == 1 and w[REF_SEQ] == 3, LAYER, 1, "layer"),
+    ("GEMV weight chunk", lambda w: w[OP] == 1 and w[REF_SEQ] == 4, W_CHUNK, 1 << 30, "weight chunk"),
+    ("GEMV chunks per row group", lambda w: w[OP] == 1 and w[REF_SEQ] == 5, KBT, 10 ** 6, "geometry"),
+    ("GEMV norm gain", lambda w: w[OP] == 1 and w[REF_SEQ] == 0, GAIN, 1 << 28, "gain"),
+    ("GEMV bias", lambda w: w[OP] == 1 and w[REF_SEQ] == 0, BIAS, 64, "bias"),
+    ("arg-max sequence", lambda w: w[OP] == 4, ATT_B, 9, "sequence"),
+], ids=lambda v: v if isinstance(v, str) and " " in v else None)
+def test_verifier_rejects_fields_that_address_weights_vectors_or_the_cache(what, pred, field, value, needle):
+    """These fields never show in the activation footprint of a task: a list that carries a wrong one
+    would read or append outside its buffers.  Host only: such lists are never run."""
+    h = build("c0_tiny")
+    wg, i, w = _anywhere(h, pred)
+    assert int(w[field]) != value
+    w[field] = value
+    mk.mk_instr_set(h, wg, i, w)
+    _expect_rejected(h, needle)
+
+
 def test_verifier_rejects_list_without_end_and_unknown_opcode():
     h = build("c0_tiny")
     w = mk.mk_instr_get(h, 0, 0)
