@@ -59,7 +59,7 @@ class mk_stats(C.Structure):
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",
            "mk_get_config", "mk_instr_count", "mk_instr_get", "mk_instr_set", "mk_pages_available",
            "mk_pipeline_stages", "mk_workspace_bytes", "mk_bind_workspace", "mk_load_weights", "mk_decode_step",
-           "mk_decode_steps", "mk_decode_step_per_op", "mk_check", "mk_last_step_ms", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
+           "mk_decode_steps", "mk_decode_step_per_op", "mk_decode_step_static", "mk_check", "mk_last_step_ms", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
 
 _lib = None
 
@@ -101,7 +101,7 @@ def lib():
         L.mk_workspace_bytes.argtypes = [H]
         L.mk_bind_workspace.argtypes = [H, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mk_load_weights.argtypes = [H, C.POINTER(mk_weights), C.c_void_p]
-        for n in ("mk_decode_step", "mk_decode_step_per_op"):
+        for n in ("mk_decode_step", "mk_decode_step_per_op", "mk_decode_step_static"):
             getattr(L, n).argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.mk_decode_steps.argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_void_p]
@@ -246,6 +246,11 @@ def mk_decode_step(h, token_ids, positions, kv_cache, logits_out, batch: int, st
 def mk_decode_steps(h, token_ids, positions, kv_cache, logits_out, tokens_out, batch: int, n_steps: int, stream=None) -> None:
     _chk(lib().mk_decode_steps(h, _ptr(token_ids), _ptr(positions), _ptr(kv_cache), _ptr(logits_out), _ptr(tokens_out),
                                batch, n_steps, _stream(stream)))
+
+
+def mk_decode_step_static(h, token_ids, positions, kv_cache, logits_out, batch: int, stream=None) -> None:
+    _chk(lib().mk_decode_step_static(h, _ptr(token_ids), _ptr(positions), _ptr(kv_cache), _ptr(logits_out), batch,
+                                     _stream(stream)))
 
 
 def mk_decode_step_per_op(h, token_ids, positions, kv_cache, logits_out, batch: int, stream=None) -> None:

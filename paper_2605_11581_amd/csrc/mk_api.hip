@@ -4,6 +4,7 @@
 // mk_sched.cpp and touches no GPU.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -56,22 +57,48 @@ std::vector<const void *> all_walk_kernels()
             (const void *)mk_megakernel_ring};
 }
 
-// Tuning knobs read from the environment (development only; defaults are the shipped values).
-uint32_t dbg_knob(const char *name, uint32_t dflt, uint32_t lo, uint32_t hi)
+// ---- scratch of the allocation-free entry point -------------------------------------------------
+// One array per GPU, held until the process ends.  `mk_static_scratch` names the array in device
+// code only; host code uses the address hipGetSymbolAddress returns for the device that is current.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char mk_static_scratch[kStaticScratchBytes];
+
+struct StaticScratch {
+    char *ptr = nullptr;      // device address of this GPU's copy of the array
+    uint64_t owner = 0;       // serial of the schedule whose counters the array holds (0: none)
+    uint32_t epoch = 0;       // steps that schedule has run on the array since its counters were zeroed
+};
+constexpr int kMaxDevices = 64;
+StaticScratch g_static[kMaxDevices];
+std::atomic<uint64_t> g_serial{0};
+
+// Scratch regions of a schedule laid out from offset 0 of a private buffer (the workspace keeps them
+// interleaved with its other regions).
+struct ScratchPlan {
+    uint64_t act, counters, err, tokens, total;
+};
+ScratchPlan plan_scratch(const mk_schedule *s)
 {
-    const char *v = getenv(name);
-    if (!v || !*v) return dflt;
-    long x = strtol(v, nullptr, 10);
-    if (x < (long)lo) x = lo;
-    if (x > (long)hi) x = hi;
-    return (uint32_t)x;
+    auto up = [](uint64_t v) { return (v + 4095u) / 4096u * 4096u; };
+    ScratchPlan p;
+    p.act = 0;
+    p.counters = up(s->am.n_floats * 4);
+    p.err = p.counters + up((uint64_t)s->n_counters * mk::kCounterDwords * 4);
+    p.tokens = p.err + 4096;
+    p.total = p.tokens + 4096;
+    return p;
 }
 
 mk::Params make_params(const mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv,
-                       float *logits, int batch, int32_t *next_tokens = nullptr, int n_steps = 1)
+                       float *logits, int batch, int32_t *next_tokens = nullptr, int n_steps = 1, char *scratch = nullptr)
 {
     mk::Params P{};
     P.ws = s->ws; P.scr = s->ws; P.lay = s->lay;
+    if (scratch) {   // the scratch regions live in a buffer of their own
+        const ScratchPlan sp = plan_scratch(s);
+        P.scr = scratch;
+        P.lay.act = sp.act; P.lay.counters = sp.counters; P.lay.err = sp.err; P.lay.tokens = sp.tokens;
+    }
     P.tokens = tokens; P.positions = positions; P.kv = (uint16_t *)kv; P.logits = logits;
     P.next_tokens = next_tokens ? next_tokens : (int32_t *)(P.scr + P.lay.tokens);
     P.n_steps = n_steps; P.amax = s->am.amax; P.want_tokens = next_tokens != nullptr;
@@ -387,6 +414,7 @@ static int launch_steps(mk_schedule *s, const int32_t *tokens, const int32_t *po
         if (rc) return rc;
     }
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch, next_tokens, n_steps);
+    s->last_static = false;
     P.epoch = s->epoch + 1;
     s->epoch += (uint32_t)n_steps;
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
@@ -423,6 +451,7 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch);
+    s->last_static = false;
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, 0, 0};
     const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
     if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
@@ -435,15 +464,81 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *
     return MK_OK;
 }
 
+// This GPU's copy of the static scratch array (looked up once per device, with that device current).
+static int static_scratch_of(int device, StaticScratch **out)
+{
+    if (device < 0 || device >= kMaxDevices) { mk::set_error("device index beyond the static scratch table"); return MK_EINVAL; }
+    StaticScratch &st = g_static[device];
+    if (!st.ptr) {
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) HIP_TRY(hipSetDevice(device));
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(mk_static_scratch));
+        if (cur != device) (void)hipSetDevice(cur);
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(mk_static_scratch)");
+        if (!p) { mk::set_error("the static scratch array has no address on this device"); return MK_EHIP; }
+        st.ptr = (char *)p;
+    }
+    *out = &st;
+    return MK_OK;
+}
+
+int mk_decode_step_static(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
+                          int32_t batch, void *stream)
+{
+    if (!s) { mk::set_error("null schedule"); return MK_EINVAL; }
+    const ScratchPlan sp = plan_scratch(s);
+    if (sp.total > kStaticScratchBytes) {   // (checked first: a property of the schedule, whatever its binding state)
+        char buf[200];
+        snprintf(buf, sizeof buf, "mk_decode_step_static: this schedule needs %llu bytes of scratch, the static array holds %llu",
+                 (unsigned long long)sp.total, (unsigned long long)kStaticScratchBytes);
+        mk::set_error(buf);
+        return MK_ENOMEM;
+    }
+    int rc = check_step_args(s, tokens, positions, kv, logits, batch);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StaticScratch *ss = nullptr;
+    rc = static_scratch_of(s->device, &ss);
+    if (rc) return rc;
+    if (!s->serial) s->serial = ++g_serial;
+    if (ss->owner != s->serial || ss->epoch >= 0x00800000u) {
+        // the array holds another schedule's counters (or none, or this one's are about to wrap): start from zero.
+        // Fill kernels, not memsets: the call may be recorded into a graph.
+        rc = fill_u32(ss->ptr + sp.counters, 0u, (size_t)s->n_counters * mk::kCounterDwords, st);
+        if (rc) return rc;
+        rc = fill_u32(ss->ptr + sp.err, 0u, 16, st);
+        if (rc) return rc;
+        ss->owner = s->serial; ss->epoch = 0;
+    }
+    mk::Params P = make_params(s, tokens, positions, kv, logits, batch, nullptr, 1, ss->ptr);
+    P.epoch = ++ss->epoch;
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
+    hipLaunchKernelGGL(walk_kernel(s, 1), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    HIP_TRY(hipGetLastError());
+    s->last_static = true;
+    return MK_OK;
+}
+
 int mk_check(mk_schedule *s, void *stream)
 {
     if (!s || !s->bound) { mk::set_error("mk_check on an unbound schedule"); return MK_ESTATE; }
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipStreamSynchronize(st));
     uint32_t e[16] = {0};
-    HIP_TRY(hipMemcpy(e, s->ws + s->lay.err, sizeof e, hipMemcpyDeviceToHost));
+    StaticScratch *ss = nullptr;
+    if (s->last_static) {
+        int rc0 = static_scratch_of(s->device, &ss);
+        if (rc0) return rc0;
+        HIP_TRY(hipMemcpy(e, ss->ptr + plan_scratch(s).err, sizeof e, hipMemcpyDeviceToHost));
+    } else {
+        HIP_TRY(hipMemcpy(e, s->ws + s->lay.err, sizeof e, hipMemcpyDeviceToHost));
+    }
     if (e[0] == 0 && e[1] == 0 && e[2] == 0) return MK_OK;
-    int rc = reset_sync_state(s, st);
+    int rc = MK_OK;
+    if (ss) ss->owner = 0;                 // the next step on the static array starts from zeroed counters and flags
+    else rc = reset_sync_state(s, st);
     HIP_TRY(hipStreamSynchronize(st));
     if (rc) return rc;
     char buf[200];

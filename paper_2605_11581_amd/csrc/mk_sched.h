@@ -83,6 +83,8 @@ struct mk_schedule {
     uint32_t epoch;
     void *ev0, *ev1;
     bool ev_valid;
+    uint64_t serial;         // identity of this handle among the users of a GPU's static scratch array (0: not yet drawn)
+    bool last_static;        // the most recent step ran on the static scratch array (mk_check reads the flags there)
 };
 
 namespace mk {
