@@ -1,7 +1,7 @@
 /*
  * mk.h -- C ABI of the MI355X decode-step megakernel library (libmk.so).
  *
- * The library runs one batch-1..8 LLM decode step (RMSNorm -> QKV projection
+ * The library runs one batch-1..16 LLM decode step (RMSNorm -> QKV projection
  * + RoPE -> GQA attention over the KV cache -> O projection + residual ->
  * SwiGLU MLP -> final norm + LM head) as ONE persistent kernel launch whose
  * execution order is fixed offline.  This mirrors the two phases of the paper
@@ -54,7 +54,7 @@ typedef struct mk_config {
     int32_t qk_norm;         /* 1: per-head RMSNorm on q and k before RoPE           */
     int32_t tie_embeddings;  /* 1: LM head shares the embedding matrix               */
     float rope_theta, rms_eps;
-    int32_t max_batch;       /* 1..8                                                 */
+    int32_t max_batch;       /* 1..16                                                */
     int32_t max_context;     /* KV slots per sequence                                */
     int32_t n_workgroups;    /* persistent grid size; 0 = one per CU of device_id    */
     int32_t device_id;       /* only read when n_workgroups == 0 or at bind time     */
@@ -82,7 +82,8 @@ typedef struct mk_config {
 
 enum {
     MK_F_TRACE = 1u,         /* record per-task clocks into the trace buffer          */
-    MK_F_TIMING = 2u         /* bracket each step's launch(es) with HIP events         */
+    MK_F_TIMING = 2u,        /* bracket each step's launch(es) with HIP events         */
+    MK_F_NO_TABLE = 4u       /* mk_build_schedule: ignore the table of recorded profile-guided tilings */
 };
 
 typedef struct mk_schedule mk_schedule; /* opaque, library-owned host object */
@@ -113,13 +114,25 @@ typedef struct mk_stats {
     int32_t candidates_tried, candidates_pruned;
     int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head;  /* rows per 1 KB weight chunk, per matrix */
     int32_t fuse_combine;
+    int32_t from_table;              /* 1: the tiling is the profiled one recorded for this configuration */
+    int32_t reserved;
 } mk_stats;
 
 /* Phase I (host only, touches no GPU unless n_workgroups == 0): build the
  * tile-task DAG of the decoder + LM head (Sec. 4.2.1 / Step 1-2), prune and
  * search the tiling space with the page-budget model and the pipeline
  * simulator (Step 3-4), verify, and emit the static per-workgroup instruction
- * lists.  *out is set only on success. */
+ * lists.  *out is set only on success.
+ *
+ * Step 4 of the paper locks in the trace that offline PROFILING on the target
+ * GPU scores best.  The profiling search (autotune.py, driving this same ABI on
+ * the device) records its winner per deployment configuration in the text table
+ * tuned_tilings.txt next to the library (another path: environment variable
+ * MK_TUNED_TABLE, read here only).  When cfg fixes no tiling field (all split_*,
+ * attn_chunks, chunk_rows, rows_* zero, fuse_combine <= 0, ring_kb <= 0, use_mfma
+ * -1) and the table holds a line for (model dimensions, max_batch, n_workgroups,
+ * weight_bits), that tiling is used (mk_stats.from_table = 1); otherwise, or with
+ * MK_F_NO_TABLE, the cost model's own pick. */
 int mk_build_schedule(const mk_config *cfg, mk_schedule **out);
 
 /* Structural check of an emitted schedule against its DAG: every tile of every
@@ -223,6 +236,14 @@ int mk_check(mk_schedule *s, void *stream);
  * events recorded on the launch stream around the launch(es).  Synchronises
  * on the closing event. */
 int mk_last_step_ms(mk_schedule *s, float *ms);
+
+/* Streaming-read ceiling of the bound device, for the roofline report: a persistent grid of n_workgroups
+ * workgroups reads the schedule's own repacked weight region (*bytes of it, a whole number of 1 KB chunks per
+ * workgroup) with the load form of the weight stream (128-bit nontemporal loads, 16 in flight per lane) and
+ * does nothing else; `reps` timed launches bracketed by HIP events on `stream`, after one untimed launch.
+ * ms_out[reps] receives the durations.  Needs a bound workspace (the weights need not be loaded: the
+ * kernel never looks at what it reads).  Synchronises `stream`. */
+int mk_read_ceiling(mk_schedule *s, int32_t reps, float *ms_out, size_t *bytes, void *stream);
 
 /* Change the run-time flags of a handle (only MK_F_TIMING may be toggled after
  * the schedule was built; MK_F_TRACE is fixed at build time because it sizes

@@ -5,10 +5,13 @@ The host-side search of ``mk_build_schedule`` ranks candidates with a pipeline c
 This module closes the loop on the device: starting from the model's choice it walks the tiling
 parameters one at a time (K splits, attention chunking, rows per weight chunk of every matrix),
 builds each candidate schedule, runs a few decode steps of the real workload and keeps what
-measures fastest.  Results are kept in ``tuned.json`` next to this file, keyed by the model shape
-and grid size; ``tuned_opts`` hands them to callers as defaults for ``binding.make_config``.
+measures fastest.  Results are kept in ``tuned_tilings.txt`` next to the library, one line per
+deployment configuration (model shape, batch limit, grid size, weight format); the LIBRARY reads that
+table: ``mk_build_schedule`` applies a configuration's line whenever the caller fixes no tiling field
+itself.  ``tuned_opts`` reads the same table for tools and tests.
 
-Only sequencing lives here; every candidate runs through the same C ABI as any other schedule.
+Only sequencing lives here; every candidate runs through the same C ABI as any other schedule, and a
+candidate is only accepted if its logits agree with those of the starting schedule.
 
     python -m paper_2605_11581_amd.autotune --config c2_1p5b --write
 """
@@ -17,11 +20,12 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 from typing import Callable, Dict, List, Optional, Tuple
 
-TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned.json")
+TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned_tilings.txt")
 
 # parameter -> candidate values, in the order they are walked
 SPACE: List[Tuple[str, List[int]]] = [
@@ -30,15 +34,13 @@ SPACE: List[Tuple[str, List[int]]] = [
     ("rows_gateup", [4, 8, 16]),
     ("rows_o", [2, 4, 8, 16]),
     ("rows_qkv", [2, 4, 8, 16]),
-    ("attn_chunks", [16, 32, 64]),
-    ("split_down", [1, 2, 4]),
+    ("attn_chunks", [4, 8, 16, 32, 64]),
+    ("fuse_combine", [0, 1]),
+    ("split_down", [1, 2, 4, 8]),
     ("split_qkv", [1, 2]),
     ("split_gateup", [1, 2]),
     ("rows_head", [8, 16]),
 ]
-_STAT_OF = {"split_o": "split_o", "rows_down": "rows_down", "rows_gateup": "rows_gateup", "rows_o": "rows_o",
-            "rows_qkv": "rows_qkv", "attn_chunks": "attn_chunks", "split_down": "split_down", "split_qkv": "split_qkv",
-            "rows_head": "rows_head", "split_gateup": "split_gateup"}
 
 
 def shape_key(model: Dict, n_workgroups: int, weight_bits: int = 16) -> str:
@@ -46,36 +48,64 @@ def shape_key(model: Dict, n_workgroups: int, weight_bits: int = 16) -> str:
     return "-".join(str(int(model[k])) for k in dims) + f"-wg{int(n_workgroups)}-w{int(weight_bits) or 16}"
 
 
-def tuned_opts(model: Dict, n_workgroups: int, weight_bits: int = 16) -> Dict[str, int]:
-    """Tiling overrides recorded for this model shape, grid size and weight format ({} if none)."""
+def read_table(path: str = TABLE) -> Dict[str, Dict[str, int]]:
+    """The recorded tilings: key -> {field: value} (the format mk_build_schedule parses)."""
+    out: Dict[str, Dict[str, int]] = {}
     try:
-        with open(TABLE) as f:
-            table = json.load(f)
+        lines = open(path).read().splitlines()
     except OSError:
-        return {}
-    entry = table.get(shape_key(model, n_workgroups, weight_bits))
-    return dict(entry["opts"]) if entry else {}
+        return out
+    for line in lines:
+        line = line.split("#", 1)[0].split()
+        if line:
+            out[line[0]] = {k: int(v) for k, v in (kv.split("=") for kv in line[1:]) if k != "ms"}
+    return out
+
+
+def write_entry(key: str, opts: Dict[str, int], note: str, path: str = TABLE) -> None:
+    """Replace (or add) the line of one configuration; comment lines and other entries stay."""
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        lines = []
+    keep = [l for l in lines if not re.match(rf"{re.escape(key)}\s", l)]
+    order = [k for k, _ in SPACE]
+    body = " ".join(f"{k}={int(opts[k])}" for k in sorted(opts, key=lambda k: order.index(k) if k in order else 99))
+    head = [l for l in keep if l.startswith("#")]
+    rest = sorted([l for l in keep if l and not l.startswith("#")] + [f"{key}  {body}  # {note}"])
+    with open(path, "w") as f:
+        f.write("\n".join(head + rest) + "\n")
+
+
+def tuned_opts(model: Dict, n_workgroups: int, weight_bits: int = 16) -> Dict[str, int]:
+    """Tiling recorded for this model shape, grid size and weight format ({} if none)."""
+    return dict(read_table().get(shape_key(model, n_workgroups, weight_bits), {}))
 
 
 def autotune(model: Dict, dev_weights: Dict, position: int, device: str = "cuda:0", steps: int = 24, warmup: int = 4,
              rounds: int = 2, base_opts: Optional[Dict] = None, log: Callable[[str], None] = lambda s: None,
-             seed_opts: Optional[Dict] = None):
-    """Coordinate descent over SPACE with the device as the scorer.  ``dev_weights``: tensors already
-    on ``device`` (see runtime.stage_weights).  Returns (best overrides, best ms per step, history)."""
+             seed_opts: Optional[Dict] = None, space: Optional[List[Tuple[str, List[int]]]] = None, tol: float = 1e-3):
+    """Coordinate descent over ``space`` (default SPACE) with the device as the scorer.  ``dev_weights``:
+    tensors already on ``device`` (see runtime.stage_weights).  A candidate replaces the incumbent only if
+    it is faster AND its logits agree with the starting schedule's to ``tol`` of the largest logit (every
+    candidate computes the same function; this catches a tiling that does not).
+    Returns (best overrides, best ms per step, history)."""
     import torch
     from . import binding as mk
     from .runtime import Decoder
 
+    space = list(space or SPACE)
     base_opts = dict(base_opts or {})
     B = int(model["max_batch"])
     tok = torch.full((B,), 17, dtype=torch.int32, device=device)
     pos = torch.full((B,), int(position), dtype=torch.int32, device=device)
     logits = torch.empty(B, model["vocab"], dtype=torch.float32, device=device)
     history = []
+    ref = {}
 
     def measure(opts: Dict) -> Optional[float]:
         try:
-            dec = Decoder(model, device=device, **base_opts, **opts)
+            dec = Decoder(model, device=device, flags=mk.MK_F_NO_TABLE, **base_opts, **opts)
         except mk.MkError as e:
             if e.code in (mk.MK_EINFEASIBLE, mk.MK_EINVAL):
                 return None
@@ -93,22 +123,31 @@ def autotune(model: Dict, dev_weights: Dict, position: int, device: str = "cuda:
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t) * 1e3 / steps
             dec.check()
+            got = logits.clone()
+            if "logits" not in ref:
+                ref["logits"] = got
+            else:
+                err = float((got - ref["logits"]).abs().max() / ref["logits"].abs().max())
+                if not err <= tol:
+                    log(f"  rejected: logits differ from the starting schedule's by {err:.2e}")
+                    return None
             return ms
         finally:
             dec.close()
 
     # start from what the cost model picks, with every searched parameter pinned to that choice
-    dec0 = Decoder(model, device=device, ring_kb=-1, **base_opts)   # naming a tiling key bypasses recorded choices
+    dec0 = Decoder(model, device=device, flags=mk.MK_F_NO_TABLE, **base_opts)
     st = dec0.stats
     dec0.close()
-    best = {k: int(st[_STAT_OF[k]]) for k, _ in SPACE}
+    best = {k: int(st[k]) for k, _ in space}
     best_ms = measure(best)
     log(f"start {best} -> {best_ms:.4f} ms")
     history.append((dict(best), best_ms))
     # a recorded choice for this shape is a second starting point (the walk below only finds the
     # nearest local optimum of whichever start is better)
-    if seed_opts and all(k in seed_opts for k, _ in SPACE):
-        seed = {k: int(seed_opts[k]) for k, _ in SPACE}
+    if seed_opts:
+        seed = dict(best)
+        seed.update({k: int(v) for k, v in seed_opts.items() if k in best})
         if seed != best:
             ms = measure(seed)
             history.append((dict(seed), ms))
@@ -117,7 +156,7 @@ def autotune(model: Dict, dev_weights: Dict, position: int, device: str = "cuda:
                 best, best_ms = seed, ms
     for r in range(rounds):
         improved = False
-        for name, values in SPACE:
+        for name, values in space:
             for v in values:
                 if v == best[name]:
                     continue
@@ -140,7 +179,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=24)
     ap.add_argument("--rounds", type=int, default=2)
     ap.add_argument("--w4", action="store_true", help="tune the W4A16 form (group 128) of the decoder projections")
-    ap.add_argument("--write", action="store_true", help="record the result in tuned.json")
+    ap.add_argument("--write", action="store_true", help="record the result in tuned_tilings.txt (the table the library reads)")
     args = ap.parse_args()
     import torch
     from . import synth
@@ -163,15 +202,7 @@ def main() -> int:
     key = shape_key(model, n_wg, bits)
     print(json.dumps({"config": args.config, "key": key, "opts": best, "ms_per_step": round(ms, 5)}))
     if args.write:
-        try:
-            table = json.load(open(TABLE))
-        except OSError:
-            table = {}
-        table[key] = {"opts": best, "ms_per_step": round(ms, 5), "position": pos,
-                                         "workload": args.config, "candidates_timed": len(hist)}
-        with open(TABLE, "w") as f:
-            json.dump(table, f, indent=1, sort_keys=True)
-            f.write("\n")
+        write_entry(key, best, f"{args.config} position {pos}: {ms:.5f} ms/step, {len(hist)} candidates timed")
     return 0
 
 

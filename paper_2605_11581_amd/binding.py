@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("MK_LIB_PATH") or os.path.join(_HERE, "libmk.so")   # override: A/B runs of two builds
 
 MK_OK, MK_EINVAL, MK_ENOMEM, MK_EINFEASIBLE, MK_ESCHED, MK_EHIP, MK_ETIMEOUT, MK_ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
-MK_F_TRACE, MK_F_TIMING = 1, 2
+MK_F_TRACE, MK_F_TIMING, MK_F_NO_TABLE = 1, 2, 4
 INSTR_DWORDS = 32
 
 
@@ -53,13 +53,14 @@ class mk_stats(C.Structure):
         ("_pad", C.c_int32), ("weight_bytes_per_step", C.c_int64), ("workspace_bytes", C.c_int64),
         ("sim_makespan_us", C.c_double), ("sim_duty_cycle", C.c_double),
         ("candidates_tried", C.c_int32), ("candidates_pruned", C.c_int32)] + [
-        (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "fuse_combine")]
+        (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "fuse_combine", "from_table",
+                                 "reserved")]
 
 
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",
            "mk_get_config", "mk_instr_count", "mk_instr_get", "mk_instr_set", "mk_pages_available",
            "mk_pipeline_stages", "mk_workspace_bytes", "mk_bind_workspace", "mk_load_weights", "mk_decode_step",
-           "mk_decode_steps", "mk_decode_step_per_op", "mk_decode_step_static", "mk_check", "mk_last_step_ms", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
+           "mk_decode_steps", "mk_decode_step_per_op", "mk_decode_step_static", "mk_check", "mk_last_step_ms", "mk_read_ceiling", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
 
 _lib = None
 
@@ -107,6 +108,7 @@ def lib():
                                       C.c_void_p]
         L.mk_check.argtypes = [H, C.c_void_p]
         L.mk_last_step_ms.argtypes = [H, C.POINTER(C.c_float)]
+        L.mk_read_ceiling.argtypes = [H, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_size_t), C.c_void_p]
         L.mk_set_flags.argtypes = [H, C.c_uint32]
         L.mk_read_trace.argtypes = [H, C.c_void_p, C.POINTER(C.c_size_t), C.c_void_p]
         L.mk_destroy.argtypes = [H]
@@ -266,6 +268,14 @@ def mk_last_step_ms(h) -> float:
     ms = C.c_float(0)
     _chk(lib().mk_last_step_ms(h, C.byref(ms)))
     return float(ms.value)
+
+
+def mk_read_ceiling(h, reps: int = 5, stream=None):
+    """(durations in ms of ``reps`` launches of the streaming-read kernel, bytes each launch read)."""
+    ms = (C.c_float * reps)()
+    n = C.c_size_t(0)
+    _chk(lib().mk_read_ceiling(h, reps, ms, C.byref(n), _stream(stream)))
+    return [float(x) for x in ms], int(n.value)
 
 
 def mk_set_flags(h, flags: int) -> None:

@@ -208,6 +208,7 @@ int mk_get_stats(const mk_schedule *s, mk_stats *o)
     o->sim_makespan_us = s->sim.makespan_us; o->sim_duty_cycle = s->sim.duty;
     o->candidates_tried = s->cand_tried; o->candidates_pruned = s->cand_pruned;
     o->fuse_combine = s->tl.fuse;
+    o->from_table = s->from_table;
     return MK_OK;
 }
 
@@ -561,6 +562,30 @@ int mk_last_step_ms(mk_schedule *s, float *ms)
     if (!(s->cfg.flags & MK_F_TIMING)) { mk::set_error("step timing needs flag bit 1 (value 2) in mk_config.flags"); return MK_ESTATE; }
     HIP_TRY(hipEventSynchronize((hipEvent_t)s->ev1));
     HIP_TRY(hipEventElapsedTime(ms, (hipEvent_t)s->ev0, (hipEvent_t)s->ev1));
+    return MK_OK;
+}
+
+int mk_read_ceiling(mk_schedule *s, int32_t reps, float *ms_out, size_t *bytes, void *stream)
+{
+    if (!s || !ms_out || !bytes || reps < 1) { mk::set_error("bad argument"); return MK_EINVAL; }
+    if (!s->bound || !s->ev_valid) { mk::set_error("mk_read_ceiling needs a bound workspace"); return MK_ESTATE; }
+    hipStream_t st = (hipStream_t)stream;
+    const uint64_t per_wg = s->wm.n_chunks / (uint64_t)s->n_wg;
+    if (per_wg == 0 || per_wg > 0xffffffffull) { mk::set_error("weight region too small or too large to stream"); return MK_EINVAL; }
+    const mk::u32x4 *src = (const mk::u32x4 *)(s->ws + s->lay.weights);
+    *bytes = (size_t)(per_wg * (uint64_t)s->n_wg * mk::kChunkBytes);
+    for (int r = -1; r < reps; ++r) {
+        if (r >= 0) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
+        hipLaunchKernelGGL(mk_stream_read_kernel, dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), 0, st, src, (uint32_t)per_wg,
+                           (uint32_t *)(s->ws + s->lay.tokens));
+        HIP_TRY(hipGetLastError());
+        if (r >= 0) {
+            HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
+            HIP_TRY(hipEventSynchronize((hipEvent_t)s->ev1));
+            HIP_TRY(hipEventElapsedTime(&ms_out[r], (hipEvent_t)s->ev0, (hipEvent_t)s->ev1));
+        }
+    }
+    HIP_TRY(hipStreamSynchronize(st));
     return MK_OK;
 }
 

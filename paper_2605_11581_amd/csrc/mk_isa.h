@@ -21,7 +21,8 @@ constexpr int kWaves = kWgThreads / 64;
 constexpr int kChunkBytes = 1024;      // one wavefront-wide 128-bit load: 16 rows x 32 k of bf16
 constexpr int kInstrDwords = 32;
 constexpr uint32_t kNone = 0xffffffffu;
-constexpr int kMaxBatch = 8;
+constexpr int kMaxBatch = 16;         // sequences per step: 8 fill the 16 columns of one matrix-core instruction (two bf16
+                                       // terms each), 9..16 take a second instruction per weight chunk
 constexpr int kActTerms = 2;           // bf16 terms (hi + lo) of an fp32 activation on the matrix-core path
 constexpr int kMaxGroup = 8;           // q heads per kv head
 constexpr int kCounterStride = 32;     // dwords between sub-counters (one 128-byte line each)

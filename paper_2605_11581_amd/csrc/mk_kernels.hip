@@ -938,7 +938,9 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     uint32_t cur_kb0 = (u0 % S) * nkb;  // first chunk of the current unit inside its row group
 
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    f32x4 cacc = {0.f, 0.f, 0.f, 0.f};
+    f32x4 cacc = {0.f, 0.f, 0.f, 0.f};    // matrix-core path: columns 0..15 (sequences 0..7, two terms each)
+    f32x4 cacc2 = {0.f, 0.f, 0.f, 0.f};   //                   columns 16..31 (sequences 8..15), used when batch > 8
+    const bool wide = MFMA && ncols > 16;
 
     auto flush = [&]() {
         if (!MFMA) {
@@ -958,17 +960,22 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             // cacc[j] = C[row 4*ksub + j][col lane & 15]; sum the nterm columns of each sequence
             const int col = lane & 15;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float v = cacc[j];
-                // the term columns of a sequence are neighbours inside the 16-lane row: DPP row shifts
-                float v1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x101, 0xf, 0xf, true));
-                float v2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x102, 0xf, 0xf, true));
-                float sum = v + v1 + (nterm == 3 ? v2 : 0.f);
-                int b = col / nterm;
-                if (col < ncols && col == b * nterm)
-                    red[wave * red_per_wave + (ul * batch + b) * 16 + ksub * 4 + j] = sum;
-                cacc[j] = 0.f;
+            for (int grp = 0; grp < 2; ++grp) {
+                if (grp && !wide) break;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float v = grp ? cacc2[j] : cacc[j];
+                    // the term columns of a sequence are neighbours inside the 16-lane row: DPP row shifts
+                    float v1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x101, 0xf, 0xf, true));
+                    float v2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x102, 0xf, 0xf, true));
+                    float sum = v + v1 + (nterm == 3 ? v2 : 0.f);
+                    const int cc = col + 16 * grp, b = cc / nterm;
+                    if (cc < ncols && cc == b * nterm)
+                        red[wave * red_per_wave + (ul * batch + b) * 16 + ksub * 4 + j] = sum;
+                }
             }
+            cacc = f32x4{0.f, 0.f, 0.f, 0.f};
+            cacc2 = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
 
@@ -1013,12 +1020,13 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             a2 += bf_lo(w.w) * x1.z; a3 += bf_hi(w.w) * x1.w;
         } else {
             const int col = lane & 15;
-            u32x4 xb = {0u, 0u, 0u, 0u};
-            if (col < ncols)
-                xb = *(const u32x4 *)(xs + (size_t)col * plane_stride + ((size_t)kb_rel * ck + ksub * 8) * 2);
+            const char *xk = xs + ((size_t)kb_rel * ck + ksub * 8) * 2;
+            u32x4 xb = {0u, 0u, 0u, 0u}, xb2 = {0u, 0u, 0u, 0u};
+            if (col < ncols) xb = *(const u32x4 *)(xk + (size_t)col * plane_stride);
+            if (wide && col + 16 < ncols) xb2 = *(const u32x4 *)(xk + (size_t)(col + 16) * plane_stride);
             bf16x8 av = __builtin_bit_cast(bf16x8, w);
-            bf16x8 bv = __builtin_bit_cast(bf16x8, xb);
-            cacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, cacc, 0, 0, 0);
+            cacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, xb), cacc, 0, 0, 0);
+            if (wide) cacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, xb2), cacc2, 0, 0, 0);
         }
         kbi += kWaves;
     };
@@ -1984,4 +1992,30 @@ extern "C" __global__ void mk_fill_u32_kernel(uint32_t *dst, uint32_t v, size_t 
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < n) dst[gid] = v;
+}
+
+
+// Streaming-read ceiling of the device: a persistent grid (one workgroup per CU) in which every workgroup reads
+// its contiguous share of a buffer with the load form of the GEMV weight stream (128-bit nontemporal loads, 16 in
+// flight per lane), and nothing else.  What this kernel reaches is the bandwidth a weight stream can reach at all.
+extern "C" __global__ void __launch_bounds__(256) mk_stream_read_kernel(const mk::u32x4 *src, uint32_t chunks_per_wg, uint32_t *sink)
+{
+    constexpr int kDepth = 16;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const mk::u32x4 *base = src + (size_t)blockIdx.x * chunks_per_wg * 64 + lane;
+    const uint32_t total = chunks_per_wg, last = total ? total - 1 : 0;
+    mk::u32x4 acc = {0u, 0u, 0u, 0u};
+    mk::u32x4 buf[kDepth];
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) buf[j] = __builtin_nontemporal_load(base + (size_t)min(wave + 4u * j, last) * 64);
+    for (uint32_t b = 0; b < total; b += 4 * kDepth) {
+#pragma unroll
+        for (int j = 0; j < kDepth; ++j) {
+            const uint32_t idx = b + 4u * j + wave;
+            if (idx < total) acc ^= buf[j];
+            buf[j] = __builtin_nontemporal_load(base + (size_t)min(idx + 4u * kDepth, last) * 64);
+        }
+    }
+    // the loads must not be optimised away; the condition does not hold for any real buffer content
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5bd1e995u && sink) sink[0] = acc.x;
 }

@@ -19,8 +19,12 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <dlfcn.h>
+
+#include <fstream>
 #include <map>
 #include <numeric>
+#include <sstream>
 
 namespace mk {
 
@@ -65,7 +69,7 @@ static int derive_dims(const mk_config &c, Dims &d)
     if (c.head_dim != 64 && c.head_dim != 128) return bad("head_dim must be 64 or 128");
     if (c.n_q_heads % c.n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
     if (c.n_q_heads / c.n_kv_heads > kMaxGroup) return bad("more than 8 q heads per kv head");
-    if (c.max_batch < 1 || c.max_batch > kMaxBatch) return bad("max_batch must be 1..8");
+    if (c.max_batch < 1 || c.max_batch > kMaxBatch) return bad("max_batch must be 1..16");
     if (c.max_context < 1) return bad("max_context must be positive");
     if (c.n_workgroups < 1 || c.n_workgroups > 4096) return bad("n_workgroups must be 1..4096");
     if (!(c.rms_eps > 0.f) || !(c.rope_theta > 0.f)) return bad("rms_eps and rope_theta must be positive");
@@ -641,6 +645,79 @@ static int assemble(const mk_config &cfg, const Dims &d, const Tiling &t, mk_sch
     return MK_OK;
 }
 
+// ---------------------------------------------------------------- recorded profile-guided tilings
+// Sec. 4.2.2 Step 4: candidates are profiled offline on the target GPU and the best trace is locked in.
+// The on-device search (autotune.py, through this same C ABI) records its winner per deployment
+// configuration in a text table next to the library: one line per configuration,
+//     <L>-<H>-<nq>-<nkv>-<d>-<I>-<V>-<max_batch>-wg<workgroups>-w<weight bits>  name=value ...
+// with the names of the tiling fields of mk_config.  mk_build_schedule applies a matching line when
+// the caller fixes no tiling field itself, so that the schedule it returns is the profiled one.
+std::string tuned_key(const mk_config &c)
+{
+    char buf[200];
+    snprintf(buf, sizeof buf, "%d-%d-%d-%d-%d-%d-%d-%d-wg%d-w%d", c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim,
+             c.intermediate, c.vocab, c.max_batch, c.n_workgroups, c.weight_bits == 4 ? 4 : 16);
+    return buf;
+}
+
+std::string tuned_table_path()
+{
+    if (const char *e = getenv("MK_TUNED_TABLE")) return e;      // read when a schedule is built, never on the launch path
+    Dl_info info;
+    if (!dladdr((const void *)&tuned_table_path, &info) || !info.dli_fname) return "";
+    std::string p = info.dli_fname;
+    const size_t slash = p.rfind('/');
+    return (slash == std::string::npos ? std::string(".") : p.substr(0, slash)) + "/tuned_tilings.txt";
+}
+
+static bool names_no_tiling(const mk_config &c)
+{
+    return !c.split_qkv && !c.split_o && !c.split_gateup && !c.split_down && !c.attn_chunks && !c.chunk_rows && !c.rows_qkv &&
+           !c.rows_o && !c.rows_gateup && !c.rows_down && !c.rows_head && c.fuse_combine <= 0 && c.ring_kb <= 0 && c.use_mfma < 0;
+}
+
+// Applies the recorded line of this configuration to `c`; false when there is none (or the table is absent).
+static bool apply_tuned(mk_config &c)
+{
+    const std::string path = tuned_table_path();
+    if (path.empty()) return false;
+    std::ifstream f(path);
+    if (!f) return false;
+    const std::string key = tuned_key(c);
+    std::string line;
+    while (std::getline(f, line)) {
+        const size_t hash = line.find('#');
+        if (hash != std::string::npos) line.resize(hash);
+        std::istringstream is(line);
+        std::string k, kv;
+        if (!(is >> k) || k != key) continue;
+        mk_config t = c;
+        struct { const char *name; int32_t mk_config::*field; } names[] = {
+            {"split_qkv", &mk_config::split_qkv}, {"split_o", &mk_config::split_o}, {"split_gateup", &mk_config::split_gateup},
+            {"split_down", &mk_config::split_down}, {"attn_chunks", &mk_config::attn_chunks}, {"rows_qkv", &mk_config::rows_qkv},
+            {"rows_o", &mk_config::rows_o}, {"rows_gateup", &mk_config::rows_gateup}, {"rows_down", &mk_config::rows_down},
+            {"rows_head", &mk_config::rows_head}, {"fuse_combine", &mk_config::fuse_combine}};
+        bool ok = true;
+        while (is >> kv) {
+            const size_t eq = kv.find('=');
+            if (eq == std::string::npos) { ok = false; break; }
+            const std::string name = kv.substr(0, eq);
+            if (name == "ms") continue;                             // the measured step time, informative only
+            char *end = nullptr;
+            const long v = strtol(kv.c_str() + eq + 1, &end, 10);
+            if (!end || *end || v < 0 || v > 4096) { ok = false; break; }
+            bool known = false;
+            for (auto &n : names)
+                if (name == n.name) { t.*(n.field) = (int32_t)v; known = true; }
+            if (!known) { ok = false; break; }
+        }
+        if (!ok) continue;      // a malformed line is ignored: the cost model's choice stands
+        c = t;
+        return true;
+    }
+    return false;
+}
+
 int build_schedule(const mk_config *cfg_in, mk_schedule **out)
 {
     if (!cfg_in || !out) { set_error("null argument"); return MK_EINVAL; }
@@ -648,6 +725,21 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     Dims d;
     int rc = derive_dims(cfg, d);
     if (rc) return rc;
+    // no tiling fixed by the caller: the profiled choice recorded for this configuration, if any (a
+    // recorded line that no longer builds falls back to the cost model's search below)
+    if (!(cfg.flags & MK_F_NO_TABLE) && names_no_tiling(cfg)) {
+        mk_config t = cfg;
+        if (apply_tuned(t)) {
+            t.flags |= MK_F_NO_TABLE;
+            mk_schedule *s = nullptr;
+            if (build_schedule(&t, &s) == MK_OK) {
+                s->cfg.flags = cfg.flags;
+                s->from_table = 1;
+                *out = s;
+                return MK_OK;
+            }
+        }
+    }
     const int mfma = d.w4 ? 0 : cfg.use_mfma < 0 ? (d.Bm > 1 ? 1 : 0) : (cfg.use_mfma ? 1 : 0);
     if (!mfma && d.Bm > 1) { set_error("mk_config: the VALU GEMV path handles max_batch == 1 only"); return MK_EINVAL; }
     if (cfg.ring_kb < -2 || (cfg.ring_kb > 0 && (cfg.ring_kb < 16 || cfg.ring_kb > 144))) { set_error("mk_config: ring_kb must be -2 (search), -1 (auto), 0 (no ring) or 16..144"); return MK_EINVAL; }

@@ -75,6 +75,7 @@ struct mk_schedule {
     std::vector<uint32_t> ref_seqs;       // distinct operator-instance ranks in topological order
     mk::SimResult sim;
     int cand_tried, cand_pruned;
+    int from_table;          // 1: the tiling came from the table of recorded profile-guided tilings
     // ---- run-time binding (filled by mk_bind_workspace / mk_load_weights)
     char *ws;
     size_t ws_bytes;

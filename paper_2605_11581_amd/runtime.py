@@ -34,23 +34,15 @@ def stage_weights(w: Dict, device) -> Dict:
     return dev
 
 
-_TILING_KEYS = {"split_qkv", "split_o", "split_gateup", "split_down", "attn_chunks", "chunk_rows", "rows_qkv", "rows_o",
-                "rows_gateup", "rows_down", "rows_head", "ring_kb", "use_mfma"}
-
-
 class Decoder:
     def __init__(self, model: Dict, device: str = "cuda:0", schedule_blob: Optional[bytes] = None, **opts):
-        """Tiling parameters not given in ``opts`` come from the offline search; when ``opts`` names
-        none at all, the profile-guided choices recorded for this shape (autotune.py) are applied."""
+        """``opts`` are fields of ``mk_config``; tiling parameters not given come from the library's own
+        choice (the profiled tiling recorded for this deployment configuration, else its cost-model search)."""
         self.device = torch.device(device)
         self.model = dict(model)
         if schedule_blob is not None:
             self.h = mk.mk_schedule_load(schedule_blob)
         else:
-            if not (_TILING_KEYS & set(opts)):
-                from .autotune import tuned_opts
-                n_wg = opts.get("n_workgroups") or torch.cuda.get_device_properties(self.device).multi_processor_count
-                opts = {**tuned_opts(model, n_wg, opts.get("weight_bits", 16)), **opts}
             self.h = mk.mk_build_schedule(mk.make_config(model, device_id=self.device.index or 0, **opts))
         self.stats = mk.mk_get_stats(self.h)
         self.workspace = torch.empty(mk.mk_workspace_bytes(self.h), dtype=torch.uint8, device=self.device)
@@ -71,9 +63,9 @@ class Decoder:
         return _dev_bits(host, self.device)
 
     def step(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor, logits: torch.Tensor,
-             per_op: bool = False) -> None:
+             per_op: bool = False, stream=None) -> None:
         fn = mk.mk_decode_step_per_op if per_op else mk.mk_decode_step
-        fn(self.h, tokens, positions, kv, logits, int(tokens.numel()))
+        fn(self.h, tokens, positions, kv, logits, int(tokens.numel()), stream)
 
     def greedy(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor, logits: torch.Tensor,
                n_steps: int) -> torch.Tensor:

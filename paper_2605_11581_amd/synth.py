@@ -43,6 +43,12 @@ CONFIGS: Dict[str, Dict] = {
                   intermediate=18944, vocab=152064, qkv_bias=1, qk_norm=0, tie_embeddings=0,
                   rope_theta=1e6, rms_eps=1e-6, max_batch=8, max_context=8320,
                   ctx0=8192, steps=128, index=4),
+    # The paper's own fixed workload (Sec. 5.2: 64-token prompts, 12 generated tokens, batch 1..16) on the
+    # second model it measures (Sec. 5.1: Qwen3-1.7B; public dimensions, random-init weights here).
+    "c5_1p7b": dict(n_layers=28, hidden=2048, n_q_heads=16, n_kv_heads=8, head_dim=128,
+                    intermediate=6144, vocab=151936, qkv_bias=0, qk_norm=1, tie_embeddings=1,
+                    rope_theta=1e6, rms_eps=1e-6, max_batch=16, max_context=128,
+                    ctx0=64, steps=12, index=5),
 }
 
 MODEL_KEYS = ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "intermediate", "vocab",

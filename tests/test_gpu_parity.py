@@ -459,11 +459,11 @@ def _weights_of(name):
     return _WEIGHTS[name]
 
 
-def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, w4=False, **opts):
+def _teacher_forced(name, steps_idx, tol=TIGHT, batch=1, w4=False, ctx0=None, **opts):
     full = synth.CONFIGS[name]
-    cfg = synth.model_cfg(full, max_batch=batch)
+    ctx0 = full["ctx0"] if ctx0 is None else ctx0
+    cfg = synth.model_cfg(full, max_batch=batch, max_context=max(full["max_context"], ctx0 + max(steps_idx) + 2))
     w = _weights_of(name)
-    ctx0 = full["ctx0"]
     kv_h = synth.make_kv_fill(cfg, ctx0, seed=synth.seed_of(full), batch=batch)
     if w4:
         pr = PairW4(cfg, w, synth.make_quant(full), **opts)
@@ -518,3 +518,31 @@ def test_c4_7b_shape(batch):
     _teacher_forced("c4_7b", (0,), batch=batch, tol=TIGHT if batch == 1 else 1e-3)
     if batch == 8:
         _WEIGHTS.clear()
+
+
+@pytest.mark.parametrize("name,batch", [("c5_1p7b", 1), ("c5_1p7b", 16), ("c2_1p5b", 16), ("c2_1p5b", 2)])
+def test_short_context_batch_sweep_workload(name, batch):
+    """The paper's fixed workload (Sec. 5.2: 64-token prompts, 12 generated tokens, batch 1..16) on the two
+    model shapes it measures (Sec. 5.1): first and last of the 12 steps, teacher-forced.  Batch 16 takes two
+    matrix-core instructions per weight chunk (sequences 0..7 and 8..15)."""
+    _teacher_forced(name, (0, 11), batch=batch, ctx0=64, tol=TIGHT if batch == 1 else 1e-3)
+    _WEIGHTS.clear()
+
+
+def test_profile_guided_search_walk_keeps_parity():
+    """The on-device tiling search (Sec. 4.2.2 Step 4: candidates scored by profiling): a two-parameter walk
+    on the tiny shape times every candidate through the C ABI, accepts only candidates whose logits agree
+    with the starting schedule's, and its winner matches the oracle."""
+    from paper_2605_11581_amd import autotune
+    from paper_2605_11581_amd.runtime import stage_weights
+    full = tiny()
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full)
+    space = [("attn_chunks", [1, 2, 4]), ("fuse_combine", [0, 1])]
+    best, ms, hist = autotune.autotune(cfg, stage_weights(w, DEV), position=100, device=DEV, steps=6, warmup=2, rounds=1,
+                                       space=space, log=say)
+    assert ms is not None and ms > 0 and len(hist) >= 4
+    assert set(best) == {"attn_chunks", "fuse_combine"}
+    assert all(m is not None for _, m in hist), "a candidate of this space was infeasible or lost parity"
+    worst = run_greedy(full, 4, 60, weights=w, **best)
+    say("winner", best, f"{ms:.4f} ms/step, worst rel err {worst:.2e}")
