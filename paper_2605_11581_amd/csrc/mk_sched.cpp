@@ -163,7 +163,7 @@ struct LdsBudget {
 // its heads, the K/V rows are read once more (they are small next to the weights).
 static int att_head_splits(const Dims &d, const Tiling &t, int n_wg)
 {
-    if (t.fuse || d.G < 2) return 1;
+    if (d.G < 2) return 1;
     const int64_t base = (int64_t)d.Bm * d.nkv * t.nc;   // tasks without a head split
     return (int)std::max<int64_t>(1, std::min<int64_t>(d.G, n_wg / base));
 }
