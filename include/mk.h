@@ -74,7 +74,9 @@ typedef struct mk_config {
     int32_t weight_bits;     /* 16 (or 0): bf16 matrices.  4: the seven decoder projections are W4A16 (Sec. 4.3.2):
                               * unsigned 4-bit codes q, two per byte along K (even k in the low nibble), and one bf16
                               * scale s per (row, group_size consecutive k): w = (q - 8) * s.  Embedding and LM head
-                              * stay bf16.  W4 needs max_batch == 1 and no page ring in this version.              */
+                              * stay bf16.  max_batch 1: VALU form (codes dequantised in registers) unless use_mfma = 1;
+                              * max_batch 2..8: matrix-core form (codes expanded to bf16 in registers, 16 rows per chunk).
+                              * No page ring with W4.                                                              */
     int32_t group_size;      /* W4: 32, 64 or 128 (0 = 128); must divide hidden, n_q_heads*head_dim, intermediate  */
     uint32_t spin_limit;     /* dependency-wait poll limit; 0 = library default      */
     uint32_t flags;          /* MK_F_*                                               */

@@ -41,19 +41,22 @@ walk_fn walk_kernel(const mk_schedule *s, int n_steps)
 {
     if (s->tl.ring_pages) return mk_megakernel_ring;
     const bool multi = n_steps > 1;
+    if (s->dm.w4 && s->tl.mfma) return multi ? mk_megakernel_steps_w4m : mk_megakernel_w4m;
     if (s->dm.w4) return multi ? mk_megakernel_steps_w4 : mk_megakernel_w4;
     if (s->tl.mfma) return multi ? mk_megakernel_steps_mfma : mk_megakernel_mfma;
     return multi ? mk_megakernel_steps : mk_megakernel;
 }
 walk_fn op_kernel(const mk_schedule *s)
 {
-    return s->dm.w4 ? mk_op_kernel_w4 : s->tl.mfma ? mk_op_kernel_mfma : mk_op_kernel;
+    if (s->dm.w4) return s->tl.mfma ? mk_op_kernel_w4m : mk_op_kernel_w4;
+    return s->tl.mfma ? mk_op_kernel_mfma : mk_op_kernel;
 }
 std::vector<const void *> all_walk_kernels()
 {
     return {(const void *)mk_megakernel, (const void *)mk_megakernel_steps, (const void *)mk_op_kernel,
             (const void *)mk_megakernel_mfma, (const void *)mk_megakernel_steps_mfma, (const void *)mk_op_kernel_mfma,
             (const void *)mk_megakernel_w4, (const void *)mk_megakernel_steps_w4, (const void *)mk_op_kernel_w4,
+            (const void *)mk_megakernel_w4m, (const void *)mk_megakernel_steps_w4m, (const void *)mk_op_kernel_w4m,
             (const void *)mk_megakernel_ring};
 }
 
@@ -326,7 +329,7 @@ static int repack(const void *src, int n_rows, int n_cols, mk_schedule *s, uint3
     if (m.w4) {
         if (!scales) { mk::set_error("mk_load_weights: weight_bits is 4 but a scale pointer is NULL"); return MK_EINVAL; }
         hipLaunchKernelGGL(mk_repack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t *)src,
-                           n_rows, n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups);
+                           n_rows, n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups, (uint32_t)(s->tl.mfma ? 1 : 0));
         HIP_TRY(hipGetLastError());
         const uint32_t spc = 2048u / (uint32_t)s->dm.group;
         const size_t n_s = (size_t)n_groups * m.kbt * spc;

@@ -24,6 +24,7 @@ namespace mk {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct LdsPlan {
     uint32_t red_bytes;   // cross-wave reduction region
@@ -530,9 +531,36 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
     const int nterm = nterm_of(P.max_batch);
     const uint32_t pro = instr_pro(I), n_parts = instr_nparts(I);
 
+    // Matrix-core W4 tasks: behind the planes, per plane, the sums of every 32 consecutive staged bf16 values (the
+    // zero point of a group of codes is 136 times the sum of the group's staged values: codes enter the matrix cores
+    // as the bf16 numbers 128 + q).  Summed from the rounded plane values, so that it cancels exactly what the
+    // products carry.
+    auto plane_sums = [&]() {
+        if (!(MFMA && (I.flags & F_W4))) return;
+        const bool nk = (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM);
+        const uint32_t ks = nk ? (uint32_t)P.hidden : I.xs_hi * instr_ck(I);
+        const uint32_t pstride = ks * 2u + 16u, nblk = ks / 32u, ncol = (uint32_t)(batch * nterm);
+        float *xsum = (float *)(xs + (size_t)(P.max_batch * nterm) * pstride);
+        for (uint32_t e = tid; e < ncol * nblk; e += kWgThreads) {
+            const uint32_t col = e / nblk, blk = e - col * nblk;
+            const u32x4 *xp = (const u32x4 *)(xs + (size_t)col * pstride + (size_t)blk * 64);
+            u32x4 xv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xv[i] = xp[i];
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a += bf_lo(xv[i].x); a += bf_hi(xv[i].x); a += bf_lo(xv[i].y); a += bf_hi(xv[i].y);
+                a += bf_lo(xv[i].z); a += bf_hi(xv[i].z); a += bf_lo(xv[i].w); a += bf_hi(xv[i].w);
+            }
+            xsum[e] = a;
+        }
+        wg_sync(lp, lds);
+    };
     if constexpr (MFMA) {
         if (batch > 1 && gemv_prologue_batched(P, I, lds, lp, batch)) {
             wg_sync(lp, lds);
+            plane_sums();
             return;
         }
     }
@@ -729,6 +757,7 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
         }
     }
     wg_sync(lp, lds);
+    plane_sums();
     if (!MFMA && (I.flags & F_W4)) {
         // W4: sums of every 32 consecutive staged values, behind the vector (the zero-point term of a
         // lane's 32 codes is 8 times such a sum)
@@ -857,6 +886,7 @@ __device__ __forceinline__ void ring_fill_stage(const Params &P, Wg &wg)
 // loads in flight cover); the scales that go with them are packed four to a slot behind the chunks.
 constexpr int kPrefetchW4 = 12;
 constexpr int kW4Slots = kPrefetchW4 + (kPrefetchW4 + 3) / 4;
+
 constexpr int kBufSlots = kPrefetch > kW4Slots ? kPrefetch : kW4Slots;
 
 struct GemvStream {
@@ -865,6 +895,9 @@ struct GemvStream {
     u32x4 buf[kBufSlots]; // direct-load path only: bf16 tasks use the first kPrefetch slots, W4 tasks kPrefetchW4 + scales
     const __attribute__((address_space(1))) uint16_t *sp;   // W4: this lane's scale of chunk 0 of the task
     uint32_t spc;                                            // W4: scales per chunk (2048 / group)
+    // matrix-core W4 path: the scales of rows 4 ksub .. 4 ksub + 3 (four bf16 = 8 bytes) of each group of a chunk,
+    // up to four groups (group size 32), fetched with the chunk
+    u32x2 sbuf[kPrefetch][4];
 };
 __device__ __forceinline__ uint32_t w4_scale_get(const GemvStream &st, int j) { return st.buf[kPrefetchW4 + (j >> 2)][j & 3]; }
 __device__ __forceinline__ void w4_scale_set(GemvStream &st, int j, uint32_t v) { st.buf[kPrefetchW4 + (j >> 2)][j & 3] = v; }
@@ -891,6 +924,21 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
         st.sp = (const __attribute__((address_space(1))) uint16_t *)(uintptr_t)(P.ws + P.lay.wscale) +
                 ((size_t)I.w_chunk + first) * st.spc + sidx;
     }
+    if (w4 && (I.flags & F_MFMA)) {
+        // matrix-core form: 16 rows x 128 k per chunk; this lane's scales are rows 4 ksub .. + 3 of every group
+        st.sp = (const __attribute__((address_space(1))) uint16_t *)(uintptr_t)(P.ws + P.lay.wscale) +
+                ((size_t)I.w_chunk + first) * st.spc + 4u * ((uint32_t)lane >> 4);
+        const uint32_t ngrp = 128u / P.w4_group;
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j) {
+            const uint32_t idx = min((uint32_t)wave + (uint32_t)j * kWaves, last);
+            st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)idx * 64);
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                if ((uint32_t)g < ngrp) st.sbuf[j][g] = *(const __attribute__((address_space(1))) u32x2 *)(st.sp + (size_t)idx * st.spc + g * 16);
+        }
+        return;
+    }
     if (w4) {
 #pragma unroll
         for (int j = 0; j < kPrefetchW4; ++j) {
@@ -915,7 +963,7 @@ __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, Gemv
 template <bool MFMA, bool RING, bool W4 = false>
 __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char *lds, Wg &lp, GemvStream &st, int batch)
 {
-    static_assert(!(W4 && (MFMA || RING)), "W4 weights: VALU path with direct loads only");
+    static_assert(!(W4 && RING), "W4 weights: direct loads only");
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     const uint32_t rlog = instr_rlog(I), R = 1u << rlog, ck = W4 ? chunk_k_w4(rlog) : chunk_k(rlog);
     const int ksub = lane >> rlog;
@@ -977,6 +1025,57 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             cacc = f32x4{0.f, 0.f, 0.f, 0.f};
             cacc2 = f32x4{0.f, 0.f, 0.f, 0.f};
         }
+    };
+
+    // Matrix-core W4: one chunk = 16 rows x 128 k of codes.  Dword i of a lane holds the 8 codes of row lane % 16 for
+    // k = 32 i + 8 ksub .. + 8, nibble p standing for k offset 2 (p % 4) + p / 4, so that (d >> 4 j) & 0x000f000f is the
+    // pair (k 2j, k 2j + 1); OR-ing 0x4300 into each half makes the bf16 numbers 128 + q.  Four matrix-core
+    // instructions per chunk; after the last one of a scale group the raw sums lose the zero point (136 times the
+    // sum of the group's staged values, per column) and gain the scale.
+    auto consume_w4m = [&](const u32x4 &w, const u32x2 (&sc)[4]) {
+        while (kbi >= cur_n) {
+            kbi -= cur_n;
+            flush();
+            ++ul;
+            cur_n = unit_nkb(u0 + ul, S, nkb, kbt);
+            cur_kb0 = ((u0 + ul) % S) * nkb;
+        }
+        const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;
+        const int col = lane & 15;
+        const bool live = col < ncols;
+        const char *xk = xs + (size_t)col * plane_stride + ((size_t)kb_rel * 128u + (uint32_t)ksub * 8u) * 2u;
+        const float *xsum = (const float *)(xs + (size_t)(P.max_batch * nterm) * plane_stride) + (size_t)col * (k_stage / 32u) + kb_rel * 4u;
+        const uint32_t dw[4] = {w.x, w.y, w.z, w.w};
+        const uint32_t group = P.w4_group;
+        u32x4 xb[4];
+        float zs[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {          // all LDS reads of the chunk first
+            xb[i] = live ? *(const u32x4 *)(xk + i * 64) : u32x4{0u, 0u, 0u, 0u};
+            zs[i] = live ? xsum[i] : 0.f;
+        }
+        f32x4 cg = {0.f, 0.f, 0.f, 0.f};
+        float z = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t d = dw[i];
+            u32x4 av;
+            av.x = (d & 0x000f000fu) | 0x43004300u;
+            av.y = ((d >> 4) & 0x000f000fu) | 0x43004300u;
+            av.z = ((d >> 8) & 0x000f000fu) | 0x43004300u;
+            av.w = ((d >> 12) & 0x000f000fu) | 0x43004300u;
+            cg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, xb[i]), cg, 0, 0, 0);
+            z += zs[i];
+            if (((uint32_t)(i + 1) * 32u) % group == 0u) {     // (wave-uniform) a scale group ends here
+                const u32x2 sv = group == 32u ? sc[i] : group == 64u ? sc[i / 2] : sc[0];   // (static indices: the slots stay in registers)
+                const float zp = 136.0f * z;
+                cacc[0] += bf_lo(sv.x) * (cg[0] - zp); cacc[1] += bf_hi(sv.x) * (cg[1] - zp);
+                cacc[2] += bf_lo(sv.y) * (cg[2] - zp); cacc[3] += bf_hi(sv.y) * (cg[3] - zp);
+                cg = f32x4{0.f, 0.f, 0.f, 0.f};
+                z = 0.f;
+            }
+        }
+        kbi += kWaves;
     };
 
     auto consume = [&](const u32x4 &w, uint32_t sbits = 0) {
@@ -1091,6 +1190,29 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
         for (uint32_t g = 0; g < ng; g += 2) {
             step(w0, w1, g);
             step(w1, w0, g + 1);
+        }
+    } else if (W4 && MFMA) {
+        if (total) {
+            const uint32_t last = total - 1, ngrp = 128u / P.w4_group;
+            constexpr uint32_t round = (uint32_t)kPrefetch * kWaves;
+            uint32_t base = 0;
+            for (; base + round < total; base += round) {
+#pragma unroll
+                for (int j = 0; j < kPrefetch; ++j) {
+                    const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+                    consume_w4m(st.buf[j], st.sbuf[j]);
+                    const uint32_t nidx = min(idx + round, last);
+                    st.buf[j] = __builtin_nontemporal_load(st.wp + (size_t)nidx * 64);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        if ((uint32_t)g < ngrp) st.sbuf[j][g] = *(const __attribute__((address_space(1))) u32x2 *)(st.sp + (size_t)nidx * st.spc + g * 16);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) {
+                const uint32_t idx = base + (uint32_t)j * kWaves + (uint32_t)wave;
+                if (idx < total) consume_w4m(st.buf[j], st.sbuf[j]);
+            }
         }
     } else if (W4) {
         // Rounds of kPrefetchW4 slots per wave: a slot is consumed, then refilled with the chunk one round
@@ -1679,6 +1801,7 @@ enum Path : int {
     kPathMfma = 1,    // bf16 weights, matrix cores (any batch)
     kPathW4 = 2,      // 4-bit decoder projections (VALU), bf16 LM head
     kPathAny16 = 3,   // bf16 weights, VALU or matrix cores by the instruction's flag
+    kPathW4M = 4,     // 4-bit decoder projections and bf16 LM head, both on the matrix cores (any batch)
 };
 
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
@@ -1698,7 +1821,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     // and an arg-max task whose result nobody takes only has to signal.
     const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens);
     const bool waiting = PERSISTENT && !dead && !no_dep;
-    constexpr bool W4 = PATH == kPathW4;
+    constexpr bool W4 = PATH == kPathW4 || PATH == kPathW4M;
     uint64_t t2 = 0;
 
     // The dependency wait of the task; called once, after the task's prefetch has been issued.
@@ -1739,10 +1862,11 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         gemv_issue<RING, W4>(P, I, st, lp.npf);
         if (PERSISTENT) trace_mark(P, pc, 0);
         await();
-        if (PATH == kPathMfma || (PATH == kPathAny16 && (I.flags & F_MFMA))) {
+        if (PATH == kPathMfma || PATH == kPathW4M || (PATH == kPathAny16 && (I.flags & F_MFMA))) {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<true>(P, I, lds, lp, P.batch);
             if (tracing && tid == 0) t2 = wall_clock64();
-            gemv_main<true, RING>(P, I, lds, lp, st, P.batch);
+            if (PATH == kPathW4M && (I.flags & F_W4)) gemv_main<true, false, true>(P, I, lds, lp, st, P.batch);
+            else gemv_main<true, RING>(P, I, lds, lp, st, P.batch);
         } else {
             if (!(I.flags & F_SKIP_PRO)) gemv_prologue<false>(P, I, lds, lp, 1);
             if (tracing && tid == 0) t2 = wall_clock64();
@@ -1892,6 +2016,9 @@ MK_KERNEL(mk_op_kernel_mfma, (mk::run_one_op<mk::kPathMfma>(P, lp)))
 MK_KERNEL(mk_megakernel_w4, (mk::run_persistent<false, false, mk::kPathW4>(P, lp)))
 MK_KERNEL(mk_megakernel_steps_w4, (mk::run_persistent<false, true, mk::kPathW4>(P, lp)))
 MK_KERNEL(mk_op_kernel_w4, (mk::run_one_op<mk::kPathW4>(P, lp)))
+MK_KERNEL(mk_megakernel_w4m, (mk::run_persistent<false, false, mk::kPathW4M>(P, lp)))
+MK_KERNEL(mk_megakernel_steps_w4m, (mk::run_persistent<false, true, mk::kPathW4M>(P, lp)))
+MK_KERNEL(mk_op_kernel_w4m, (mk::run_one_op<mk::kPathW4M>(P, lp)))
 // Any step count, with the per-wave LDS page ring carrying the weight stream (bf16, either GEMV body).
 MK_KERNEL(mk_megakernel_ring, (mk::run_persistent<true, true, mk::kPathAny16>(P, lp)))
 
@@ -1931,8 +2058,11 @@ extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int
 // -> chunks of R rows x 2048/R k; lane = ksub * R + r takes the 16 bytes holding k0 + 32 ksub .. + 32 of
 // its row.  Same row-group placement rules as mk_repack_kernel; rows and columns beyond the source are
 // code 8 (weight zero).
+// With `mfma` (16 rows per chunk) the codes are laid out for the matrix cores instead: dword i of lane ksub * 16 + r
+// holds the 8 codes of k0 + 32 i + 8 ksub .. + 8, nibble p standing for offset 2 (p % 4) + p / 4 inside those 8.
 extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, int n_cols, mk::u32x4 *dst, uint32_t kbt,
-                                               uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups)
+                                               uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups,
+                                               uint32_t mfma)
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n_groups * kbt * 64;
@@ -1946,6 +2076,26 @@ extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, i
     long row = (long)grp * rpu + (r - r_off);
     const int k0 = (int)(kb * ck + ksub * 32);
     uint32_t d[4];
+    if (mfma) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int k = (int)(kb * ck) + 32 * i + 8 * (int)ksub + 2 * (p % 4) + p / 4;
+                uint32_t code = 8u;                                  // absent rows / columns: weight zero
+                if (row < n_rows && k < n_cols) {
+                    const uint32_t byte = src[(size_t)row * (n_cols / 2) + k / 2];
+                    code = (k & 1) ? (byte >> 4) : (byte & 15u);
+                }
+                v |= code << (4 * p);
+            }
+            d[i] = v;
+        }
+        mk::u32x4 v4 = {d[0], d[1], d[2], d[3]};
+        dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v4;
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         uint32_t v = 0;

@@ -350,9 +350,16 @@ class PairW4(Pair):
 
 
 @pytest.mark.parametrize("opts", [
-    dict(), dict(group=64), dict(group=32, qkv_bias=1), dict(chunk_rows=16), dict(chunk_rows=16, split_o=2, split_down=2),
-    dict(rows_gateup=16, split_gateup=2, split_qkv=2, attn_chunks=4), dict(n_workgroups=36, rows_down=4, rows_o=8),
-    dict(fuse_combine=1, attn_chunks=4), dict(fuse_combine=1, rows_o=16, split_o=2),
+    # VALU form (batch 1): a lane dequantises its 32 codes in registers
+    dict(use_mfma=0), dict(use_mfma=0, group=64), dict(use_mfma=0, group=32, qkv_bias=1), dict(use_mfma=0, chunk_rows=16),
+    dict(use_mfma=0, chunk_rows=16, split_o=2, split_down=2),
+    dict(use_mfma=0, rows_gateup=16, split_gateup=2, split_qkv=2, attn_chunks=4), dict(use_mfma=0, n_workgroups=36, rows_down=4, rows_o=8),
+    dict(use_mfma=0, fuse_combine=1, attn_chunks=4), dict(use_mfma=0, fuse_combine=1, rows_o=16, split_o=2),
+    dict(),
+    # matrix-core form (the default at batch > 1): codes expanded to bf16 numbers 128 + q, four instructions per chunk
+    dict(use_mfma=1), dict(use_mfma=1, group=64), dict(use_mfma=1, group=32, qkv_bias=1), dict(use_mfma=1, split_o=2, split_down=2),
+    dict(use_mfma=1, split_gateup=2, split_qkv=2, attn_chunks=4), dict(use_mfma=1, n_workgroups=36),
+    dict(use_mfma=1, fuse_combine=1, attn_chunks=4),
 ], ids=lambda o: ",".join(f"{k}={v}" for k, v in o.items()) or "default")
 def test_w4_c0_greedy_steps_match_oracle(opts):
     opts = dict(opts)
@@ -389,12 +396,38 @@ def test_w4_c0_greedy_steps_match_oracle(opts):
 
 def test_w4_rejects_what_it_does_not_cover():
     full = tiny(intermediate=640)
-    for bad in (dict(max_batch=2), dict(ring_kb=32), dict(use_mfma=1), dict(group_size=48), dict(intermediate=688)):
+    for bad in (dict(max_batch=9), dict(max_batch=2, use_mfma=0), dict(ring_kb=32), dict(group_size=48), dict(intermediate=688),
+                dict(rows_qkv=8, use_mfma=1)):
         cfg = synth.model_cfg(dict(full, **{k: v for k, v in bad.items() if k in ("max_batch", "intermediate")}))
         opts = {k: v for k, v in bad.items() if k not in ("max_batch", "intermediate")}
         with pytest.raises(mk.MkError) as e:
             mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=64, weight_bits=4, **opts))
         assert e.value.code == mk.MK_EINVAL, bad
+
+
+@pytest.mark.parametrize("group,batch_max,present", [(128, 4, 3), (64, 8, 8), (32, 2, 2)])
+def test_w4_batched_sequences_on_the_matrix_cores(group, batch_max, present):
+    """W4A16 at batch > 1 (the paper measures batch 1..16 in this precision, Sec. 5.2): ragged positions,
+    teacher-forced, every sequence against the oracle."""
+    full = tiny(intermediate=640, qkv_bias=1, index=17)
+    cfg = synth.model_cfg(full, max_batch=batch_max)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    q = synth.make_quant(full, group=group)
+    pr = PairW4(cfg, w, q)
+    assert pr.dec.stats["use_mfma"] == 1
+    pr.kv_h = synth.make_kv_fill(cfg, 50, seed=5, batch=present)
+    pr.kv_d = pr.dec.new_kv(pr.kv_h)
+    rng = np.random.default_rng(11)
+    for s in range(3):
+        toks = rng.integers(0, cfg["vocab"], size=present, dtype=np.int32)
+        poss = [50 - 7 * b + s for b in range(present)]
+        want = pr.orc.step(toks, poss, pr.kv_h)
+        got = pr.gpu_step(toks, poss)
+        for b in range(present):
+            e = rel_err(got[b], want[b])
+            say(f"W4 group {group} batch {present}/{batch_max} step {s} seq {b}: rel err {e:.2e}")
+            assert e <= 1e-3 and int(got[b].argmax()) == oracle.argmax(want[b])
+    pr.close()
 
 
 def test_two_runs_are_bit_identical():

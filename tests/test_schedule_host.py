@@ -90,7 +90,7 @@ def test_fixed_tiling_overrides_are_honoured():
     mk.mk_destroy(h)
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=8), dict(hidden=100), dict(max_batch=9), dict(max_batch=0),
+@pytest.mark.parametrize("bad", [dict(head_dim=8), dict(hidden=100), dict(max_batch=17), dict(max_batch=0),
                                  dict(n_q_heads=3), dict(n_layers=0), dict(max_context=0),
                                  dict(max_batch=2, use_mfma=0), dict(ring_kb=200), dict(ring_kb=8), dict(ring_kb=-3),
                                  dict(split_down=10 ** 6)])
