@@ -298,6 +298,7 @@ def main() -> int:
     ap.add_argument("--opt", action="append", default=[], help="schedule override key=value (e.g. split_down=4)")
     ap.add_argument("--w4", action="store_true", help="W4A16 decoder projections (group 128) instead of bf16")
     ap.add_argument("--context", type=int, default=0, help="KV context at the first step (default: the configuration's)")
+    ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device-to-device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters in profiler runs)")
     ap.add_argument("--all", action="store_true", help="every BASELINE workload, one line each; also written to profiles/results.json")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -308,6 +309,14 @@ def main() -> int:
         k, v = kv.split("=")
         opts[k] = int(v)
     cache: dict = {}
+    if args.calib_copy:
+        import torch
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     if not args.all:
         headline = args.config == "c2_1p5b" and args.batch == 1 and not args.w4 and args.context == 0
         out = run_workload(args.config, args.batch, args.w4, args.steps, max(args.warmup, 1), args.reps, args.context, opts,

@@ -2,7 +2,7 @@
 short text summaries kept under profiles/.
 
     python -m paper_2605_11581_amd.profile_summary stats  <dir> <out.txt> "<command line>"
-    python -m paper_2605_11581_amd.profile_summary pmc    <fetch_dir> <write_dir> <out.txt> "<command lines>"
+    python -m paper_2605_11581_amd.profile_summary pmc    <fetch_dir> <write_dir> <out.txt> "<command lines>" [kernel name]
 
 The counter summary scales FETCH_SIZE and WRITE_SIZE (KiB per dispatch) by what the same counters
 read for the runtime's plain 1 GiB device-to-device copy kernel in the same run.
@@ -68,4 +68,4 @@ if __name__ == "__main__":
     if sys.argv[1] == "stats":
         stats(sys.argv[2], sys.argv[3], sys.argv[4])
     else:
-        pmc(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5])
+        pmc(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], *(sys.argv[6:7]))
