@@ -85,7 +85,10 @@ typedef struct mk_config {
 enum {
     MK_F_TRACE = 1u,         /* record per-task clocks into the trace buffer          */
     MK_F_TIMING = 2u,        /* bracket each step's launch(es) with HIP events         */
-    MK_F_NO_TABLE = 4u       /* mk_build_schedule: ignore the table of recorded profile-guided tilings */
+    MK_F_NO_TABLE = 4u,      /* mk_build_schedule: ignore the table of recorded profile-guided tilings */
+    MK_F_VALU_ATTENTION = 8u /* mk_build_schedule: keep the attention tasks of a matrix-core schedule (max_batch > 1 or
+                              * use_mfma = 1) on the vector ALUs; by default such schedules score and weight blocks of 16
+                              * positions with matrix-core instructions                                           */
 };
 
 typedef struct mk_schedule mk_schedule; /* opaque, library-owned host object */
@@ -117,7 +120,7 @@ typedef struct mk_stats {
     int32_t rows_qkv, rows_o, rows_gateup, rows_down, rows_head;  /* rows per 1 KB weight chunk, per matrix */
     int32_t fuse_combine;
     int32_t from_table;              /* 1: the tiling is the profiled one recorded for this configuration */
-    int32_t reserved;
+    int32_t attention_mfma;          /* 1: the attention tasks run on the matrix cores */
 } mk_stats;
 
 /* Phase I (host only, touches no GPU unless n_workgroups == 0): build the

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("MK_LIB_PATH") or os.path.join(_HERE, "libmk.so")   # override: A/B runs of two builds
 
 MK_OK, MK_EINVAL, MK_ENOMEM, MK_EINFEASIBLE, MK_ESCHED, MK_EHIP, MK_ETIMEOUT, MK_ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
-MK_F_TRACE, MK_F_TIMING, MK_F_NO_TABLE = 1, 2, 4
+MK_F_TRACE, MK_F_TIMING, MK_F_NO_TABLE, MK_F_VALU_ATTENTION = 1, 2, 4, 8
 INSTR_DWORDS = 32
 
 
@@ -54,7 +54,7 @@ class mk_stats(C.Structure):
         ("sim_makespan_us", C.c_double), ("sim_duty_cycle", C.c_double),
         ("candidates_tried", C.c_int32), ("candidates_pruned", C.c_int32)] + [
         (n, C.c_int32) for n in ("rows_qkv", "rows_o", "rows_gateup", "rows_down", "rows_head", "fuse_combine", "from_table",
-                                 "reserved")]
+                                 "attention_mfma")]
 
 
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",

@@ -212,6 +212,7 @@ int mk_get_stats(const mk_schedule *s, mk_stats *o)
     o->candidates_tried = s->cand_tried; o->candidates_pruned = s->cand_pruned;
     o->fuse_combine = s->tl.fuse;
     o->from_table = s->from_table;
+    o->attention_mfma = s->tl.att_mc;
     return MK_OK;
 }
 
@@ -281,8 +282,10 @@ int mk_bind_workspace(mk_schedule *s, void *dev, size_t bytes, void *stream)
             if (l[i].op != mk::OP_GEMV) continue;
             const mk::Instr &I = l[i];
             if (I.S == 0) { mk::set_error("a GEMV task has zero K splits"); return MK_ESCHED; }
-            const uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb, ue = I.u0 + I.nu;
-            const uint32_t total = (ue / I.S) * I.kbt + (ue % I.S) * I.nkb - first;
+            const bool sm = (I.flags & mk::F_SLICE_MAJOR) != 0;
+            const uint32_t groups = mk::instr_groups(I);
+            const uint32_t first = mk::unit_chunk0(sm, I.u0, I.S, groups, I.kbt, I.nkb);
+            const uint32_t total = mk::unit_chunk0(sm, I.u0 + I.nu, I.S, groups, I.kbt, I.nkb) - first;
             if ((uint64_t)I.w_chunk + first + total > s->wm.n_chunks) { mk::set_error("a GEMV task reaches beyond the weight region"); return MK_ESCHED; }
             dst[2 * e] = I.w_chunk + first; dst[2 * e + 1] = total;
             ++e;
@@ -326,22 +329,23 @@ static int repack(const void *src, int n_rows, int n_cols, mk_schedule *s, uint3
     if (!src) { mk::set_error("mk_load_weights: a required matrix pointer is NULL"); return MK_EINVAL; }
     size_t total = (size_t)n_groups * m.kbt * 64;
     mk::u32x4 *dst = (mk::u32x4 *)(s->ws + s->lay.weights) + (size_t)chunk0 * 64;
+    const mk::ChunkOrder ord = {(uint32_t)m.S, (uint32_t)((m.kbt + m.S - 1) / m.S), (uint32_t)m.groups, (uint32_t)m.sm};
     if (m.w4) {
         if (!scales) { mk::set_error("mk_load_weights: weight_bits is 4 but a scale pointer is NULL"); return MK_EINVAL; }
         hipLaunchKernelGGL(mk_repack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t *)src,
-                           n_rows, n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups, (uint32_t)(s->tl.mfma ? 1 : 0));
+                           n_rows, n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups, (uint32_t)(s->tl.mfma ? 1 : 0), ord);
         HIP_TRY(hipGetLastError());
         const uint32_t spc = 2048u / (uint32_t)s->dm.group;
         const size_t n_s = (size_t)n_groups * m.kbt * spc;
         uint16_t *sdst = (uint16_t *)(s->ws + s->lay.wscale) + (size_t)chunk0 * spc;
         hipLaunchKernelGGL(mk_repack_scales_kernel, dim3((unsigned)((n_s + 255) / 256)), dim3(256), 0, st,
                            (const uint16_t *)scales, n_rows, n_cols, sdst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0,
-                           n_groups, (uint32_t)s->dm.group);
+                           n_groups, (uint32_t)s->dm.group, ord);
         HIP_TRY(hipGetLastError());
         return MK_OK;
     }
     hipLaunchKernelGGL(mk_repack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t *)src, n_rows,
-                       n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups);
+                       n_cols, dst, (uint32_t)m.kbt, (uint32_t)m.rlog, rpu, r_off, g0, n_groups, ord);
     HIP_TRY(hipGetLastError());
     return MK_OK;
 }

@@ -66,7 +66,9 @@ enum Flags : uint32_t {
     F_ARGMAX = 32u,     // LM-head task: also leave (max logit, its row) per sequence in partial slot `spare`
     F_WAIT_PREV = 64u,  // wait_ctr[0] is awaited at the PREVIOUS step's target: the first tasks of a step wait
                         // for the greedy token (and with it for every task) of the step before
-    F_W4 = 128u         // the matrix is stored as 4-bit codes: a chunk holds four times the k of a bf16 chunk
+    F_W4 = 128u,        // the matrix is stored as 4-bit codes: a chunk holds four times the k of a bf16 chunk
+    F_SLICE_MAJOR = 256u, // units (and the matrix's chunks) are numbered K slice first: see unit_place()
+    F_ATT_MC = 512u      // attention task: scores and weighted values on the matrix cores (blocks of 16 positions per wavefront)
 };
 
 // Weight chunk geometry.  A chunk is one wavefront-wide 128-bit load (1 KB): R rows x (512 / R)
@@ -86,7 +88,8 @@ struct Instr {                 // 32 dwords
     uint32_t wait_ctr[2];      // 4,5   counter index or kNone
     uint32_t wait_cnt[2];      // 6,7   signals per step the counter receives
     uint32_t sig_ctr;          // 8     counter to signal once the outputs are stored (kNone: none)
-    // ---- GEMV: units u0 .. u0+nu of a matrix; unit u = (row group u / S of R rows, K split u % S)
+    // ---- GEMV: units u0 .. u0+nu of a matrix; unit u = (row group u / S of R rows, K split u % S), or with
+    //      F_SLICE_MAJOR (K split u / groups, row group u % groups)
     uint32_t w_chunk;          // 9   first 1 KB chunk of the matrix inside the weight region
     uint32_t kbt;              // 10  chunks per row group (whole K)
     uint32_t nkb;              // 11  chunks per unit (last split of a row group may be shorter)
@@ -116,6 +119,41 @@ __host__ __device__ inline uint32_t instr_ck(const Instr &I) { return ((I.flags 
 __host__ __device__ inline uint32_t instr_rlog(const Instr &I) { return (I.cfg >> 4) & 15u; }
 __host__ __device__ inline uint32_t instr_prod_rlog(const Instr &I) { return (I.cfg >> 8) & 15u; }
 __host__ __device__ inline uint32_t instr_nparts(const Instr &I) { return (I.cfg >> 16) & 255u; }
+__host__ __device__ inline uint32_t instr_groups(const Instr &I) { return (I.n_rows + (1u << instr_rlog(I)) - 1u) >> instr_rlog(I); }
+
+// Unit numbering and chunk order of a matrix cut into S K slices of nkb chunks (the last slice may be shorter) over
+// `groups` row groups of kbt chunks each.  Row-group-major (sm = false): unit u = rg * S + s, the chunks of a row group
+// are contiguous along K.  Slice-major (sm = true): unit u = s * groups + rg, and the chunks of a slice come first for
+// every row group: a run of consecutive units then shares its K range (one staged input slice) AND is one contiguous
+// byte range of weights.
+__host__ __device__ inline uint32_t slice_chunks(uint32_t s, uint32_t S, uint32_t nkb, uint32_t kbt)
+{
+    return s + 1u == S ? kbt - s * nkb : nkb;
+}
+__host__ __device__ inline void unit_place(bool sm, uint32_t u, uint32_t S, uint32_t groups, uint32_t &rg, uint32_t &s)
+{
+    if (sm) { s = u / groups; rg = u - s * groups; }
+    else    { rg = u / S; s = u - rg * S; }
+}
+// first chunk of unit u, relative to the matrix (u may be one past the last unit)
+__host__ __device__ inline uint32_t unit_chunk0(bool sm, uint32_t u, uint32_t S, uint32_t groups, uint32_t kbt, uint32_t nkb)
+{
+    uint32_t rg, s;
+    unit_place(sm, u, S, groups, rg, s);
+    if (!sm) return rg * kbt + s * nkb;
+    if (s >= S) return groups * kbt;
+    return groups * s * nkb + rg * slice_chunks(s, S, nkb, kbt);
+}
+// where chunk kb of row group grp is stored, relative to the matrix
+__host__ __device__ inline uint32_t chunk_slot(bool sm, uint32_t grp, uint32_t kb, uint32_t S, uint32_t groups, uint32_t kbt,
+                                               uint32_t nkb)
+{
+    if (!sm) return grp * kbt + kb;
+    uint32_t s = kb / nkb;
+    if (s >= S) s = S - 1u;
+    return groups * s * nkb + grp * slice_chunks(s, S, nkb, kbt) + (kb - s * nkb);
+}
+struct ChunkOrder { uint32_t S, nkb, groups, sm; };   // how the offline reorder numbers the chunks of one matrix
 __host__ __device__ inline uint32_t make_cfg(uint32_t pro, uint32_t rlog, uint32_t prod_rlog, uint32_t n_parts)
 {
     return pro | (rlog << 4) | (prod_rlog << 8) | (n_parts << 16);

@@ -778,12 +778,15 @@ __device__ __forceinline__ void gemv_prologue(const Params &P, const Instr &I, c
     }
 }
 
-// chunks in unit u of a matrix with S splits of nkb chunks per row group (last split ragged)
-__device__ __forceinline__ uint32_t unit_nkb(uint32_t u, uint32_t S, uint32_t nkb, uint32_t kbt)
-{
-    uint32_t s = u % S;
-    return (s == S - 1) ? kbt - s * nkb : nkb;
-}
+// Cursor over the units of a GEMV task in list order: (row group, K slice) of the current unit.
+struct UnitCursor {
+    uint32_t rg, s;
+    __device__ __forceinline__ void next(bool sm, uint32_t S, uint32_t groups)
+    {
+        if (sm) { if (++rg == groups) { rg = 0; ++s; } }
+        else    { if (++s == S) { s = 0; ++rg; } }
+    }
+};
 
 // ---- weight-page ring ------------------------------------------------------------------------
 // Wait until at most 4 * k4 vector-memory operations of this wave are outstanding (k4 is clamped
@@ -908,9 +911,10 @@ template <bool RING, bool W4>
 __device__ __forceinline__ void gemv_issue(const Params &P, const Instr &I, GemvStream &st, int npf)
 {
     const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
-    uint32_t first = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb;
-    uint32_t ulast = I.u0 + I.nu;  // one past the last unit
-    uint32_t end = (ulast / I.S) * I.kbt + (ulast % I.S) * I.nkb;
+    const bool sm = (I.flags & F_SLICE_MAJOR) != 0;
+    const uint32_t groups = instr_groups(I);
+    const uint32_t first = unit_chunk0(sm, I.u0, I.S, groups, I.kbt, I.nkb);
+    const uint32_t end = unit_chunk0(sm, I.u0 + I.nu, I.S, groups, I.kbt, I.nkb);   // (one past the last unit)
     st.total = end - first;
     if (RING) return;
     st.wp = (const __attribute__((address_space(1))) u32x4 *)(uintptr_t)(P.ws + P.lay.weights) + ((size_t)I.w_chunk + first) * 64 + lane;
@@ -982,8 +986,12 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
 
     // running position of this wave inside the task: unit ul, chunk kbi within the unit
     uint32_t ul = 0, kbi = (uint32_t)wave;
-    uint32_t cur_n = unit_nkb(u0, S, nkb, kbt);
-    uint32_t cur_kb0 = (u0 % S) * nkb;  // first chunk of the current unit inside its row group
+    const bool sm = (I.flags & F_SLICE_MAJOR) != 0;
+    const uint32_t groups = instr_groups(I);
+    UnitCursor cur;
+    unit_place(sm, u0, S, groups, cur.rg, cur.s);
+    uint32_t cur_n = slice_chunks(cur.s, S, nkb, kbt);
+    uint32_t cur_kb0 = cur.s * nkb;  // first chunk of the current unit inside its row group
 
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     f32x4 cacc = {0.f, 0.f, 0.f, 0.f};    // matrix-core path: columns 0..15 (sequences 0..7, two terms each)
@@ -1037,8 +1045,9 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             kbi -= cur_n;
             flush();
             ++ul;
-            cur_n = unit_nkb(u0 + ul, S, nkb, kbt);
-            cur_kb0 = ((u0 + ul) % S) * nkb;
+            cur.next(sm, S, groups);
+            cur_n = slice_chunks(cur.s, S, nkb, kbt);
+            cur_kb0 = cur.s * nkb;
         }
         const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;
         const int col = lane & 15;
@@ -1084,8 +1093,9 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             kbi -= cur_n;
             flush();
             ++ul;
-            cur_n = unit_nkb(u0 + ul, S, nkb, kbt);
-            cur_kb0 = ((u0 + ul) % S) * nkb;
+            cur.next(sm, S, groups);
+            cur_n = slice_chunks(cur.s, S, nkb, kbt);
+            cur_kb0 = cur.s * nkb;
         }
         const uint32_t kb_rel = cur_kb0 + kbi - x_kb0;  // chunk inside the staged vector
         if (W4) {
@@ -1135,14 +1145,19 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
     float resid0 = 0.f;
     if (!MFMA && (I.flags & F_ADD_RESID) && (uint32_t)tid < red_per_wave) {
         const uint32_t ub = (uint32_t)tid >> rlog, uu = u0 + ub;
-        resid0 = ld_act((const float *)(P.scr + P.lay.act) + I.resid + (size_t)(uu / S) * R + ((uint32_t)tid & (R - 1)));
+        uint32_t rg, s;
+        unit_place(sm, uu, S, groups, rg, s);
+        resid0 = ld_act((const float *)(P.scr + P.lay.act) + I.resid + (size_t)rg * R + ((uint32_t)tid & (R - 1)));
     }
     // Likewise the bias of this thread's first output (a constant).
     float bias0 = 0.f;
     if (I.bias != kNone && (uint32_t)tid < red_per_wave) {
         const uint32_t nb0 = (uint32_t)(MFMA ? batch : 1);
-        const uint32_t uu = u0 + ((uint32_t)tid >> rlog) / nb0, row = (uu / S) * R + ((uint32_t)tid & (R - 1));
-        if (uu % S == 0 && row < I.n_rows) bias0 = bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
+        const uint32_t uu = u0 + ((uint32_t)tid >> rlog) / nb0;
+        uint32_t rg, s;
+        unit_place(sm, uu, S, groups, rg, s);
+        const uint32_t row = rg * R + ((uint32_t)tid & (R - 1));
+        if (s == 0 && row < I.n_rows) bias0 = bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
     }
     const uint32_t total = st.total;
     if (RING) {
@@ -1301,7 +1316,8 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
             float v = rsum(t);
             uint32_t r = t & (R - 1), ub = t >> rlog;
             uint32_t b = ub % nb, uu = u0 + ub / nb;
-            uint32_t rg = uu / S, s = uu % S;
+            uint32_t rg, s;
+            unit_place(sm, uu, S, groups, rg, s);
             uint32_t row = rg * R + r;
             if (I.bias != kNone && s == 0 && row < I.n_rows)
                 v += t == (uint32_t)tid ? bias0 : bf_to_f(((const uint16_t *)(P.ws + P.lay.vecs))[I.bias + row]);
@@ -1327,7 +1343,7 @@ __device__ __forceinline__ void gemv_main(const Params &P, const Instr &I, char 
                     const uint32_t ub = t >> rlog;
                     if (ub % nb != b) continue;
                     const float v = red[t];
-                    const uint32_t row = ((u0 + ub / nb) / S) * R + (t & (R - 1));
+                    const uint32_t row = (u0 + ub / nb) * R + (t & (R - 1));   // (the LM head has one K slice: unit = row group)
                     if (v > bv || (v == bv && row < bi)) { bv = v; bi = row; }
                 }
                 argmax_wave(bv, bi);
@@ -1427,27 +1443,23 @@ __device__ __forceinline__ void att_issue(const Params &P, const Wg &lp, const I
     }
 }
 
+// Prologue of an attention task (both forms): the q heads of the task -- and, in the task that owns the block of the
+// new position, the new k and v -- are summed from the QKV partials, normalised (QK-norm), rotated and left in LDS:
+// sq [kMaxGroup][D] (pre-scaled by 1/sqrt(D)), snew [2][D] (rounded to bf16 like the rows in the cache).  The owner of
+// the group's first heads appends the new rows to the cache.  Returns whether this task owns the new position.
 template <int D>
-__device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp, AttStream &as, uint32_t pc)
+__device__ __forceinline__ bool att_prologue(const Params &P, const InstrAtt &I, char *lds, Wg &lp, int p, uint32_t pc)
 {
-    constexpr int LPP = D / 8;       // lanes per position (16 B each)
-    constexpr int PPW = 64 / LPP;    // positions per wavefront load
     const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
     const int b = (int)I.b, g = (int)I.g;
-    if (b >= P.batch) return;
     // The task covers heads [hb, hb + G) of the GG query heads that share KV head g.
     const int GG = P.n_q_heads / P.n_kv_heads, hb = (int)I.h0, G = (int)I.nh;
-    const int p = as.p;
     const int qd = P.n_q_heads * D, kvd = P.n_kv_heads * D;
     const float *act = (const float *)(P.scr + P.lay.act);
     const uint16_t *vecs = (const uint16_t *)(P.ws + P.lay.vecs);
     const float *rope = (const float *)(P.ws + P.lay.rope) + (size_t)p * D;  // [D/2][2]
-
-    // LDS scratch inside the xs region
-    float *sq = (float *)(lds + lp.xs_off);              // [G][D] rotated, pre-scaled q
-    float *snew = sq + kMaxGroup * D;                    // [2][D] new k (rotated, bf16-rounded) and v
-    float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][MS]: acc[D], m, l, pad (rows 16-byte aligned)
-    constexpr int MS = D + 4;
+    float *sq = (float *)(lds + lp.xs_off);
+    float *snew = sq + kMaxGroup * D;
     const int jb_new = p >> kAttBlockLog;
     const bool owner = (jb_new % (int)I.nc) == (int)I.c;
 
@@ -1518,6 +1530,26 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
         const uint32_t pk = (__float_as_uint(snew[which * D + 2 * j]) >> 16) | (__float_as_uint(snew[which * D + 2 * j + 1]) & 0xffff0000u);
         __hip_atomic_store((gptr)(uintptr_t)(P.kv + base + 2 * j), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    return owner;
+}
+
+template <int D>
+__device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp, AttStream &as, uint32_t pc)
+{
+    constexpr int LPP = D / 8;       // lanes per position (16 B each)
+    constexpr int PPW = 64 / LPP;    // positions per wavefront load
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
+    const int b = (int)I.b, g = (int)I.g;
+    if (b >= P.batch) return;
+    const int GG = P.n_q_heads / P.n_kv_heads, hb = (int)I.h0, G = (int)I.nh;
+    const int p = as.p;
+
+    // LDS scratch inside the xs region
+    float *sq = (float *)(lds + lp.xs_off);              // [G][D] rotated, pre-scaled q
+    float *snew = sq + kMaxGroup * D;                    // [2][D] new k (rotated, bf16-rounded) and v
+    float *smerge = snew + 2 * D;                        // [kWaves * PPW][G][MS]: acc[D], m, l, pad (rows 16-byte aligned)
+    constexpr int MS = D + 4;
+    const bool owner = att_prologue<D>(P, I, lds, lp, p, pc);
 
     // ---- main loop over this task's history positions (t < p)
     const int sub = as.sub, dl = lane % LPP;   // position inside the load, 8-dim slice
@@ -1686,6 +1718,260 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
             float *ml = (float *)(P.scr + P.lay.act) + dst + D;
             st_act(ml, sfac[G * NSLOT + h]);
             st_act(ml + 1, sfac[G * NSLOT + G + h]);
+        }
+    }
+    trace_mark(P, pc, 3);
+}
+
+// ---------------------------------------------------------------- attention task on the matrix cores
+// The same flash-decode partial as att_task, for the kernels that serve several sequences: there the history loop of
+// the vector form is bound by its arithmetic (every lane of a 16-lane group repeats the soft-max bookkeeping of
+// each head), not by the K/V stream.  Here a wavefront takes whole blocks of 16 positions:
+//   scores   S[pos][col] = K[pos][:] . q[col][:]       D/32 x v_mfma_f32_16x16x32_bf16; the K rows are the A operand
+//            straight from the cache (lane % 16 = position, lane / 16 = 16-byte slice of every 64 bytes of the row),
+//            the B operand holds the rotated, pre-scaled q of every head as TWO bf16 columns (hi, lo), so that
+//            the product keeps fp32-like accuracy: up to 8 heads fill the 16 columns;
+//   soft-max once per (position, column): a lane owns four positions of one column; the running maximum of a
+//            column is only raised when some score of the block exceeds it (a wave-wide vote), and only then are the
+//            accumulators rescaled;
+//   values   O^T[d][col] += V^T[d][pos] . P[pos][col]  D/16 x v_mfma_f32_16x16x16_bf16; P is again hi / lo columns and is
+//            already laid out as the B operand (a lane's four positions are its four k values); V^T comes from a
+//            transposed copy of the block in LDS (rows of 16 positions), written with 16-bit stores.
+// Each wavefront leaves (max, denominator, accumulators) per head in LDS; they are merged in wave order and stored in
+// the same partial-row format as att_task writes, so that combine tasks and the fused combine read either.
+constexpr int kAttMcDepth = 2;   // blocks (K and V rows of 16 positions) a wavefront keeps in flight
+constexpr int kVtRow = 40;       // bytes per row of the transposed V block: 16 positions of bf16 + 8 bytes of bank skew
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct AttStreamMc {
+    const __attribute__((address_space(1))) u32x4 *kp, *vp;   // K / V of (sequence, kv head): row 0, this lane's 16-byte slice
+    int p, nblk;                                               // position of the new token; blocks of this wavefront
+    u32x4 kbuf[kAttMcDepth][D / 32], vbuf[kAttMcDepth][D / 32];
+};
+
+// Loads of block kk of this wavefront (blocks wave, wave + 4, ... of the task) into slot s.  Rows at or beyond p go
+// to row p - 1 instead (they are masked when consumed): no cache then holds a line of a row before the step that
+// appends it has written it.
+template <int D>
+__device__ __forceinline__ void att_mc_load(const InstrAtt &I, AttStreamMc<D> &st, int s, int kk)
+{
+    const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
+    int t = (((int)I.c + (wave + kk * kWaves) * (int)I.nc) << kAttBlockLog) + (lane & 15);
+    t = t < st.p ? t : st.p - 1;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+        st.kbuf[s][i] = __builtin_nontemporal_load(st.kp + (size_t)t * (D / 8) + 4 * i);
+        st.vbuf[s][i] = __builtin_nontemporal_load(st.vp + (size_t)t * (D / 8) + 4 * i);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void att_issue_mc(const Params &P, const Wg &lp, const InstrAtt &I, AttStreamMc<D> &st)
+{
+    typedef const __attribute__((address_space(1))) u32x4 *gp;
+    const int lane = threadIdx.x & 63, wave = (int)rfl(threadIdx.x >> 6);
+    const int b = (int)I.b, g = (int)I.g;
+    st.p = 0; st.nblk = 0;
+#pragma unroll
+    for (int s = 0; s < kAttMcDepth; ++s)
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) { st.kbuf[s][i] = u32x4{0u, 0u, 0u, 0u}; st.vbuf[s][i] = u32x4{0u, 0u, 0u, 0u}; }
+    if (b >= P.batch) return;
+    const int p = position_of(P, lp, b);
+    const int nc = (int)I.nc, c = (int)I.c;
+    const int nblk_all = (p + (1 << kAttBlockLog)) >> kAttBlockLog;    // blocks containing positions <= p (the new one included)
+    const int my_blocks = (nblk_all > c) ? (nblk_all - c + nc - 1) / nc : 0;
+    st.p = p;
+    st.nblk = my_blocks > wave ? (my_blocks - wave + kWaves - 1) / kWaves : 0;
+    const size_t head_elems = (size_t)P.max_context * D;
+    const uint16_t *Kc = P.kv + ((((size_t)I.layer * 2 + 0) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
+    const uint16_t *Vc = P.kv + ((((size_t)I.layer * 2 + 1) * P.max_batch + b) * P.n_kv_heads + g) * head_elems;
+    st.kp = (gp)(uintptr_t)Kc + (lane >> 4);
+    st.vp = (gp)(uintptr_t)Vc + (lane >> 4);
+    if (p > 0) {
+#pragma unroll
+        for (int s = 0; s < kAttMcDepth; ++s)
+            if (s < st.nblk) att_mc_load<D>(I, st, s, s);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void att_task_mc(const Params &P, const InstrAtt &I, char *lds, Wg &lp, AttStreamMc<D> &as, uint32_t pc)
+{
+    constexpr int ND = D / 32, NV = D / 16, MS = D + 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (int)rfl((uint32_t)tid >> 6);
+    const int b = (int)I.b, g = (int)I.g;
+    if (b >= P.batch) return;
+    const int GG = P.n_q_heads / P.n_kv_heads, hb = (int)I.h0, G = (int)I.nh;
+    const int p = as.p;
+    float *sq = (float *)(lds + lp.xs_off);              // [kMaxGroup][D] rotated, pre-scaled q
+    float *snew = sq + kMaxGroup * D;                    // [2][D] new k and v
+    char *vt = (char *)(snew + 2 * D) + (size_t)wave * (D * kVtRow);   // this wavefront's transposed V block [D][16 positions]
+    float *smerge = (float *)((char *)(snew + 2 * D) + (size_t)kWaves * (D * kVtRow));   // [kWaves][G][MS]
+    const bool owner = att_prologue<D>(P, I, lds, lp, p, pc);
+
+    const int col = lane & 15, r = lane >> 4;   // operand / result column; 16-byte slice (operands), row group (results)
+    const int h = col >> 1, term = col & 1;     // head of the column inside this task; 0: hi term, 1: lo term
+    // B operand of the score products: this column's q term, k = 32 i + 8 r .. + 8
+    bf16x8 qop[ND];
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+        const f32x4 *qp = (const f32x4 *)(sq + (h < G ? h : 0) * D + 32 * i + 8 * r);
+        f32x4 a = qp[0], c4 = qp[1];
+        u32x4 pk = {pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(c4.x, c4.y), pack_bf16x2(c4.z, c4.w)};
+        if (term) {
+            a.x -= bf_lo(pk.x); a.y -= bf_hi(pk.x); a.z -= bf_lo(pk.y); a.w -= bf_hi(pk.y);
+            c4.x -= bf_lo(pk.z); c4.y -= bf_hi(pk.z); c4.z -= bf_lo(pk.w); c4.w -= bf_hi(pk.w);
+            pk = u32x4{pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(c4.x, c4.y), pack_bf16x2(c4.z, c4.w)};
+        }
+        if (h >= G) pk = u32x4{0u, 0u, 0u, 0u};
+        qop[i] = __builtin_bit_cast(bf16x8, pk);
+    }
+
+    float M = -INFINITY, lsum = 0.f;
+    f32x4 acc[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nc = (int)I.nc, c = (int)I.c;
+    const int jb_new = p >> kAttBlockLog;
+    auto swap2 = [](float v) { return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true)); };
+    auto pair = [](float lo, float hi) { return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u); };
+
+    auto block = [&](int s, int kk) {
+        const int jb = c + (wave + kk * kWaves) * nc;        // block of the cache
+        const int t0 = jb << kAttBlockLog;
+        u32x4 kr[ND], vr[ND];
+#pragma unroll
+        for (int i = 0; i < ND; ++i) { kr[i] = as.kbuf[s][i]; vr[i] = as.vbuf[s][i]; }
+        if (owner && jb == jb_new && col == (p & 15)) {
+            // the new position: its rows come from LDS (bf16-rounded like the rows in the cache); the loads went to row p - 1
+#pragma unroll
+            for (int i = 0; i < ND; ++i) {
+                const float *kn = snew + 32 * i + 8 * r, *vn = snew + D + 32 * i + 8 * r;
+                const f32x4 k0 = *(const f32x4 *)kn, k1 = *(const f32x4 *)(kn + 4), v0 = *(const f32x4 *)vn, v1 = *(const f32x4 *)(vn + 4);
+                kr[i] = u32x4{pair(k0.x, k0.y), pair(k0.z, k0.w), pair(k1.x, k1.y), pair(k1.z, k1.w)};
+                vr[i] = u32x4{pair(v0.x, v0.y), pair(v0.z, v0.w), pair(v1.x, v1.y), pair(v1.z, v1.w)};
+            }
+        }
+        // the V block, transposed, into this wavefront's LDS rows: VT[d][position] (LDS requests of a wavefront are served in
+        // order, so these stores cannot overtake the reads of the previous block)
+        {
+            char *wb = vt + (8 * r) * kVtRow + 2 * col;
+#pragma unroll
+            for (int i = 0; i < ND; ++i) {
+                const uint32_t dw[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    *(uint16_t *)(wb + (32 * i + 2 * q) * kVtRow) = (uint16_t)(dw[q] & 0xffffu);
+                    *(uint16_t *)(wb + (32 * i + 2 * q + 1) * kVtRow) = (uint16_t)(dw[q] >> 16);
+                }
+            }
+        }
+        // scores of the 16 positions against every column
+        f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < ND; ++i) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[i]), qop[i], sc, 0, 0, 0);
+        float sv[4], bmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float v = sc[j] + swap2(sc[j]);                       // hi + lo column of the head
+            sv[j] = (t0 + 4 * r + j <= p) ? v : -INFINITY;              // sc[j]: position t0 + 4 r + j
+            bmax = fmaxf(bmax, sv[j]);
+        }
+        if (__any(bmax > M)) {
+            // some column's maximum rises: agree on it across the four row groups, rescale that column's sums
+            float mn = fmaxf(M, bmax);
+            mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
+            mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
+            const float rs = safe_exp_diff(M, mn);
+            lsum *= rs;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc[i] *= rs;
+            M = mn;
+        }
+        float pr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pr[j] = safe_exp_diff(sv[j], M);
+        lsum += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+        uint32_t p01 = pack_bf16x2(pr[0], pr[1]), p23 = pack_bf16x2(pr[2], pr[3]);
+        if (term) {
+            p01 = pack_bf16x2(pr[0] - bf_lo(p01), pr[1] - bf_hi(p01));
+            p23 = pack_bf16x2(pr[2] - bf_lo(p23), pr[3] - bf_hi(p23));
+        }
+        typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+        const s16x4 pop = __builtin_bit_cast(s16x4, u32x2v{p01, p23});
+        const char *rb = vt + col * kVtRow + 8 * r;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const s16x4 va = *(const s16x4 *)(rb + 16 * i * kVtRow);   // V^T[16 i + lane % 16][4 r .. 4 r + 3]
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pop, acc[i], 0, 0, 0);
+        }
+    };
+
+    for (int base = 0; base < as.nblk; base += kAttMcDepth) {
+#pragma unroll
+        for (int s = 0; s < kAttMcDepth; ++s) {
+            if (base + s < as.nblk) {            // (wave-uniform)
+                block(s, base + s);
+                if (base + s + kAttMcDepth < as.nblk) att_mc_load<D>(I, as, s, base + s + kAttMcDepth);   // (implies p > 0)
+            }
+        }
+    }
+    trace_mark(P, pc, 1);
+
+    // ---- this wavefront's state per head: the denominators of the four row groups and the two term columns add up
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += swap2(acc[i][j]);
+    if (term == 0 && h < G) {
+        float *dst = smerge + ((size_t)wave * G + h) * MS;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) *(f32x4 *)(dst + 16 * i + 4 * r) = acc[i];      // acc[i][j]: d = 16 i + 4 r + j
+        if (r == 0) { dst[D] = M; dst[D + 1] = lsum; }
+    }
+    wg_sync(lp, lds);
+    trace_mark(P, pc, 2);
+
+    // merged max, denominator and per-wavefront weights of every head: thread (head, wavefront), a head's four in one quad
+    float *sfac = smerge + (size_t)kWaves * G * MS;     // [G][kWaves] weights, then [G] max, [G] denominators
+    static_assert(kWaves == 4, "the merge reduces over quads of lanes");
+    if (tid < G * kWaves) {
+        const int hh = tid / kWaves, w = tid % kWaves;
+        const float *src = smerge + ((size_t)w * G + hh) * MS;
+        const float m = src[D], l = src[D + 1];
+        float Mx = dpp_max<0xB1>(m);
+        Mx = dpp_max<0x4E>(Mx);
+        const float f = safe_exp_diff(m, Mx);
+        float L = dpp_add<0xB1>(f * l);
+        L = dpp_add<0x4E>(L);
+        sfac[hh * kWaves + w] = f;
+        if (w == 0) { sfac[G * kWaves + hh] = Mx; sfac[G * kWaves + G + hh] = L; }
+    }
+    wg_sync(lp, lds);
+    const ActBuf ab = act_buf(P);
+    for (int e = tid; e < G * D / 4; e += kWgThreads) {       // four adjacent outputs per thread
+        const int hh = (4 * e) / D, i = (4 * e) % D;
+        f32x4 svv[kWaves];
+        float fv[kWaves];
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            svv[w] = *(const f32x4 *)(smerge + ((size_t)w * G + hh) * MS + i);
+            fv[w] = sfac[hh * kWaves + w];
+        }
+        f32x4 A = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) A += svv[w] * fv[w];
+        // partial layout [b][head][nc][D + kPartStride]
+        const uint32_t dst = I.out + (uint32_t)((((size_t)b * P.n_q_heads + (g * GG + hb + hh)) * I.nc + I.c) * (D + kPartStride));
+        st_act4(ab, dst + (uint32_t)i, A);
+        if (i == 0) {
+            float *ml = (float *)(P.scr + P.lay.act) + dst + D;
+            st_act(ml, sfac[G * kWaves + hh]);
+            st_act(ml + 1, sfac[G * kWaves + G + hh]);
         }
     }
     trace_mark(P, pc, 3);
@@ -1873,6 +2159,19 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
             if (W4 && (I.flags & F_W4)) gemv_main<false, false, true>(P, I, lds, lp, st, 1);
             else gemv_main<false, RING>(P, I, lds, lp, st, 1);
         }
+    } else if (I.op == OP_ATT && (PATH == kPathMfma || PATH == kPathW4M || PATH == kPathAny16) && (I.flags & F_ATT_MC)) {
+        const InstrAtt &A = *(const InstrAtt *)&I;
+        if (P.head_dim == 128) {
+            AttStreamMc<128> as;
+            att_issue_mc<128>(P, lp, A, as);
+            await();
+            att_task_mc<128>(P, A, lds, lp, as, pc);
+        } else {
+            AttStreamMc<64> as;
+            att_issue_mc<64>(P, lp, A, as);
+            await();
+            att_task_mc<64>(P, A, lds, lp, as, pc);
+        }
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
         AttStream as;
@@ -2027,9 +2326,10 @@ MK_KERNEL(mk_megakernel_ring, (mk::run_persistent<true, true, mk::kPathAny16>(P,
 // r_off = 0 for a plain matrix; rpu = R/2 with r_off 0 / R/2 interleaves the gate and up matrices).
 // Chunk (group, kb) holds lane-major 16 B: lane = ksub * R + r -> W[row][kb * 512/R + ksub*8 + 0..7].
 // Lanes whose r lies outside [r_off, r_off + rpu) belong to the other matrix and are left alone;
-// rows and columns beyond the source are written as zeros.
+// rows and columns beyond the source are written as zeros.  `ord` says where chunk (group, kb) is stored (chunk_slot).
 extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int n_cols, mk::u32x4 *dst, uint32_t kbt,
-                                            uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups)
+                                            uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups,
+                                            mk::ChunkOrder ord)
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n_groups * kbt * 64;
@@ -2051,7 +2351,7 @@ extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int
     mk::u32x4 v;
     v.x = e[0] | ((uint32_t)e[1] << 16); v.y = e[2] | ((uint32_t)e[3] << 16);
     v.z = e[4] | ((uint32_t)e[5] << 16); v.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v;
+    dst[(size_t)mk::chunk_slot(ord.sm != 0, g0 + grp, kb, ord.S, ord.groups, kbt, ord.nkb) * 64 + lane] = v;
 }
 
 // Offline reorder of a W4 matrix: codes row-major uint8 [n_rows][n_cols / 2] (even k in the low nibble)
@@ -2062,7 +2362,7 @@ extern "C" __global__ void mk_repack_kernel(const uint16_t *src, int n_rows, int
 // holds the 8 codes of k0 + 32 i + 8 ksub .. + 8, nibble p standing for offset 2 (p % 4) + p / 4 inside those 8.
 extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, int n_cols, mk::u32x4 *dst, uint32_t kbt,
                                                uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0, uint32_t n_groups,
-                                               uint32_t mfma)
+                                               uint32_t mfma, mk::ChunkOrder ord)
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n_groups * kbt * 64;
@@ -2093,7 +2393,7 @@ extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, i
             d[i] = v;
         }
         mk::u32x4 v4 = {d[0], d[1], d[2], d[3]};
-        dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v4;
+        dst[(size_t)mk::chunk_slot(ord.sm != 0, g0 + grp, kb, ord.S, ord.groups, kbt, ord.nkb) * 64 + lane] = v4;
         return;
     }
 #pragma unroll
@@ -2108,14 +2408,14 @@ extern "C" __global__ void mk_repack_w4_kernel(const uint8_t *src, int n_rows, i
         d[i] = v;
     }
     mk::u32x4 v4 = {d[0], d[1], d[2], d[3]};
-    dst[((size_t)(g0 + grp) * kbt + kb) * 64 + lane] = v4;
+    dst[(size_t)mk::chunk_slot(ord.sm != 0, g0 + grp, kb, ord.S, ord.groups, kbt, ord.nkb) * 64 + lane] = v4;
 }
 
 // The scales that go with it: src bf16 [n_rows][n_cols / group] -> per chunk 2048/group values, index
 // g * R + r for group g of the chunk's k range and row r of the chunk; absent rows / groups get 0.
 extern "C" __global__ void mk_repack_scales_kernel(const uint16_t *src, int n_rows, int n_cols, uint16_t *dst, uint32_t kbt,
                                                    uint32_t rlog, uint32_t rpu, uint32_t r_off, uint32_t g0,
-                                                   uint32_t n_groups, uint32_t group)
+                                                   uint32_t n_groups, uint32_t group, mk::ChunkOrder ord)
 {
     const uint32_t R = 1u << rlog, ck = 2048u >> rlog, spc = 2048u / group;
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -2129,7 +2429,7 @@ extern "C" __global__ void mk_repack_scales_kernel(const uint16_t *src, int n_ro
     long row = (long)grp * rpu + (r - r_off);
     const uint32_t kg = (kb * ck) / group + g;       // group index along K
     const uint32_t n_kg = (uint32_t)n_cols / group;
-    dst[((size_t)(g0 + grp) * kbt + kb) * spc + si] = (row < n_rows && kg < n_kg) ? src[(size_t)row * n_kg + kg] : (uint16_t)0;
+    dst[(size_t)mk::chunk_slot(ord.sm != 0, g0 + grp, kb, ord.S, ord.groups, kbt, ord.nkb) * spc + si] = (row < n_rows && kg < n_kg) ? src[(size_t)row * n_kg + kg] : (uint16_t)0;
 }
 
 extern "C" __global__ void mk_copy_u16_kernel(const uint16_t *src, uint16_t *dst, size_t n)

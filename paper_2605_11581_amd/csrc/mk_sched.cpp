@@ -95,6 +95,7 @@ static MatGeom mat_geom(int rlog, int n_rows, int k_len, int w4 = 0)
     g.rlog = rlog; g.R = 1 << rlog; g.ck = (w4 ? 2048 : 512) >> rlog; g.w4 = w4;
     g.groups = ceil_div(n_rows, g.R); g.kbt = ceil_div(k_len, g.ck);
     g.n_rows = n_rows; g.k_len = k_len;
+    g.S = 1; g.sm = 0;
     return g;
 }
 
@@ -107,6 +108,10 @@ static void derive_geom(const Dims &d, const Tiling &t, Geom &g)
     g.gu = mat_geom(t.r_gu, 2 * g.ipad, d.H, d.w4);
     g.down = mat_geom(t.r_d, d.H, d.I, d.w4);
     g.head = mat_geom(t.r_head, d.V, d.H);
+    g.qkv.S = t.s_qkv; g.o.S = t.s_o; g.gu.S = t.s_gu; g.down.S = t.s_d;
+    // O and down stage only the K range of their units: numbered slice first, the units a workgroup gets share one
+    // slice (QKV and gate/up normalise the whole residual whatever their K range, so they gain nothing from it)
+    g.o.sm = t.s_o > 1; g.down.sm = t.s_d > 1;
 }
 
 // ---------------------------------------------------------------- memory maps
@@ -163,13 +168,16 @@ struct LdsBudget {
 // its heads, the K/V rows are read once more (they are small next to the weights).
 static int att_head_splits(const Dims &d, const Tiling &t, int n_wg)
 {
-    if (d.G < 2) return 1;
+    // (a matrix-core attention task scores up to 8 heads for the price of one: splitting would only re-read K and V)
+    if (d.G < 2 || t.att_mc) return 1;
     const int64_t base = (int64_t)d.Bm * d.nkv * t.nc;   // tasks without a head split
     return (int)std::max<int64_t>(1, std::min<int64_t>(d.G, n_wg / base));
 }
 
-static uint32_t att_scratch_bytes(const Dims &d)
+static uint32_t att_scratch_bytes(const Dims &d, const Tiling &t)
 {
+    if (t.att_mc)   // q, new k/v, a transposed V block (d rows of 40 bytes) per wavefront, per-wavefront merge rows (d + 4), merge weights
+        return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * d.G * (d.d + 4) + kWaves * kMaxGroup + 2 * kMaxGroup) * 4u + (uint32_t)(kWaves * d.d * 40);
     return (uint32_t)((kMaxGroup + 2) * d.d + kWaves * (512 / d.d) * d.G * (d.d + 4 + 1) + 2 * kMaxGroup) * 4u;   // q, new k/v, per-slot merge rows (d + 4), merge weights
 }
 
@@ -192,7 +200,7 @@ static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
     const int64_t fixed = kLdsRed + b.red_bytes;
     // pages are the 1 KB chunk slots of the ring; a pipeline stage is 16 of them
     const int64_t pages_total = pages_available(kLdsMax, 1, kLdsMisc - kLdsInstr, kLdsRed - kLdsMisc, b.red_bytes, t.page_bytes);
-    const int64_t need = std::max<int64_t>(att_scratch_bytes(d), norm_stage_bytes(d, t));
+    const int64_t need = std::max<int64_t>(att_scratch_bytes(d, t), norm_stage_bytes(d, t));
     const int64_t pages_act = (need + t.page_bytes - 1) / t.page_bytes;
     if (t.ring_pages > 0 && pipeline_stages(pages_total, 0, 0, pages_act, 16) * 16 < t.ring_pages) return false;
     const int64_t left = kLdsMax - fixed - (int64_t)t.ring_pages * t.page_bytes;
@@ -271,7 +279,8 @@ struct Builder {
                 // grow the task unit by unit while the reduction area and the staged input fit
                 uint32_t nu = 0, klo = 0, khi = 0;
                 while (u + nu < u_end && nu < cap_units) {
-                    uint32_t uu = u + nu, s = uu % S;
+                    uint32_t uu = u + nu, rg, s;
+                    unit_place(m.sm != 0, uu, S, (uint32_t)m.groups, rg, s);
                     uint32_t lo = s * nkb, hi = (s == S - 1) ? kbt : lo + nkb;
                     uint32_t nlo = nu ? std::min(klo, lo) : lo, nhi = nu ? std::max(khi, hi) : hi;
                     if (!normk && stage_bytes((nhi - nlo) * m.ck) + (pro == PRO_COMBINE ? combine_bytes((nhi - nlo) * m.ck) : 0u) > lb.xs_cap) break;
@@ -311,7 +320,8 @@ struct Builder {
                 lists[wg].push_back(I);
                 ++n_tasks;
                 // load: chunks streamed + a fixed per-task cost (in chunk equivalents)
-                uint32_t c0 = (u / S) * kbt + (u % S) * nkb, ue = u + nu, c1 = (ue / S) * kbt + (ue % S) * nkb;
+                const uint32_t c0 = unit_chunk0(m.sm != 0, u, S, (uint32_t)m.groups, kbt, nkb);
+                const uint32_t c1 = unit_chunk0(m.sm != 0, u + nu, S, (uint32_t)m.groups, kbt, nkb);
                 load[wg] += (double)(c1 - c0) + 4.0;
                 u += nu; first = false;
             }
@@ -323,7 +333,7 @@ struct Builder {
                      uint32_t prod_rlog) const
     {
         Instr I{};
-        I.op = OP_GEMV; I.flags = (t.mfma ? F_MFMA : 0u) | (m.w4 ? F_W4 : 0u); I.ref_seq = (uint32_t)l * 8 + stage; I.layer = (uint32_t)l;
+        I.op = OP_GEMV; I.flags = (t.mfma ? F_MFMA : 0u) | (m.w4 ? F_W4 : 0u) | (m.sm ? F_SLICE_MAJOR : 0u); I.ref_seq = (uint32_t)l * 8 + stage; I.layer = (uint32_t)l;
         I.w_chunk = w_chunk; I.kbt = (uint32_t)m.kbt; I.S = (uint32_t)S; I.nkb = (uint32_t)ceil_div(m.kbt, S);
         I.n_rows = (uint32_t)m.n_rows; I.k_len = (uint32_t)m.k_len;
         I.cfg = make_cfg(pro, (uint32_t)m.rlog, prod_rlog, n_parts);
@@ -377,7 +387,7 @@ struct Builder {
                             const int h_base = d.G / hs, h_rem = d.G % hs;
                             const int h_lo = hp * h_base + std::min(hp, h_rem), h_n = h_base + (hp < h_rem ? 1 : 0);
                             a.h0 = (uint32_t)h_lo; a.nh = (uint32_t)h_n;
-                            a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l;
+                            a.op = OP_ATT; a.ref_seq = l * 8 + ST_ATT; a.layer = l; a.flags = t.att_mc ? F_ATT_MC : 0u;
                             a.wait_ctr[0] = c_qkv; a.wait_cnt[0] = ctr_signals[c_qkv]; a.wait_ctr[1] = kNone;
                             a.sig_ctr = c_att[b * d.nkv + gh]; ++ctr_signals[a.sig_ctr];
                             a.b = b; a.g = gh; a.c = c; a.nc = t.nc; a.bs = t.bs;
@@ -463,7 +473,7 @@ struct Builder {
                 load[order[b % n_wg]] += 2.0;
             }
         }
-        max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d));
+        max_xs_bytes = std::max(max_xs_bytes, att_scratch_bytes(d, t));
         max_xs_bytes = std::max(max_xs_bytes, (uint32_t)(t.nc * (d.d + kPartPad + 1) * 4));   // combine task: partial rows + merge weights
         return true;
     }
@@ -530,9 +540,9 @@ static bool replay(const mk_schedule *s, F &&visit, std::string *why)
 
 static uint32_t task_chunks(const Instr &I)
 {
-    uint32_t c0 = (I.u0 / I.S) * I.kbt + (I.u0 % I.S) * I.nkb, ue = I.u0 + I.nu;
-    uint32_t c1 = (ue / I.S) * I.kbt + (ue % I.S) * I.nkb;
-    return c1 - c0;
+    const bool sm = (I.flags & F_SLICE_MAJOR) != 0;
+    const uint32_t groups = instr_groups(I);
+    return unit_chunk0(sm, I.u0 + I.nu, I.S, groups, I.kbt, I.nkb) - unit_chunk0(sm, I.u0, I.S, groups, I.kbt, I.nkb);
 }
 
 // Pipeline cost model (Sec. 4.2.2 Step 3-4).  Per workgroup two timelines: the weight stream
@@ -803,6 +813,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     best.r_qkv = c_rq[0]; best.r_o = c_ro[0]; best.r_gu = c_rgu[0]; best.r_d = c_rd[0]; best.r_head = c_rh[0];
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.fuse = cfg.fuse_combine > 0 ? 1 : 0;   // not searched by the cost model: chosen by the caller or by on-device tuning
+    best.att_mc = (mfma && !(cfg.flags & MK_F_VALU_ATTENTION)) ? 1 : 0;
     best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
     // weight-page ring: a pipeline stage is 16 pages (4 per wavefront).  The depth is only searched
     // when asked for (ring_kb == -2): measured on MI355X the direct-load path is the faster one at
@@ -904,9 +915,11 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
                     if (I.flags & F_SILU_EPI) {
                         wr(I.out + (uint64_t)b * I.out_ld + (uint64_t)u * (R / 2), R / 2);
                     } else {
-                        const uint64_t row0 = (uint64_t)(u / I.S) * R;
+                        uint32_t rg, sl;
+                        unit_place((I.flags & F_SLICE_MAJOR) != 0, u, I.S, instr_groups(I), rg, sl);
+                        const uint64_t row0 = (uint64_t)rg * R;
                         if (I.flags & F_ADD_RESID) rd(I.resid + (uint64_t)b * I.out_ld + row0, R);
-                        wr(I.out + (uint64_t)(u % I.S) * I.out_split_stride + (uint64_t)b * I.out_ld + row0, R);
+                        wr(I.out + (uint64_t)sl * I.out_split_stride + (uint64_t)b * I.out_ld + row0, R);
                     }
                 }
         }
@@ -1004,7 +1017,8 @@ int verify_schedule(const mk_schedule *s)
                 if (I.w_chunk != chunk) return bad("weight chunk offset differs from the planned matrix");
                 if (I.kbt != (uint32_t)m->kbt || I.S != (uint32_t)S || I.nkb != (uint32_t)ceil_div(m->kbt, S) ||
                     instr_rlog(I) != (uint32_t)m->rlog || I.n_rows != (uint32_t)m->n_rows || I.k_len != (uint32_t)m->k_len ||
-                    ((I.flags & F_W4) != 0) != (m->w4 != 0) || ((I.flags & F_MFMA) != 0) != (s->tl.mfma != 0))
+                    ((I.flags & F_W4) != 0) != (m->w4 != 0) || ((I.flags & F_MFMA) != 0) != (s->tl.mfma != 0) ||
+                    ((I.flags & F_SLICE_MAJOR) != 0) != (m->sm != 0) || instr_groups(I) != (uint32_t)m->groups)
                     return bad("matrix geometry differs from the planned matrix");
                 const uint32_t pro = instr_pro(I);
                 const bool normk = pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM;
@@ -1012,6 +1026,15 @@ int verify_schedule(const mk_schedule *s)
                 if (normk && I.gain != gain) return bad("norm gain offset differs from the planned vector");
                 if (I.bias != bias) return bad("bias offset differs from the planned vector");
                 if ((uint64_t)I.u0 + I.nu > (uint64_t)m->groups * S) return bad("units beyond the matrix");
+                if (!normk) {
+                    // the staged chunk range must hold the K slice of every unit of the task
+                    for (uint32_t u = I.u0; u < I.u0 + I.nu; ++u) {
+                        uint32_t rg, sl;
+                        unit_place(m->sm != 0, u, I.S, (uint32_t)m->groups, rg, sl);
+                        const uint32_t lo = sl * I.nkb, hi = lo + slice_chunks(sl, I.S, I.nkb, I.kbt);
+                        if (lo < I.xs_lo || hi > I.xs_lo + I.xs_hi) return bad("a unit's K slice lies outside the staged input range");
+                    }
+                }
             } else if (I.op == OP_ATT || I.op == OP_COMB) {
                 const InstrAtt &A = *(const InstrAtt *)&I;
                 if (st != (I.op == OP_ATT ? ST_ATT : ST_COMB)) return bad("attention task at the wrong stage");
@@ -1019,6 +1042,7 @@ int verify_schedule(const mk_schedule *s)
                 if (A.nc != (uint32_t)s->tl.nc) return bad("chunk count differs from the tiling");
                 if (A.out != s->am.attp) return bad("attention partial buffer offset differs from the plan");
                 if (I.op == OP_ATT) {
+                    if (((I.flags & F_ATT_MC) != 0) != (s->tl.att_mc != 0)) return bad("attention form differs from the tiling");
                     if (A.g >= (uint32_t)d.nkv) return bad("kv head out of range");
                     if (A.c >= A.nc) return bad("chunk index out of range");
                     if (A.bs != (uint32_t)s->tl.bs || A.bs != 16u) return bad("block size differs from the tiling");
@@ -1262,7 +1286,7 @@ struct BlobHeader {
     uint64_t n_instr_words;
 };
 constexpr uint32_t kMagic = 0x4d4b5343u;  // "MKSC"
-constexpr uint32_t kVersion = 6;
+constexpr uint32_t kVersion = 7;
 }  // namespace
 
 int dump_schedule(const mk_schedule *s, void *buf, size_t *bytes)

@@ -24,6 +24,7 @@ struct Tiling {              // the searched parameters (Sec. 4.2.2 Step 3, "til
     int bs;                      // positions per attention block
     int mfma;                    // 0 VALU, 1 MFMA
     int fuse;                    // 1: the O projection combines the attention partials itself (no combine tasks)
+    int att_mc;                  // 1: attention tasks run on the matrix cores (kernels of the matrix-core path only)
     int ring_pages, page_bytes, n_stage;  // Eq. 1-2 outcome (0 pages: weights go straight to registers)
 };
 
@@ -33,6 +34,8 @@ struct MatGeom {             // tile-major geometry of one matrix under a tiling
     int kbt;                 // chunks per row group
     int n_rows, k_len;       // true output rows and K
     int w4;                  // 4-bit codes: ck = 2048 / R instead of 512 / R
+    int S;                   // K slices per row group
+    int sm;                  // 1: units and chunks are numbered K slice first (mk::unit_place)
 };
 
 struct Geom {

@@ -105,6 +105,8 @@ def test_c0_greedy_32_steps_match_oracle():
     dict(chunk_rows=16, split_qkv=2, split_o=2, split_gateup=2, split_down=4, attn_chunks=4),
     dict(chunk_rows=8, split_gateup=2, split_down=2), dict(n_workgroups=40, attn_chunks=8), dict(attn_chunks=1),
     dict(use_mfma=1, split_qkv=2, split_o=4, split_gateup=2, split_down=2),
+    # matrix-core kernels: attention on the matrix cores (default there) with one / many chunk tasks, and kept on the vector ALUs
+    dict(use_mfma=1, attn_chunks=1), dict(use_mfma=1, attn_chunks=8, n_workgroups=40), dict(use_mfma=1, flags=mk.MK_F_VALU_ATTENTION),
     # weight-page ring (LDS-DMA stream across task boundaries): shallow, deep, ragged stages, matrix-core path
     dict(ring_kb=16), dict(ring_kb=32, attn_chunks=2), dict(ring_kb=96, chunk_rows=2), dict(ring_kb=64, n_workgroups=24),
     dict(ring_kb=48, use_mfma=1, split_o=2, split_down=2),
@@ -237,7 +239,7 @@ def test_cache_rows_beyond_the_position_are_never_used():
     full = tiny(max_context=96)
     cfg = synth.model_cfg(full)
     w = synth.make_weights(full)
-    for opts in (dict(), dict(attn_chunks=4), dict(ring_kb=32, attn_chunks=2)):
+    for opts in (dict(), dict(attn_chunks=4), dict(ring_kb=32, attn_chunks=2), dict(use_mfma=1, attn_chunks=2)):
         pr = Pair(cfg, w, **opts)
         prompt = synth.make_prompt(full, 21)
         pr.orc.prefill(prompt[:-1], pr.kv_h)

@@ -363,6 +363,42 @@ def test_verifier_rejects_fields_that_address_weights_vectors_or_the_cache(what,
     _expect_rejected(h, needle)
 
 
+S_FIELD, NKB, N_ROWS, CFG, XS_LO, XS_N = 12, 11, 15, 16, 22, 23
+F_SLICE_MAJOR = 256
+
+
+def test_k_sliced_down_projection_keeps_a_workgroups_units_inside_one_slice():
+    """7B shape at batch 8: the down projection needs eight K slices to fit its staged input in LDS.  Units are numbered
+    slice first there, so that a workgroup's share is a few row groups of ONE slice (one staged input, one contiguous
+    weight range) rather than one task per (row group, slice) pair."""
+    cfg = synth.model_cfg(synth.CONFIGS["c4_7b"], max_batch=8)
+    h = mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=256, flags=mk.MK_F_NO_TABLE, split_down=8))
+    mk.mk_schedule_verify(h)
+    st = mk.mk_get_stats(h)
+    assert st["split_down"] == 8
+    n_down, multi = 0, 0
+    for wg in range(0, 256, 17):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if w[OP] != 1 or w[REF_SEQ] % 8 != 5 or w[LAYER] != 0:
+                continue
+            assert w[FLAGS] & F_SLICE_MAJOR
+            rlog = (int(w[CFG]) >> 4) & 15
+            groups = (int(w[N_ROWS]) + (1 << rlog) - 1) >> rlog
+            slices = {u // groups for u in range(int(w[U0]), int(w[U0]) + int(w[NU]))}
+            assert len(slices) == 1                                   # one K slice per task
+            (sl,) = slices
+            assert int(w[XS_LO]) == sl * int(w[NKB]) and int(w[XS_N]) <= int(w[NKB])
+            n_down += 1
+            multi += int(w[NU]) > 1
+    assert n_down and multi                                           # ... and several row groups in it
+    # a unit outside the staged slice is rejected
+    wg, i, w = _anywhere(h, lambda w: w[OP] == 1 and w[REF_SEQ] % 8 == 5 and w[NU] > 1)
+    w[XS_N] = 1
+    mk.mk_instr_set(h, wg, i, w)
+    _expect_rejected(h, "staged input range")
+
+
 def test_verifier_rejects_list_without_end_and_unknown_opcode():
     h = build("c0_tiny")
     w = mk.mk_instr_get(h, 0, 0)
