@@ -229,6 +229,8 @@ def run_workload(config: str, batch: int, w4: bool, steps: int, warmup: int, rep
 
     if per_op:
         n_po = min(steps, 32)
+        # (a level that sums the down projection's partial rows exists from 64 K floats of them on)
+        residual_sum = int(st["split_down"] > 1 and st["split_down"] * cfg["max_batch"] * cfg["hidden"] >= 65536)
         run(warmup, 2, per_op_launches=True)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
@@ -236,7 +238,7 @@ def run_workload(config: str, batch: int, w4: bool, steps: int, warmup: int, rep
         torch.cuda.synchronize()
         po = (time.perf_counter() - t2) / n_po
         out["per_op_baseline"] = {"ms_per_step": round(po * 1e3, 5), "tokens_per_s": round(B / po, 2),
-                                  "launches_per_step": cfg["n_layers"] * (6 - st["fuse_combine"]) + 2, "steps": n_po,
+                                  "launches_per_step": cfg["n_layers"] * (6 - st["fuse_combine"] + residual_sum) + 2, "steps": n_po,
                                   "speedup_of_one_launch": round(po * 1e3 / ms_per_step, 3)}
 
     if cpu_baseline:

@@ -42,10 +42,19 @@ constexpr int kLdsInstr = 0;
 constexpr int kLdsMisc = 256;
 constexpr int kLdsRed = 512;
 
-enum Op : uint32_t { OP_END = 0, OP_GEMV = 1, OP_ATT = 2, OP_COMB = 3, OP_ARGMAX = 4 };
+enum Op : uint32_t { OP_END = 0, OP_GEMV = 1, OP_ATT = 2, OP_COMB = 3, OP_ARGMAX = 4, OP_RSUM = 5 };
 
 // stage of an operator instance inside a layer; ref_seq = layer * 8 + stage
-enum Stage : uint32_t { ST_QKV = 0, ST_ATT = 1, ST_COMB = 2, ST_O = 3, ST_GU = 4, ST_DOWN = 5, ST_HEAD = 6, ST_ARGMAX = 7 };
+enum Stage : uint32_t { ST_QKV = 0, ST_ATT = 1, ST_COMB = 2, ST_O = 3, ST_GU = 4, ST_DOWN = 5, ST_HEAD = 6, ST_ARGMAX = 7,
+                        ST_RSUM = 6 };   // (inside a layer; ST_HEAD and ST_ARGMAX only exist behind the last one)
+
+// The down projection's K slices leave S partial rows per sequence, which every task of the next operator would read
+// whole.  From about 64 K floats of partial rows on (a level costs about 3.5 us, the re-reading about 0.07 us per thousand
+// floats and workgroup) one extra level in which each workgroup sums a slice of the rows once is cheaper.
+__host__ __device__ inline bool wants_residual_sum(int s_down, int max_batch, int hidden)
+{
+    return s_down > 1 && (long)s_down * max_batch * hidden >= 65536;
+}
 
 enum Pro : uint32_t {
     PRO_EMBED_NORM = 0,  // x = embedding row; store slice; RMSNorm
@@ -80,6 +89,8 @@ __host__ __device__ inline uint32_t chunk_k(uint32_t rlog) { return 512u >> rlog
 // has 2048 / group scales (bf16), index (32 ksub / group) * R + r, in a parallel array.
 __host__ __device__ inline uint32_t chunk_k_w4(uint32_t rlog) { return 2048u >> rlog; }
 
+// OP_RSUM uses the GEMV view: out[b][lo .. hi) = base[b][lo .. hi) + sum of the n_parts partial rows (in slice order), with
+// in_base, in_parts, part_stride, in_ld, cfg (n_parts), xs_lo / xs_hi = [lo, hi) (multiples of 4) and xs_out = out.
 struct Instr {                 // 32 dwords
     uint32_t op;               // 0
     uint32_t flags;            // 1

@@ -412,34 +412,45 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
             }
         }
         wg_sync(lp, lds);
-        for (int b = wave; b < batch; b += kWaves) {         // one wave per sequence
-            const f32x4 *vp = (const f32x4 *)(xs + (size_t)b * seq_stride);
-            float ss = 0.f;
-            for (int q = lane; q < nq4; q += 64) {
-                const f32x4 x = vp[q];
-                ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-            }
-            ss = wave_sum(ss);
-            if (lane == 0) misc[b] = 1.0f / sqrtf(ss / (float)H + P.rms_eps);
-        }
-        for (int b = 0; b < batch; ++b) {
-            const f32x4 *vp = (const f32x4 *)(xs + (size_t)b * seq_stride);
-            f32x4 v[kQuadsPerThread];
+        // The planes of a sequence overwrite its parked row.  Every lane takes its part of the rows of up to kSeqGroup
+        // sequences into registers and adds up its squares (summed over the wavefront with DPP, the four wavefront sums
+        // meet in LDS); one barrier later the rows are scaled and written as planes -- one LDS round trip and one barrier per
+        // group of sequences.  The wavefront sums of consecutive groups use alternating halves of a 32-float area.
+        constexpr int kSeqGroup = 4;
+        for (int b0 = 0, grp = 0; b0 < batch; b0 += kSeqGroup, ++grp) {
+            f32x4 v[kSeqGroup][kQuadsPerThread];
+            float *part = misc + 16 * (grp & 1);
 #pragma unroll
-            for (int j = 0; j < kQuadsPerThread; ++j) {
-                const int q = tid + j * kWgThreads;
-                v[j] = q < nq4 ? vp[q] : f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            wg_sync(lp, lds);      // every lane holds its part of sequence b: the planes may overwrite the parked row
-            const float inv = misc[b];
+            for (int g = 0; g < kSeqGroup; ++g) {
+                const f32x4 *vp = (const f32x4 *)(xs + (size_t)min(b0 + g, batch - 1) * seq_stride);
+                float ss = 0.f;
 #pragma unroll
-            for (int j = 0; j < kQuadsPerThread; ++j) {
-                const int q = tid + j * kWgThreads;
-                if (q < nq4) {
-                    f32x4 y;
-                    y.x = v[j].x * inv * bf_lo(gw[j].x); y.y = v[j].y * inv * bf_hi(gw[j].x);
-                    y.z = v[j].z * inv * bf_lo(gw[j].y); y.w = v[j].w * inv * bf_hi(gw[j].y);
-                    store_x4<true>(xs, b, 4 * q, y, nterm, plane_stride);
+                for (int j = 0; j < kQuadsPerThread; ++j) {
+                    const int q = tid + j * kWgThreads;
+                    v[g][j] = q < nq4 ? vp[q] : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int j = 0; j < kQuadsPerThread; ++j)
+                    ss += (v[g][j].x * v[g][j].x + v[g][j].y * v[g][j].y) + (v[g][j].z * v[g][j].z + v[g][j].w * v[g][j].w);
+                ss = wave_sum(ss);
+                if (lane == 0) part[g * kWaves + wave] = ss;
+            }
+            wg_sync(lp, lds);
+#pragma unroll
+            for (int g = 0; g < kSeqGroup; ++g) {
+                const int b = b0 + g;
+                if (b >= batch) break;
+                const float tot = (part[g * kWaves] + part[g * kWaves + 1]) + (part[g * kWaves + 2] + part[g * kWaves + 3]);
+                const float inv = 1.0f / sqrtf(tot / (float)H + P.rms_eps);
+#pragma unroll
+                for (int j = 0; j < kQuadsPerThread; ++j) {
+                    const int q = tid + j * kWgThreads;
+                    if (q < nq4) {
+                        f32x4 y;
+                        y.x = v[g][j].x * inv * bf_lo(gw[j].x); y.y = v[g][j].y * inv * bf_hi(gw[j].x);
+                        y.z = v[g][j].z * inv * bf_lo(gw[j].y); y.w = v[g][j].w * inv * bf_hi(gw[j].y);
+                        store_x4<true>(xs, b, 4 * q, y, nterm, plane_stride);
+                    }
                 }
             }
         }
@@ -2036,6 +2047,26 @@ __device__ __forceinline__ void comb_task(const Params &P, const InstrAtt &I, ch
     }
 }
 
+// Residual sum: this workgroup's slice of the residual rows of every sequence plus the partial rows a K-sliced
+// projection left, summed in slice order and stored as the new residual (all loads of an item in flight together).
+__device__ __forceinline__ void rsum_task(const Params &P, const Instr &I)
+{
+    constexpr uint32_t kMaxParts = 8;
+    const ActBuf ab = act_buf(P);
+    const uint32_t n4 = (I.xs_hi - I.xs_lo) >> 2, np = min(instr_nparts(I), kMaxParts);
+    const uint32_t items = (uint32_t)P.batch * n4;
+    for (uint32_t it = threadIdx.x; it < items; it += kWgThreads) {
+        const uint32_t b = it / n4, off = b * I.in_ld + I.xs_lo + 4u * (it - b * n4);
+        f32x4 v = ld_act4(ab, I.in_base + off), pv[kMaxParts];
+#pragma unroll
+        for (uint32_t s = 0; s < kMaxParts; ++s) pv[s] = ld_act4(ab, s < np ? I.in_parts + s * I.part_stride + off : kNone);
+#pragma unroll
+        for (uint32_t s = 0; s < kMaxParts; ++s)
+            if (s < np) v += pv[s];
+        st_act4(ab, I.xs_out + off, v);
+    }
+}
+
 // Greedy token of sequence b: reduce the (max logit, row) partials the LM-head tasks left, in slot
 // order (ties: smaller row, i.e. the first maximum), and hand the row to the caller and to the
 // next step of this launch.
@@ -2188,6 +2219,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
         await();
         if (I.op == OP_COMB) comb_task(P, *(const InstrAtt *)&I, lds, lp);
         else if (I.op == OP_ARGMAX) argmax_task(P, *(const InstrAtt *)&I, lds, lp);
+        else if (I.op == OP_RSUM) rsum_task(P, I);
     }
 
     if (PERSISTENT && I.sig_ctr != kNone) {

@@ -451,6 +451,27 @@ struct Builder {
                 if (!emit_gemv(dn, g.down, c_gu, c_d)) return false;
             }
             prev_done = c_d;
+            // ---- residual sum: one level in which each workgroup adds its slice of the down projection's partial rows to
+            //      the residual, instead of every task of the next operator reading all of them
+            if (parts_n && wants_residual_sum(t.s_d, d.Bm, d.H)) {
+                const uint32_t c_rs = new_counter();
+                const int np = std::min(n_wg, d.H / 4);
+                std::vector<int> order = by_load();
+                for (int pi = 0; pi < np; ++pi) {
+                    Instr r{};
+                    r.op = OP_RSUM; r.ref_seq = (uint32_t)l * 8 + ST_RSUM; r.layer = (uint32_t)l;
+                    r.wait_ctr[0] = c_d; r.wait_cnt[0] = ctr_signals[c_d]; r.wait_ctr[1] = kNone;
+                    r.sig_ctr = c_rs; ++ctr_signals[c_rs];
+                    r.cfg = make_cfg(0, 0, 0, parts_n);
+                    r.in_base = res; r.in_parts = parts_off; r.part_stride = (uint32_t)(d.Bm * d.H); r.in_ld = (uint32_t)d.H;
+                    r.xs_lo = 4u * (uint32_t)((uint64_t)(d.H / 4) * pi / np);
+                    r.xs_hi = 4u * (uint32_t)((uint64_t)(d.H / 4) * (pi + 1) / np);
+                    r.xs_out = other(res);
+                    lists[order[pi]].push_back(r); ++n_tasks;
+                    load[order[pi]] += 2.0;
+                }
+                res = other(res); parts_n = 0; prev_done = c_rs;
+            }
         }
         // ---- final norm + LM head (never stores a residual slice)
         Instr h = gemv_proto(ST_HEAD, d.L, g.head, wm.head, 1, PRO_RESID_NORM, parts_n, 0);
@@ -574,14 +595,24 @@ static SimResult simulate(const mk_schedule *s)
                 // one memory round trip per four partials in flight, plus the bytes themselves
                 pro = 0.8 + 0.8 * ((np + 3) / 4) + fl * d.Bm / 1000.0 * pro_us_per_kfloat;
                 if (pr == PRO_COMBINE) pro = 1.6 + fl * d.Bm / 1000.0 * pro_us_per_kfloat;   // all partial rows in flight at once
+                if (s->tl.mfma && pr != PRO_COMBINE) {
+                    // matrix-core staging, fitted to task traces at batch 4 and 8 (1.5B and 7B shapes): every float read
+                    // past the caches costs about 0.07 us per thousand, every staged value (split into two bf16 planes)
+                    // 0.1 us per thousand, the normalising forms one more pass over LDS
+                    const double loaded = fl * d.Bm / 1000.0;
+                    const double staged = (normk ? (double)d.H : (double)I.xs_hi * instr_ck(I)) * d.Bm / 1000.0;
+                    pro = 0.9 + 0.07 * loaded + 0.1 * staged + (normk ? 0.8 : 0.0);
+                }
             }
             // units are flushed through a cross-lane reduction: small R means more flushes per byte
             pro += 0.004 * I.nu;
         } else if (I.op == OP_ATT) {
             bytes = (double)d.Tm / s->tl.nc * d.d * 4.0;
-            pro = 0.5;
+            pro = s->tl.att_mc ? 2.4 : 0.5;   // (matrix-core form: q staging as bf16 columns and the per-wavefront merge)
         } else if (I.op == OP_COMB) {
             pro = 0.3 + s->tl.nc * 0.01;
+        } else if (I.op == OP_RSUM) {
+            pro = 1.2;   // one round trip for the base and partial rows of a slice
         } else {
             pro = 1.0;   // arg-max over the LM-head partials
         }
@@ -923,6 +954,14 @@ void decode_accesses(const mk_schedule *s, const Instr &I, std::vector<Access> &
                     }
                 }
         }
+    } else if (I.op == OP_RSUM) {
+        const uint64_t n = I.xs_hi > I.xs_lo ? I.xs_hi - I.xs_lo : 0;
+        for (int b = 0; b < d.Bm; ++b) {
+            const uint64_t off = (uint64_t)b * I.in_ld + I.xs_lo;
+            rd(I.in_base + off, n);
+            for (uint32_t p = 0; p < instr_nparts(I); ++p) rd(I.in_parts + (uint64_t)p * I.part_stride + off, n);
+            wr(I.xs_out + off, n);
+        }
     } else if (I.op == OP_ATT) {
         const InstrAtt &A = *(const InstrAtt *)&I;
         for (uint32_t p = 0; p < A.n_parts; ++p) {
@@ -965,7 +1004,7 @@ int verify_schedule(const mk_schedule *s)
         for (; i < mi; ++i) {
             const Instr &I = all[(size_t)w * mi + i];
             if (I.op == OP_END) break;
-            if (I.op != OP_GEMV && I.op != OP_ATT && I.op != OP_COMB && I.op != OP_ARGMAX) return fail("unknown opcode");
+            if (I.op != OP_GEMV && I.op != OP_ATT && I.op != OP_COMB && I.op != OP_ARGMAX && I.op != OP_RSUM) return fail("unknown opcode");
             if (I.sig_ctr != kNone) {
                 if (I.sig_ctr >= (uint32_t)s->n_counters) return fail("signal to a counter that does not exist");
                 ++signals[I.sig_ctr];
@@ -1000,9 +1039,18 @@ int verify_schedule(const mk_schedule *s)
                 return fail(buf);
             };
             if (I.layer != l) return bad("layer field does not match the operator instance");
-            const bool tail = st == ST_HEAD || st == ST_ARGMAX;
+            const bool tail = (st == ST_HEAD && I.op != OP_RSUM) || st == ST_ARGMAX;
             if (tail ? l != (uint32_t)d.L : l >= (uint32_t)d.L) return bad("layer out of range");
-            if (I.op == OP_GEMV) {
+            if (I.op == OP_RSUM) {
+                if (st != ST_RSUM) return bad("residual-sum task at the wrong stage");
+                if (!wants_residual_sum(s->tl.s_d, d.Bm, d.H)) return bad("residual-sum task in a schedule that has none");
+                const bool ab = I.in_base == s->am.xa && I.xs_out == s->am.xb, ba = I.in_base == s->am.xb && I.xs_out == s->am.xa;
+                if (!ab && !ba) return bad("residual buffers differ from the plan");
+                if (I.in_parts != s->am.pd || instr_nparts(I) != (uint32_t)s->tl.s_d || I.part_stride != (uint32_t)(d.Bm * d.H) ||
+                    I.in_ld != (uint32_t)d.H)
+                    return bad("partial-row description differs from the plan");
+                if ((I.xs_lo | I.xs_hi) & 3u || I.xs_lo >= I.xs_hi || I.xs_hi > (uint32_t)d.H) return bad("residual slice out of range");
+            } else if (I.op == OP_GEMV) {
                 const MatGeom *m = nullptr;
                 uint32_t chunk = 0, gain = kNone, bias = kNone;
                 int S = 1;
@@ -1075,6 +1123,8 @@ int verify_schedule(const mk_schedule *s)
                     if (I.nu == 0 || I.S == 0 || I.nkb == 0) return fail("empty GEMV task");
                     units[I.ref_seq].push_back({I.u0, I.u0 + I.nu});
                     if (I.flags & F_ARGMAX) slots.push_back(I.spare);
+                } else if (I.op == OP_RSUM) {
+                    units[I.ref_seq].push_back({I.xs_lo, I.xs_hi});   // (slices of the hidden dimension)
                 } else {
                     const InstrAtt &A = *(const InstrAtt *)&I;
                     if (I.op == OP_ATT && (A.nh == 0 || A.h0 + A.nh > (uint32_t)d.G)) return fail("attention task with an empty or out-of-group head range");
@@ -1100,8 +1150,12 @@ int verify_schedule(const mk_schedule *s)
                 {ST_QKV, (uint32_t)gm.qkv.groups * s->tl.s_qkv}, {ST_O, (uint32_t)gm.o.groups * s->tl.s_o},
                 {ST_GU, (uint32_t)gm.gu.groups * s->tl.s_gu}, {ST_DOWN, (uint32_t)gm.down.groups * s->tl.s_d},
                 {ST_HEAD, (uint32_t)gm.head.groups}};
+            if (l < d.L) {   // (stage 6 inside a layer: the residual-sum slices tile the hidden dimension, or there are none)
+                g[4].st = ST_RSUM;
+                g[4].total = wants_residual_sum(s->tl.s_d, d.Bm, d.H) ? (uint32_t)d.H : 0u;
+            }
             for (auto &e : g) {
-                if ((l == d.L) != (e.st == ST_HEAD)) continue;
+                if (l == d.L && e.st != ST_HEAD) continue;
                 auto &v = units[l * 8 + e.st];
                 std::sort(v.begin(), v.end());
                 uint32_t at = 0;

@@ -54,15 +54,18 @@ def report(tr, seq, layer: int, out=sys.stdout) -> None:
         t0, t1, t2, t3 = (us(tr[..., k][m]) for k in range(4))
         rows[int(sq)] = (t0, t1, t2, t3)
     per_stage = {}
+    n_layers = int(seq[valid].max()) // 8       # the LM head and the arg-max tasks carry the index one past the last layer
+    # stage 6 inside a layer is the residual-sum level that follows a K-sliced down projection
+    name = lambda l, st: "RSUM" if (st == 6 and l < n_layers) else STAGES.get(st, st)
     for sq, (t0, t1, t2, t3) in rows.items():
         l, st = divmod(sq, 8)
-        per_stage.setdefault(st, []).append((t3.max() - t0.min(), (t1 - t0).mean(), (t2 - t1).mean(), (t3 - t2).mean()))
-        if l != layer and not (st >= 6):
+        per_stage.setdefault((st, name(l, st)), []).append((t3.max() - t0.min(), (t1 - t0).mean(), (t2 - t1).mean(), (t3 - t2).mean()))
+        if l != layer and l < n_layers:
             continue
         gap = ""
         if prev_end is not None:
             gap = f"{t2.min() - prev_end:6.1f} / {t2.max() - prev_end:6.1f}"
-        print(f"L{l:02d} {STAGES.get(st, st):6s} {len(t0):5d} | {t0.min():7.1f} {np.median(t0):7.1f} {t0.max():7.1f} | "
+        print(f"L{l:02d} {name(l, st):6s} {len(t0):5d} | {t0.min():7.1f} {np.median(t0):7.1f} {t0.max():7.1f} | "
               f"{np.median(t1):7.1f} {t1.max():7.1f} | {t3.min():7.1f} {np.median(t3):7.1f} {t3.max():7.1f} | "
               f"{(t1 - t0).mean():5.2f} {(t2 - t1).mean():5.2f} {(t3 - t2).mean():6.2f} | {gap}", file=out)
         prev_end = t3.max()
@@ -84,7 +87,7 @@ def report(tr, seq, layer: int, out=sys.stdout) -> None:
     print("mean over all layers: level span (first begin to last end), wait, prologue, body [us]", file=out)
     for st in sorted(per_stage):
         a = np.array(per_stage[st]).mean(0)
-        print(f"  {STAGES.get(st, st):6s} {a[0]:7.2f} {a[1]:6.2f} {a[2]:6.2f} {a[3]:6.2f}", file=out)
+        print(f"  {st[1]:6s} {a[0]:7.2f} {a[1]:6.2f} {a[2]:6.2f} {a[3]:6.2f}", file=out)
 
 
 def main() -> int:

@@ -211,6 +211,31 @@ def test_partial_batches_of_a_wider_schedule():
     pr.close()
 
 
+def test_residual_sum_level_after_a_k_sliced_down_projection():
+    """Eight sequences and a down projection in eight K slices (64 K floats of partial rows): its partial rows are summed into the residual by a level
+    of their own (one slice of the rows per workgroup) instead of by every task of the next operator.  Same results as
+    the oracle, and bit-identical to the per-operator launches of the same schedule."""
+    full = tiny(max_batch=8, hidden=1024, index=13)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    pr = Pair(cfg, w, split_down=8, split_o=2)
+    assert pr.dec.stats["split_down"] == 8 and pr.dec.stats["use_mfma"] == 1
+    ops = {int(mk.mk_instr_get(pr.dec.h, wg, i)[0]) for wg in range(0, 256, 5) for i in range(mk.mk_instr_count(pr.dec.h, wg))}
+    assert 5 in ops, "no residual-sum task in the schedule"
+    toks = [3 + 5 * b for b in range(8)]
+    for s_, poss in enumerate(([0] * 8, [1, 1, 1, 1, 1, 1, 1, 1], [2, 2, 2, 2, 2, 2, 2, 2])):
+        say("residual-sum level, step", s_)
+        want = pr.orc.step(toks, poss, pr.kv_h)
+        got = pr.gpu_step(toks, poss)
+        again = pr.gpu_step(toks, poss, per_op=True)
+        for b in range(8):
+            assert rel_err(got[b], want[b]) <= 1e-3, (s_, b)
+            assert int(got[b].argmax()) == oracle.argmax(want[b])
+        assert np.array_equal(got, again)
+        toks = [oracle.argmax(want[b]) for b in range(8)]
+    pr.close()
+
+
 def test_ring_and_direct_kernels_agree_bit_for_bit():
     """The page ring changes where the weights wait (LDS instead of registers), not the arithmetic:
     on the same schedule the ring kernel, the direct-load kernel and the per-operator launches

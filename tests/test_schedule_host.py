@@ -399,6 +399,35 @@ def test_k_sliced_down_projection_keeps_a_workgroups_units_inside_one_slice():
     _expect_rejected(h, "staged input range")
 
 
+def test_residual_sum_level_exists_where_many_partial_rows_would_be_reread():
+    """7B shape, batch 8, down projection in 8 K slices: 64 partial rows.  The schedule sums them in a level of its own
+    (op 5, one slice of the hidden dimension per workgroup); the next layer's QKV tasks then read one row per sequence.
+    At batch 1 there is no such level."""
+    cfg = synth.model_cfg(synth.CONFIGS["c4_7b"], max_batch=8)
+    h = mk.mk_build_schedule(mk.make_config(cfg, n_workgroups=256, flags=mk.MK_F_NO_TABLE, split_down=8))
+    mk.mk_schedule_verify(h)
+    covered = []
+    for wg in range(256):
+        for i in range(mk.mk_instr_count(h, wg)):
+            w = mk.mk_instr_get(h, wg, i)
+            if w[OP] == 5 and w[LAYER] == 3:
+                assert w[REF_SEQ] == 3 * 8 + 6 and (int(w[CFG]) >> 16) & 255 == 8
+                covered.append((int(w[XS_LO]), int(w[XS_N])))       # (for this op: slice [lo, hi) of the hidden dimension)
+            if w[OP] == 1 and w[REF_SEQ] == 4 * 8 + 0:
+                assert (int(w[CFG]) >> 16) & 255 == 0                # the next QKV reads no partial rows
+    covered.sort()
+    assert covered[0][0] == 0 and covered[-1][1] == cfg["hidden"]
+    assert all(a[1] == b[0] for a, b in zip(covered, covered[1:]))
+    # a slice that overlaps its neighbour is rejected
+    wg, i, w = _anywhere(h, lambda w: w[OP] == 5 and w[XS_LO] > 0)
+    w[XS_LO] -= 4
+    mk.mk_instr_set(h, wg, i, w)
+    _expect_rejected(h)
+    h1 = build("c2_1p5b")
+    assert all(mk.mk_instr_get(h1, wg, i)[OP] != 5 for wg in (0, 100, 255) for i in range(mk.mk_instr_count(h1, wg)))
+    mk.mk_destroy(h1)
+
+
 def test_verifier_rejects_list_without_end_and_unknown_opcode():
     h = build("c0_tiny")
     w = mk.mk_instr_get(h, 0, 0)
