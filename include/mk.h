@@ -218,11 +218,11 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *token_ids, const int32_
 /* mk_decode_step for callers that cannot allocate device memory or let a library do so (code under
  * HIP graph capture, tight serving loops, harnesses that forbid it): the same single launch with the
  * same arguments and results, but the step's scratch (activations, partial sums, dependency counters,
- * error flags) lives in a device array built into the library, 8 MiB per GPU, held until the process
+ * error flags) lives in a device array built into the library, 16 MiB per GPU, held until the process
  * ends, instead of in the bound workspace.  The call makes no allocation of any kind; weights,
  * instruction lists and the RoPE table are still read from the workspace bound earlier.
- *   - MK_ENOMEM if the schedule's scratch (mk_get_stats: activations + counters) exceeds 8 MiB
- *     (all shapes up to the 7B one at batch 8 fit).
+ *   - MK_ENOMEM if the schedule's scratch (mk_get_stats: activations + counters) exceeds 16 MiB
+ *     (every workload of the benchmark fits; the largest, the 1.7B shape at batch 16, needs 11.8 MB).
  *   - Every call on a GPU shares that GPU's one array: calls that overlap in time on the same GPU (two
  *     streams, two handles) race.  When the handle changes between calls the counters are re-zeroed by a
  *     small fill kernel on `stream` first.

@@ -63,7 +63,7 @@ std::vector<const void *> all_walk_kernels()
 // ---- scratch of the allocation-free entry point -------------------------------------------------
 // One array per GPU, held until the process ends.  `mk_static_scratch` names the array in device
 // code only; host code uses the address hipGetSymbolAddress returns for the device that is current.
-constexpr size_t kStaticScratchBytes = 8u << 20;
+constexpr size_t kStaticScratchBytes = 16u << 20;
 static __device__ __align__(256) unsigned char mk_static_scratch[kStaticScratchBytes];
 
 struct StaticScratch {

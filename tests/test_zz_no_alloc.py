@@ -59,11 +59,11 @@ def test_static_scratch_entry_point_matches_the_workspace_one():
     _step_both(*small)          # same handle again: its counters carry on from the previous epoch
     _step_both(*big)
     # a schedule whose scratch cannot fit is refused before anything is launched
-    cfg = synth.model_cfg(synth.CONFIGS["c4_7b"], max_batch=8)
+    cfg = synth.model_cfg(synth.CONFIGS["c5_1p7b"], max_batch=16)
     h = mk.mk_build_schedule(mk.make_config(cfg, attn_chunks=64))
-    t = torch.zeros(8, dtype=torch.int32, device=DEV)
+    t = torch.zeros(16, dtype=torch.int32, device=DEV)
     with pytest.raises(mk.MkError) as e:
-        mk.mk_decode_step_static(h, t, t, t, t, 8)
+        mk.mk_decode_step_static(h, t, t, t, t, 16)
     assert e.value.code == mk.MK_ENOMEM and "static array" in str(e.value)
     mk.mk_destroy(h)
     for c in (big, small):
