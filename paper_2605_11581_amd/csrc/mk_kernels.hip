@@ -353,8 +353,8 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
     constexpr uint32_t kNone = 0xfffffff0u;            // beyond the descriptor: the load returns zeros
 
     if (pro == PRO_EMBED_NORM || pro == PRO_RESID_NORM) {
-        const int H = P.hidden, nq4 = H >> 2;
-        const uint32_t plane_stride = (uint32_t)H * 2u + 16u;
+        const int H = P.hidden, nq4 = H >> 2, total = batch * nq4;
+        const uint32_t plane_stride = (uint32_t)H * 2u + 16u, seq_stride = (uint32_t)nterm * plane_stride;
         const uint16_t *gain = (const uint16_t *)(P.ws + P.lay.vecs) + I.gain;
         uint2 gw[kQuadsPerThread];                       // constants: fetched with the input loads
 #pragma unroll
@@ -362,73 +362,76 @@ __device__ __forceinline__ bool gemv_prologue_batched(const Params &P, const Ins
             const int q = tid + j * kWgThreads;
             gw[j] = q < nq4 ? *(const uint2 *)(gain + 4 * q) : uint2{0u, 0u};
         }
-        // Up to kSeqGroup sequences at a time, entirely in registers: thread t holds quads t, t + 256, ... of every row of the
-        // group (all loads of the group in flight together: one memory round trip, partial rows two at a time), stores its
-        // part of the new residual slice, adds up its squares (summed over the wavefront with DPP, the four wavefront
-        // sums meet in LDS), and one barrier later scales the rows and writes them as bf16 planes.  The wavefront sums of
-        // consecutive groups use alternating halves of a 32-float area.
+        for (int e0 = tid; e0 < total; e0 += kWgThreads * kItems) {
+            f32x4 v[kItems];
+            uint32_t off[kItems];                        // b * in_ld + 4 q of the item, kNone past the end
+            int bq[kItems];                              // b << 16 | q
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                const int e = e0 + u * kWgThreads;
+                const int b = e / nq4, q = e - b * nq4;
+                off[u] = e < total ? (uint32_t)b * I.in_ld + 4u * (uint32_t)q : kNone;
+                bq[u] = (b << 16) | q;
+            }
+            if (pro == PRO_EMBED_NORM) {
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) {
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (off[u] != kNone) {
+                        const int tok = token_of(P, lp, bq[u] >> 16), k = 4 * (bq[u] & 0xffff);
+                        x.x = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k);
+                        x.y = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 1);
+                        x.z = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 2);
+                        x.w = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 3);
+                    }
+                    v[u] = x;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) v[u] = ld_act4(ab, off[u] != kNone ? I.in_base + off[u] : kNone);
+                // the producer's partial sums, two partials of every item in flight, added in order
+                for (uint32_t s0 = 0; s0 < n_parts; s0 += 2) {
+                    f32x4 t0[kItems], t1[kItems];
+                    const uint32_t p0 = I.in_parts + s0 * I.part_stride, p1 = p0 + I.part_stride;
+                    const bool two = s0 + 1 < n_parts;
+#pragma unroll
+                    for (int u = 0; u < kItems; ++u) {
+                        t0[u] = ld_act4(ab, off[u] != kNone ? p0 + off[u] : kNone);
+                        t1[u] = ld_act4(ab, (two && off[u] != kNone) ? p1 + off[u] : kNone);
+                    }
+#pragma unroll
+                    for (int u = 0; u < kItems; ++u) { v[u] += t0[u]; v[u] += t1[u]; }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                if (off[u] == kNone) continue;
+                const int b = bq[u] >> 16, q = bq[u] & 0xffff;
+                if ((uint32_t)(4 * q) >= I.xs_lo && (uint32_t)(4 * q) < I.xs_hi) st_act4(ab, I.xs_out + off[u], v[u]);
+                *(f32x4 *)(xs + (size_t)b * seq_stride + (size_t)q * 16) = v[u];
+            }
+        }
+        wg_sync(lp, lds);
+        // The planes of a sequence overwrite its parked row.  Every lane takes its part of the rows of up to kSeqGroup
+        // sequences into registers and adds up its squares (summed over the wavefront with DPP, the four wavefront sums
+        // meet in LDS); one barrier later the rows are scaled and written as planes -- one LDS round trip and one barrier per
+        // group of sequences.  The wavefront sums of consecutive groups use alternating halves of a 32-float area.
         constexpr int kSeqGroup = 4;
         for (int b0 = 0, grp = 0; b0 < batch; b0 += kSeqGroup, ++grp) {
             f32x4 v[kSeqGroup][kQuadsPerThread];
             float *part = misc + 16 * (grp & 1);
-            auto off_of = [&](int g, int j) -> uint32_t {
-                const int q = tid + j * kWgThreads;
-                return (b0 + g < batch && q < nq4) ? (uint32_t)(b0 + g) * I.in_ld + 4u * (uint32_t)q : kNone;
-            };
-            if (pro == PRO_EMBED_NORM) {
-#pragma unroll
-                for (int g = 0; g < kSeqGroup; ++g) {
-                    const int tok = b0 + g < batch ? token_of(P, lp, b0 + g) : 0;
-#pragma unroll
-                    for (int j = 0; j < kQuadsPerThread; ++j) {
-                        f32x4 x = {0.f, 0.f, 0.f, 0.f};
-                        if (off_of(g, j) != kNone) {
-                            const int k = 4 * (tid + j * kWgThreads);
-                            x.x = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k);
-                            x.y = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 1);
-                            x.z = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 2);
-                            x.w = tile_elem(P.ws + P.lay.weights, P.embed_chunk, P.embed_kbt, P.embed_rlog, tok, k + 3);
-                        }
-                        v[g][j] = x;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int g = 0; g < kSeqGroup; ++g)
-#pragma unroll
-                    for (int j = 0; j < kQuadsPerThread; ++j) {
-                        const uint32_t o = off_of(g, j);
-                        v[g][j] = ld_act4(ab, o != kNone ? I.in_base + o : kNone);
-                    }
-                // the producer's partial sums, two partials of every quad in flight, added in order
-                for (uint32_t s0 = 0; s0 < n_parts; s0 += 2) {
-                    f32x4 t0[kSeqGroup][kQuadsPerThread], t1[kSeqGroup][kQuadsPerThread];
-                    const uint32_t p0 = I.in_parts + s0 * I.part_stride, p1 = p0 + I.part_stride;
-                    const bool two = s0 + 1 < n_parts;
-#pragma unroll
-                    for (int g = 0; g < kSeqGroup; ++g)
-#pragma unroll
-                        for (int j = 0; j < kQuadsPerThread; ++j) {
-                            const uint32_t o = off_of(g, j);
-                            t0[g][j] = ld_act4(ab, o != kNone ? p0 + o : kNone);
-                            t1[g][j] = ld_act4(ab, (two && o != kNone) ? p1 + o : kNone);
-                        }
-#pragma unroll
-                    for (int g = 0; g < kSeqGroup; ++g)
-#pragma unroll
-                        for (int j = 0; j < kQuadsPerThread; ++j) { v[g][j] += t0[g][j]; v[g][j] += t1[g][j]; }
-                }
-            }
 #pragma unroll
             for (int g = 0; g < kSeqGroup; ++g) {
+                const f32x4 *vp = (const f32x4 *)(xs + (size_t)min(b0 + g, batch - 1) * seq_stride);
                 float ss = 0.f;
 #pragma unroll
                 for (int j = 0; j < kQuadsPerThread; ++j) {
-                    const uint32_t o = off_of(g, j);
-                    const uint32_t k = 4u * (uint32_t)(tid + j * kWgThreads);
-                    if (o != kNone && k >= I.xs_lo && k < I.xs_hi) st_act4(ab, I.xs_out + o, v[g][j]);
-                    ss += (v[g][j].x * v[g][j].x + v[g][j].y * v[g][j].y) + (v[g][j].z * v[g][j].z + v[g][j].w * v[g][j].w);
+                    const int q = tid + j * kWgThreads;
+                    v[g][j] = q < nq4 ? vp[q] : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
+#pragma unroll
+                for (int j = 0; j < kQuadsPerThread; ++j)
+                    ss += (v[g][j].x * v[g][j].x + v[g][j].y * v[g][j].y) + (v[g][j].z * v[g][j].z + v[g][j].w * v[g][j].w);
                 ss = wave_sum(ss);
                 if (lane == 0) part[g * kWaves + wave] = ss;
             }
