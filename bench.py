@@ -240,6 +240,37 @@ def run_workload(config: str, batch: int, w4: bool, steps: int, warmup: int, rep
         out["per_op_baseline"] = {"ms_per_step": round(po * 1e3, 5), "tokens_per_s": round(B / po, 2),
                                   "launches_per_step": cfg["n_layers"] * (6 - st["fuse_combine"] + residual_sum) + 2, "steps": n_po,
                                   "speedup_of_one_launch": round(po * 1e3 / ms_per_step, 3)}
+        # The same per-operator launches recorded ONCE into a HIP graph and replayed (Sec. 2: launch overhead that graphs
+        # do not remove, since every operator is still a kernel boundary).  The recorded work is kernels only; positions
+        # advance inside the graph.
+        try:
+            tg, pg = toks[warmup].clone(), poss[warmup].clone()
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                dec.step(tg, pg, kv_d, logits, per_op=True, stream=side)      # (eager once on the capture stream)
+                graph.capture_begin()
+                dec.step(tg, pg, kv_d, logits, per_op=True, stream=side)
+                pg.add_(1)
+                graph.capture_end()
+            stream.wait_stream(side)
+            pg.copy_(poss[warmup])
+            torch.cuda.synchronize()
+            graph.replay(); graph.replay()
+            pg.copy_(poss[warmup])
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            for _ in range(n_po):
+                graph.replay()
+            torch.cuda.synchronize()
+            pg_ms = (time.perf_counter() - t3) / n_po * 1e3
+            dec.check()
+            out["per_op_baseline"]["graph_replay_ms_per_step"] = round(pg_ms, 5)
+            out["per_op_baseline"]["speedup_of_one_launch_over_graph"] = round(pg_ms / ms_per_step, 3)
+            del graph
+        except Exception as exc:                                            # the baseline is a side figure: never lose the line
+            out["per_op_baseline"]["graph_replay_error"] = str(exc)[:200]
 
     if cpu_baseline:
         note("GPU legs done; CPU oracle")

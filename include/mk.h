@@ -224,8 +224,13 @@ int mk_decode_step_per_op(mk_schedule *s, const int32_t *token_ids, const int32_
  *   - MK_ENOMEM if the schedule's scratch (mk_get_stats: activations + counters) exceeds 16 MiB
  *     (every workload of the benchmark fits; the largest, the 1.7B shape at batch 16, needs 11.8 MB).
  *   - Every call on a GPU shares that GPU's one array: calls that overlap in time on the same GPU (two
- *     streams, two handles) race.  When the handle changes between calls the counters are re-zeroed by a
- *     small fill kernel on `stream` first.
+ *     streams, two handles) race.  When the handle changes between calls the counters are re-zeroed on
+ *     `stream` first.
+ *   - The step number the dependency counters are compared with lives in the array too, and a one-workgroup
+ *     kernel ahead of the step advances it: a call recorded into a HIP graph replays correctly (the recorded
+ *     work is kernels only; tokens, positions and the cache are read through the pointers given at capture).
+ *     mk_decode_step and mk_decode_steps pass that number as a kernel argument instead: a recorded call of
+ *     theirs must not be replayed.
  *   - mk_check after such a step reports the flags of the static array. */
 int mk_decode_step_static(mk_schedule *s, const int32_t *token_ids, const int32_t *positions,
                           void *kv_cache, float *logits_out, int32_t batch, void *stream);

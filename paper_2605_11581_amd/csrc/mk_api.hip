@@ -69,7 +69,6 @@ static __device__ __align__(256) unsigned char mk_static_scratch[kStaticScratchB
 struct StaticScratch {
     char *ptr = nullptr;      // device address of this GPU's copy of the array
     uint64_t owner = 0;       // serial of the schedule whose counters the array holds (0: none)
-    uint32_t epoch = 0;       // steps that schedule has run on the array since its counters were zeroed
 };
 constexpr int kMaxDevices = 64;
 StaticScratch g_static[kMaxDevices];
@@ -511,17 +510,21 @@ int mk_decode_step_static(mk_schedule *s, const int32_t *tokens, const int32_t *
     rc = static_scratch_of(s->device, &ss);
     if (rc) return rc;
     if (!s->serial) s->serial = ++g_serial;
-    if (ss->owner != s->serial || ss->epoch >= 0x00800000u) {
-        // the array holds another schedule's counters (or none, or this one's are about to wrap): start from zero.
-        // Fill kernels, not memsets: the call may be recorded into a graph.
-        rc = fill_u32(ss->ptr + sp.counters, 0u, (size_t)s->n_counters * mk::kCounterDwords, st);
-        if (rc) return rc;
+    // The step number lives in the array itself and a one-workgroup kernel advances it ahead of every step (and zeroes the
+    // counters when the array holds another schedule's, or none, or the number nears the wrap range): a call recorded
+    // into a graph therefore replays correctly.  Kernels, not memsets, for the same reason.
+    const uint32_t reset = ss->owner != s->serial ? 1u : 0u;
+    if (reset) {
         rc = fill_u32(ss->ptr + sp.err, 0u, 16, st);
         if (rc) return rc;
-        ss->owner = s->serial; ss->epoch = 0;
+        ss->owner = s->serial;
     }
+    uint32_t *epoch_dev = (uint32_t *)(ss->ptr + sp.tokens + 2048);
+    hipLaunchKernelGGL(mk_static_begin_kernel, dim3(1), dim3(1024), 0, st, epoch_dev, (uint32_t *)(ss->ptr + sp.counters),
+                       (size_t)s->n_counters * mk::kCounterDwords, reset);
+    HIP_TRY(hipGetLastError());
     mk::Params P = make_params(s, tokens, positions, kv, logits, batch, nullptr, 1, ss->ptr);
-    P.epoch = ++ss->epoch;
+    P.epoch = 0; P.epoch_ptr = epoch_dev;
     mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
     hipLaunchKernelGGL(walk_kernel(s, 1), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
     HIP_TRY(hipGetLastError());

@@ -228,6 +228,8 @@ struct Params {
     int32_t qk_norm;
     float rms_eps;
     uint32_t epoch;       // step number since the counters were last zeroed (>= 1)
+    const uint32_t *epoch_ptr;   // non-null: the step number is read from device memory instead (a launch recorded into a graph
+                                 // then finds the right number at every replay)
     uint32_t spin_limit;
     uint32_t max_instr;
     uint32_t flags;

@@ -2258,7 +2258,11 @@ __device__ __forceinline__ Wg make_wg(const Params &P, const LdsPlan &p, char *l
     wg.pf_ptr = wg.pf_begin = (cptr)(uintptr_t)((const uint32_t *)(P.ws + P.lay.stream) + (size_t)blockIdx.x * P.max_instr * 2);
     wg.pf_left = P.max_instr;
     wg.pf_steps = P.n_steps > 0 ? (uint32_t)P.n_steps - 1u : 0u;
-    wg.epoch = P.epoch; wg.pos_off = 0; wg.tok_src = P.tokens; wg.tok_out = P.next_tokens; wg.logits = P.logits;
+    wg.epoch = P.epoch; wg.pos_off = 0;
+    if (P.epoch_ptr) {
+        typedef const __attribute__((address_space(1))) uint32_t *gptr;
+        wg.epoch = rfl(__hip_atomic_load((gptr)(uintptr_t)P.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    } wg.tok_src = P.tokens; wg.tok_out = P.next_tokens; wg.logits = P.logits;
     wg.pf_src = nullptr; wg.pf_rem = 0; wg.pf_live = wg.ring && wg.nst > 0;
     return wg;
 }
@@ -2468,6 +2472,21 @@ extern "C" __global__ void mk_copy_u16_kernel(const uint16_t *src, uint16_t *dst
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < n) dst[gid] = src[gid];
+}
+
+// Opens a step on the static scratch array (one workgroup): advances the step number kept in device memory and, when
+// asked to or when the number comes near the range where (step number x signals) would wrap, zeroes the dependency
+// counters and starts again from 1.  Being a kernel, it does the right thing at every replay of a recorded graph.
+extern "C" __global__ void __launch_bounds__(1024) mk_static_begin_kernel(uint32_t *epoch, uint32_t *counters, size_t n_dwords, uint32_t reset)
+{
+    __shared__ uint32_t cur;
+    if (threadIdx.x == 0) cur = *epoch;
+    __syncthreads();
+    const bool zero = reset != 0u || cur >= 0x00800000u;
+    if (zero)
+        for (size_t i = threadIdx.x; i < n_dwords; i += blockDim.x) counters[i] = 0u;
+    __syncthreads();
+    if (threadIdx.x == 0) *epoch = zero ? 1u : cur + 1u;
 }
 
 extern "C" __global__ void mk_fill_u32_kernel(uint32_t *dst, uint32_t v, size_t n)

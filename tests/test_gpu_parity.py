@@ -258,6 +258,40 @@ def test_ring_and_direct_kernels_agree_bit_for_bit():
     pr.close()
 
 
+def test_per_operator_launches_replayed_from_a_graph_match_eager():
+    """The per-operator baseline recorded once into a graph (kernels only) and replayed, with eager work and
+    synchronisations between the replays: every replay equals the eager single-launch step bit for bit."""
+    full = tiny(index=17)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    pr = Pair(cfg, w)
+    pr.prefill(synth.make_prompt(full, 30)[:-1])
+    kv_g = pr.kv_d.clone()
+    t = torch.tensor([9], dtype=torch.int32, device=DEV)
+    p = torch.tensor([29], dtype=torch.int32, device=DEV)
+    lg = torch.zeros_like(pr.logits)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        pr.dec.step(t, p, kv_g, lg, per_op=True, stream=side)
+        graph.capture_begin()
+        pr.dec.step(t, p, kv_g, lg, per_op=True, stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(4):
+        say("graph replay", r)
+        t.fill_(9 + 7 * r)
+        p.fill_(29 + r)
+        lg.fill_(float("nan"))
+        eager = pr.gpu_step([9 + 7 * r], [29 + r])[0]
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(lg[0].cpu().numpy(), eager), f"replay {r} differs from the eager step"
+        assert torch.equal(kv_g, pr.kv_d)
+    pr.close()
+
+
 def test_cache_rows_beyond_the_position_are_never_used():
     """KV slots at and after the current position hold whatever the caller left there (here NaN and
     Inf bit patterns); masked positions must contribute exactly nothing."""

@@ -68,3 +68,46 @@ def test_static_scratch_entry_point_matches_the_workspace_one():
     mk.mk_destroy(h)
     for c in (big, small):
         c[2].close()
+
+
+def test_static_scratch_step_recorded_into_a_graph_replays_correctly():
+    """The step number of the static-array entry point lives on the device, so a recorded call can be replayed.  Every
+    replay (with eager work and synchronisations of the program between the replays) must give what the eager
+    workspace entry point gives for the same tokens and positions: bit-identical logits and cache rows."""
+    cfg, orc, dec, kv_h, toks, poss = _case(2, 2, 5)
+    B = 2
+    t = torch.from_numpy(toks).to(DEV); p = torch.from_numpy(poss).to(DEV)
+    kv_g, kv_e = dec.new_kv(kv_h), dec.new_kv(kv_h)
+    lg = torch.full((B, cfg["vocab"]), float("nan"), device=DEV)
+    le = torch.full((B, cfg["vocab"]), float("nan"), device=DEV)
+    # one eager step first (the array then belongs to this schedule), then record one step
+    mk.mk_decode_step_static(dec.h, t, p, kv_g, lg, B)
+    dec.check()
+    mk.mk_decode_step(dec.h, t, p, kv_e, le, B)
+    dec.check()
+    assert torch.equal(lg, le)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        mk.mk_decode_step_static(dec.h, t, p, kv_g, lg, B, stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(4):
+        # eager work of the program between the replays: new tokens and positions, the reference step, a host sync
+        t.copy_(torch.from_numpy(((toks.astype(np.int64) * (r + 3) + 11 * r) % cfg["vocab"]).astype(np.int32)))
+        p.add_(1)
+        lg.fill_(float("nan"))
+        mk.mk_decode_step(dec.h, t, p, kv_e, le, B)
+        dec.check()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(lg.cpu().numpy()).all(), r
+        assert torch.equal(lg, le), f"replay {r} differs from the eager step"
+        assert torch.equal(kv_g, kv_e), f"replay {r}: cache rows differ"
+    want = orc.step(t.cpu().numpy(), p.cpu().numpy(), kv_e.cpu().numpy().view(np.uint16).copy())
+    got = lg.cpu().numpy()
+    for i in range(B):
+        assert float(np.abs(got[i] - want[i]).max() / np.abs(want[i]).max()) <= TOL
+    dec.close()
