@@ -2282,8 +2282,9 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
     // A launch walks the list once per decode step.  Step s decodes the greedy tokens of step s-1 at
     // the caller's positions + s; its tasks are ordered after step s-1 by the arg-max counter.
     const int n_steps = MULTI ? P.n_steps : 1;   // the single-step kernel keeps the step context constant
+    const uint32_t epoch0 = lp.epoch;            // (the launch's argument, or the number kept in device memory)
     for (int step = 0; step < n_steps; ++step) {
-        lp.epoch = P.epoch + (uint32_t)step;
+        lp.epoch = epoch0 + (uint32_t)step;
         lp.pos_off = step;
         lp.tok_src = step ? P.next_tokens + (size_t)(step - 1) * P.batch : P.tokens;
         lp.tok_out = P.next_tokens + (size_t)step * P.batch;
