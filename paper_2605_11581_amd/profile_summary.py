@@ -37,17 +37,26 @@ def stats(src: str, out: str, cmd: str) -> None:
 
 
 def _counter(src: str, name: str):
+    """kernel name -> counter values of its dispatches, in dispatch order."""
+    rows = [r for r in csv.DictReader(open(_one(os.path.join(src, "**", "*_counter_collection.csv")))) if r["Counter_Name"] == name]
+    rows.sort(key=lambda r: int(r.get("Dispatch_Id") or 0))
     acc = collections.defaultdict(list)
-    for r in csv.DictReader(open(_one(os.path.join(src, "**", "*_counter_collection.csv")))):
-        if r["Counter_Name"] == name:
-            acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    for r in rows:
+        acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
     return acc
+
+
+def _calibration(values) -> float:
+    """The benchmark runs its three 1 GiB calibration copies before anything else: the median of the first three
+    dispatches of the runtime's copy kernel (later copies of other sizes belong to the workload)."""
+    first = sorted(values[:3])
+    return first[len(first) // 2] if first else 0.0
 
 
 def pmc(fetch_dir: str, write_dir: str, out: str, cmd: str, kernel: str = "mk_megakernel") -> None:
     fe, wr = _counter(fetch_dir, "FETCH_SIZE"), _counter(write_dir, "WRITE_SIZE")
-    copy_f = max(fe.get("__amd_rocclr_copyBuffer", [0.0]))
-    copy_w = max(wr.get("__amd_rocclr_copyBuffer", [0.0]))
+    copy_f = _calibration(fe.get("__amd_rocclr_copyBuffer", []))
+    copy_w = _calibration(wr.get("__amd_rocclr_copyBuffer", []))
     # the calibration copy moves exactly 1 GiB each way
     kf = GIB_KIB / copy_f if copy_f else float("nan")
     kw = GIB_KIB / copy_w if copy_w else float("nan")
