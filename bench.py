@@ -39,7 +39,7 @@ SHAPE_NAMES = {"c0_tiny": "tiny Qwen2-style", "c1_0p5b": "Qwen2.5-0.5B-shaped", 
 # on the two model shapes it measures.
 ALL_WORKLOADS = [("c2_1p5b", 1, False, 0, 0), ("c1_0p5b", 1, False, 0, 0), ("c3_4b", 1, False, 0, 0), ("c4_7b", 1, False, 0, 0),
                  ("c4_7b", 4, False, 0, 0), ("c4_7b", 8, False, 0, 0), ("c2_1p5b", 1, True, 0, 0), ("c2_1p5b", 4, False, 0, 0),
-                 ("c2_1p5b", 8, False, 0, 0)] + [
+                 ("c2_1p5b", 8, False, 0, 0), ("c2_1p5b", 4, True, 0, 0), ("c2_1p5b", 8, True, 0, 0)] + [
     (name, b, False, 64, 12) for name in ("c2_1p5b", "c5_1p7b") for b in (1, 2, 4, 8, 16)]
 
 
