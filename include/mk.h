@@ -208,6 +208,18 @@ int mk_decode_step(mk_schedule *s, const int32_t *token_ids, const int32_t *posi
 int mk_decode_steps(mk_schedule *s, const int32_t *token_ids, const int32_t *positions, void *kv_cache,
                     float *logits_out, int32_t *tokens_out, int32_t batch, int32_t n_steps, void *stream);
 
+/* Fills the cache from known tokens (a prompt) with the decode path itself: n_tokens decode steps as ONE persistent
+ * launch, step s decoding token_ids[s][b] at positions[b] + s for every sequence b < batch, with no token feedback, no
+ * LM head and no logits (the LM-head tasks only keep their place in the dependency chain).  Token by token this is
+ * mathematically the batched causal prefill; it is NOT a GEMM prefill: every step streams the decoder weights once
+ * (the paper leaves prefill to the host engine, Sec. 4.3; this call makes the library able to fill its own cache).
+ *   token_ids : dev int32 [n_tokens][batch]
+ *   positions : dev int32 [batch], position of the FIRST token of every sequence; positions[b] + n_tokens - 1 must
+ *               stay below max_context (otherwise clamped, error flag raised)
+ * Appends rows positions[b] .. positions[b] + n_tokens - 1 of K and V; asynchronous on `stream`. */
+int mk_fill_cache(mk_schedule *s, const int32_t *token_ids, const int32_t *positions, void *kv_cache, int32_t batch,
+                  int32_t n_tokens, void *stream);
+
 /* Baseline with the same device task bodies and the same instruction lists,
  * but one kernel launch per DAG operator (stream order supplies the
  * dependencies).  Same arguments and results (bit-identical) as

@@ -60,7 +60,7 @@ class mk_stats(C.Structure):
 EXPORTS = ("mk_build_schedule", "mk_schedule_verify", "mk_schedule_dump", "mk_schedule_load", "mk_get_stats",
            "mk_get_config", "mk_instr_count", "mk_instr_get", "mk_instr_set", "mk_pages_available",
            "mk_pipeline_stages", "mk_workspace_bytes", "mk_bind_workspace", "mk_load_weights", "mk_decode_step",
-           "mk_decode_steps", "mk_decode_step_per_op", "mk_decode_step_static", "mk_check", "mk_last_step_ms", "mk_read_ceiling", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
+           "mk_decode_steps", "mk_decode_step_per_op", "mk_decode_step_static", "mk_fill_cache", "mk_check", "mk_last_step_ms", "mk_read_ceiling", "mk_set_flags", "mk_read_trace", "mk_destroy", "mk_last_error")
 
 _lib = None
 
@@ -106,6 +106,8 @@ def lib():
             getattr(L, n).argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.mk_decode_steps.argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_void_p]
+        if hasattr(L, "mk_fill_cache"):      # (absent from older builds loaded through MK_LIB_PATH for A/B runs)
+            L.mk_fill_cache.argtypes = [H, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.mk_check.argtypes = [H, C.c_void_p]
         L.mk_last_step_ms.argtypes = [H, C.POINTER(C.c_float)]
         L.mk_read_ceiling.argtypes = [H, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_size_t), C.c_void_p]
@@ -248,6 +250,10 @@ def mk_decode_step(h, token_ids, positions, kv_cache, logits_out, batch: int, st
 def mk_decode_steps(h, token_ids, positions, kv_cache, logits_out, tokens_out, batch: int, n_steps: int, stream=None) -> None:
     _chk(lib().mk_decode_steps(h, _ptr(token_ids), _ptr(positions), _ptr(kv_cache), _ptr(logits_out), _ptr(tokens_out),
                                batch, n_steps, _stream(stream)))
+
+
+def mk_fill_cache(h, token_ids, positions, kv_cache, batch: int, n_tokens: int, stream=None) -> None:
+    _chk(lib().mk_fill_cache(h, _ptr(token_ids), _ptr(positions), _ptr(kv_cache), int(batch), int(n_tokens), _stream(stream)))
 
 
 def mk_decode_step_static(h, token_ids, positions, kv_cache, logits_out, batch: int, stream=None) -> None:

@@ -451,6 +451,35 @@ int mk_decode_steps(mk_schedule *s, const int32_t *tokens, const int32_t *positi
     return launch_steps(s, tokens, positions, kv, logits, tokens_out, batch, n_steps, (hipStream_t)stream);
 }
 
+int mk_fill_cache(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, int32_t batch, int32_t n_tokens,
+                  void *stream)
+{
+    if (!s) { mk::set_error("null schedule"); return MK_EINVAL; }
+    if (!s->bound) { mk::set_error("mk_fill_cache before mk_bind_workspace"); return MK_ESTATE; }
+    if (!s->loaded) { mk::set_error("mk_fill_cache before mk_load_weights"); return MK_ESTATE; }
+    if (!tokens || !positions || !kv) { mk::set_error("null device pointer"); return MK_EINVAL; }
+    if (batch < 1 || batch > s->dm.Bm) { mk::set_error("batch outside 1..max_batch"); return MK_EINVAL; }
+    if (n_tokens < 1 || n_tokens > s->dm.Tm) { mk::set_error("n_tokens outside 1..max_context"); return MK_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    if ((uint64_t)s->epoch + (uint64_t)n_tokens >= 0x00800000u) {   // keep epoch * signals far from wrapping
+        int rc = reset_sync_state(s, st);
+        if (rc) return rc;
+    }
+    mk::Params P = make_params(s, tokens, positions, kv, nullptr, batch, nullptr, n_tokens);
+    P.forced_tokens = tokens;
+    s->last_static = false;
+    P.epoch = s->epoch + 1;
+    s->epoch += (uint32_t)n_tokens;
+    mk::LdsPlan lp{s->lds_red_bytes, s->lds_xs_off, s->lds_ring_off, s->lds_ring_slots};
+    const bool timing = (s->cfg.flags & MK_F_TIMING) != 0;
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev0, st));
+    // (always the kernel that walks its lists once per step, also for a single token: only it knows forced tokens)
+    hipLaunchKernelGGL(walk_kernel(s, 2), dim3((unsigned)s->n_wg), dim3(mk::kWgThreads), s->lds_total, st, P, lp);
+    HIP_TRY(hipGetLastError());
+    if (timing) HIP_TRY(hipEventRecord((hipEvent_t)s->ev1, st));
+    return MK_OK;
+}
+
 int mk_decode_step_per_op(mk_schedule *s, const int32_t *tokens, const int32_t *positions, void *kv, float *logits,
                           int32_t batch, void *stream)
 {

@@ -222,6 +222,8 @@ struct Params {
     int32_t *next_tokens;   // [n_steps][batch] greedy tokens, written by the arg-max task of every step
     int32_t n_steps;        // decode steps walked by this launch (token of step s+1 = arg-max of step s)
     int32_t want_tokens;    // 0: the caller takes logits only, the arg-max work is skipped (its tasks still signal)
+    const int32_t *forced_tokens;   // cache fill: [n_steps][batch] tokens every step decodes (no feedback); the LM head is
+                                    // skipped (its tasks only wait and signal), nothing is written to `logits`
     uint32_t amax;          // float offset of the arg-max partials [slot][max_batch][2] in the activation region
     int32_t batch, max_batch, max_context;
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, inter_pad, vocab;

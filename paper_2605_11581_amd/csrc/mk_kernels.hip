@@ -2124,7 +2124,7 @@ enum Path : int {
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
 template <bool PERSISTENT, bool RING, int PATH>
 __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
-                                           bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr)
+                                           bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr, bool fill_only = false)
 {
     const int tid = threadIdx.x;
     lp.pc = pc;
@@ -2136,7 +2136,8 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
 
     // Nothing to wait for: the first step of a launch follows the previous launch in stream order,
     // and an arg-max task whose result nobody takes only has to signal.
-    const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens);
+    // (in a launch of several steps the arg-max tasks always wait: their counter is what orders the steps)
+    const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens && P.n_steps <= 1);
     const bool waiting = PERSISTENT && !dead && !no_dep;
     constexpr bool W4 = PATH == kPathW4 || PATH == kPathW4M;
     uint64_t t2 = 0;
@@ -2174,7 +2175,9 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
 
     // Each kind of task is one straight path (prefetch, wait, work), so that the prefetch registers
     // of one kind are not kept alive across the code of another.
-    if (I.op == OP_GEMV) {
+    if (fill_only && I.op == OP_GEMV && (I.flags & F_LOGITS)) {
+        await();     // a cache fill takes no logits: the LM-head tasks keep their place in the dependency chain, nothing else
+    } else if (I.op == OP_GEMV) {
         GemvStream st;
         gemv_issue<RING, W4>(P, I, st, lp.npf);
         if (PERSISTENT) trace_mark(P, pc, 0);
@@ -2287,6 +2290,7 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
         lp.epoch = epoch0 + (uint32_t)step;
         lp.pos_off = step;
         lp.tok_src = step ? P.next_tokens + (size_t)(step - 1) * P.batch : P.tokens;
+        if (MULTI && P.forced_tokens) lp.tok_src = P.forced_tokens + (size_t)step * P.batch;
         lp.tok_out = P.next_tokens + (size_t)step * P.batch;
         wg_sync(lp, lds);   // the previous walk's last instruction has been read by every wave
         fetch_instr(list, 0, sinstr);
@@ -2299,7 +2303,8 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
             const bool more = pc + 1 < P.max_instr;
             if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
             if (RING) pin_uniform(lp);
-            exec_instr<true, RING, PATH>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr);
+            exec_instr<true, RING, PATH>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr,
+                                         MULTI && P.forced_tokens != nullptr);
         }
     }
     // no DMA load may still be writing LDS when the workgroup retires

@@ -67,6 +67,12 @@ class Decoder:
         fn = mk.mk_decode_step_per_op if per_op else mk.mk_decode_step
         fn(self.h, tokens, positions, kv, logits, int(tokens.numel()), stream)
 
+    def fill_cache(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor) -> None:
+        """Appends the K/V rows of ``tokens`` [n_tokens][batch] (int32, device), sequence b starting at ``positions[b]``:
+        the decode path used as a prefill, one launch, no logits."""
+        n_tokens, batch = int(tokens.shape[0]), int(tokens.shape[1])
+        mk.mk_fill_cache(self.h, tokens.contiguous(), positions, kv, batch, n_tokens)
+
     def greedy(self, tokens: torch.Tensor, positions: torch.Tensor, kv: torch.Tensor, logits: torch.Tensor,
                n_steps: int) -> torch.Tensor:
         """``n_steps`` greedy decode steps in ONE launch; returns the chosen tokens [n_steps][batch] (int32, device)."""

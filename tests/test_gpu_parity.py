@@ -258,6 +258,44 @@ def test_ring_and_direct_kernels_agree_bit_for_bit():
     pr.close()
 
 
+@pytest.mark.parametrize("batch_max,lens", [(1, [37]), (2, [21, 21]), (4, [9, 9, 9, 9])], ids=["b1", "b2", "b4"])
+def test_cache_fill_from_a_prompt_matches_the_oracle_prefill(batch_max, lens):
+    """mk_fill_cache: the prompt's K/V rows written by one launch of forced-token decode steps (no LM head) are the
+    oracle prefill's rows (both round the same fp32 values to bf16: one ulp of slack), and the decode step that
+    follows on the filled cache matches the oracle's.  Batch 1 runs the vector kernels, batch 2 / 4 the matrix cores."""
+    full = tiny(max_batch=batch_max, index=19)
+    cfg = synth.model_cfg(full)
+    w = synth.make_weights(full, gain_jitter=0.1)
+    pr = Pair(cfg, w)
+    n = lens[0]
+    prompts = np.stack([synth.make_prompt(full, n + 1, name=f"fill{b}") for b in range(batch_max)], axis=1)   # [n + 1][B]
+    one = oracle.Decoder(synth.model_cfg(full, max_batch=1), w)
+    for b in range(batch_max):
+        kv1 = one.new_kv()
+        one.prefill(prompts[:n, b], kv1)
+        pr.kv_h[:, :, b] = kv1[:, :, 0]
+    say("cache fill,", n, "tokens, batch", batch_max)
+    toks = torch.from_numpy(prompts[:n].astype(np.int32)).to(DEV)
+    pos0 = torch.zeros(batch_max, dtype=torch.int32, device=DEV)
+    # in two launches (a first part, then the rest from where it ended), so that a start position > 0 is covered too
+    k = n // 3
+    pr.dec.fill_cache(toks[:k], pos0, pr.kv_d)
+    pr.dec.fill_cache(toks[k:], pos0 + k, pr.kv_d)
+    pr.dec.check()
+    got = synth.bf16_bits_to_f32(pr.kv_d.cpu().numpy().view(np.uint16)[:, :, :, :, :n])
+    want = synth.bf16_bits_to_f32(pr.kv_h[:, :, :, :, :n])
+    assert np.abs(got - want).max() <= 2 ** -7 * np.abs(want).max()
+    assert (pr.kv_d.cpu().numpy()[:, :, :, :, n:] == 0).all(), "rows beyond the prompt were touched"
+    cur = [int(t) for t in prompts[n]]
+    wl = pr.orc.step(cur, [n] * batch_max, pr.kv_h)
+    gl = pr.gpu_step(cur, [n] * batch_max)
+    for b in range(batch_max):
+        assert rel_err(gl[b], wl[b]) <= 1e-3 and int(gl[b].argmax()) == oracle.argmax(wl[b])
+    with pytest.raises(mk.MkError):
+        mk.mk_fill_cache(pr.dec.h, toks, pos0, pr.kv_d, batch_max + 1, n)
+    pr.close()
+
+
 def test_per_operator_launches_replayed_from_a_graph_match_eager():
     """The per-operator baseline recorded once into a graph (kernels only) and replayed, with eager work and
     synchronisations between the replays: every replay equals the eager single-launch step bit for bit."""
