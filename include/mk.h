@@ -85,10 +85,7 @@ typedef struct mk_config {
 enum {
     MK_F_TRACE = 1u,         /* record per-task clocks into the trace buffer          */
     MK_F_TIMING = 2u,        /* bracket each step's launch(es) with HIP events         */
-    MK_F_NO_TABLE = 4u,      /* mk_build_schedule: ignore the table of recorded profile-guided tilings */
-    MK_F_VALU_ATTENTION = 8u /* mk_build_schedule: keep the attention tasks of a matrix-core schedule (max_batch > 1 or
-                              * use_mfma = 1) on the vector ALUs; by default such schedules score and weight blocks of 16
-                              * positions with matrix-core instructions                                           */
+    MK_F_NO_TABLE = 4u       /* mk_build_schedule: ignore the table of recorded profile-guided tilings */
 };
 
 typedef struct mk_schedule mk_schedule; /* opaque, library-owned host object */

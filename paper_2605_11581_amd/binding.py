@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("MK_LIB_PATH") or os.path.join(_HERE, "libmk.so")   # override: A/B runs of two builds
 
 MK_OK, MK_EINVAL, MK_ENOMEM, MK_EINFEASIBLE, MK_ESCHED, MK_EHIP, MK_ETIMEOUT, MK_ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
-MK_F_TRACE, MK_F_TIMING, MK_F_NO_TABLE, MK_F_VALU_ATTENTION = 1, 2, 4, 8
+MK_F_TRACE, MK_F_TIMING, MK_F_NO_TABLE = 1, 2, 4
 INSTR_DWORDS = 32
 
 

@@ -1390,9 +1390,10 @@ __device__ __forceinline__ void trace_mark(const Params &P, uint32_t pc, int k)
 // The K/V history does not depend on this step's QKV projection, so the first
 // loads of the task are issued before the dependency wait (paper Sec. 4.2.3,
 // Fig. 4: history KV loads leave the critical path).
+template <int GM>
 struct AttState {
-    float m[kMaxGroup], l[kMaxGroup];
-    float acc[kMaxGroup][8];
+    float m[GM], l[GM];
+    float acc[GM][8];
 };
 
 constexpr int kAttPrefetch = 6;   // K and V 128-bit loads in flight per lane
@@ -1544,7 +1545,9 @@ __device__ __forceinline__ bool att_prologue(const Params &P, const InstrAtt &I,
     return owner;
 }
 
-template <int D>
+// GM: the most heads a task may carry (its running states and q slices live in registers, sized by GM whatever the task's
+// own head count: tasks of at most four heads run the GM = 4 form, which leaves the register file room to spare).
+template <int D, int GM>
 __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, char *lds, Wg &lp, AttStream &as, uint32_t pc)
 {
     constexpr int LPP = D / 8;       // lanes per position (16 B each)
@@ -1564,9 +1567,9 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
 
     // ---- main loop over this task's history positions (t < p)
     const int sub = as.sub, dl = lane % LPP;   // position inside the load, 8-dim slice
-    AttState st;
+    AttState<GM> st;
 #pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h) {
+    for (int h = 0; h < GM; ++h) {
         st.m[h] = -INFINITY; st.l[h] = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) st.acc[h][j] = 0.f;
@@ -1575,9 +1578,9 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     const int npos = as.npos;
 
     // this lane's 8-dim slice of every (rotated, pre-scaled) q head, read from LDS once
-    f32x4 qreg[kMaxGroup][2];
+    f32x4 qreg[GM][2];
 #pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h) {
+    for (int h = 0; h < GM; ++h) {
         const f32x4 *qp = (const f32x4 *)(sq + (h < G ? h : 0) * D + dl * 8);
         qreg[h][0] = qp[0];
         qreg[h][1] = qp[1];
@@ -1601,7 +1604,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
             vf[u][4] = bf_lo(vv.z); vf[u][5] = bf_hi(vv.z); vf[u][6] = bf_lo(vv.w); vf[u][7] = bf_hi(vv.w);
         }
 #pragma unroll
-        for (int h = 0; h < kMaxGroup; ++h)
+        for (int h = 0; h < GM; ++h)
             if (h < G) {
                 const f32x4 q0 = qreg[h][0], q1 = qreg[h][1];
                 float sc[N];
@@ -1678,7 +1681,7 @@ __device__ __forceinline__ void att_task(const Params &P, const InstrAtt &I, cha
     {
         const int slot = wave * PPW + sub;
 #pragma unroll
-        for (int h = 0; h < kMaxGroup; ++h)
+        for (int h = 0; h < GM; ++h)
             if (h < G) {
                 float *dst = smerge + ((size_t)slot * G + h) * MS;
                 f32x4 lo4 = {st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]};
@@ -2124,7 +2127,8 @@ enum Path : int {
 // Executes one instruction.  `PERSISTENT`: wait on / signal the dependency counters.
 template <bool PERSISTENT, bool RING, int PATH>
 __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, const Instr &I, uint32_t pc,
-                                           bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr, bool fill_only = false)
+                                           bool &dead, uint32_t nxt = 0, uint32_t *nxt_slot = nullptr, bool fill_only = false,
+                                           bool one_step = true)
 {
     const int tid = threadIdx.x;
     lp.pc = pc;
@@ -2137,7 +2141,7 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
     // Nothing to wait for: the first step of a launch follows the previous launch in stream order,
     // and an arg-max task whose result nobody takes only has to signal.
     // (in a launch of several steps the arg-max tasks always wait: their counter is what orders the steps)
-    const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens && P.n_steps <= 1);
+    const bool no_dep = ((I.flags & F_WAIT_PREV) && lp.pos_off == 0) || (I.op == OP_ARGMAX && !P.want_tokens && one_step);
     const bool waiting = PERSISTENT && !dead && !no_dep;
     constexpr bool W4 = PATH == kPathW4 || PATH == kPathW4M;
     uint64_t t2 = 0;
@@ -2206,17 +2210,19 @@ __device__ __forceinline__ void exec_instr(const Params &P, Wg &lp, char *lds, c
             await();
             att_task_mc<64>(P, A, lds, lp, as, pc);
         }
-    } else if (I.op == OP_ATT) {
+    } else if (I.op == OP_ATT && PATH != kPathMfma && PATH != kPathW4M) {   // (the matrix-core kernels carry only the form above)
         const InstrAtt &A = *(const InstrAtt *)&I;
         AttStream as;
         if (P.head_dim == 128) {
             att_issue<128>(P, lp, A, as);
             await();
-            att_task<128>(P, A, lds, lp, as, pc);
+            if (A.nh <= 4) att_task<128, 4>(P, A, lds, lp, as, pc);
+            else att_task<128, kMaxGroup>(P, A, lds, lp, as, pc);
         } else {
             att_issue<64>(P, lp, A, as);
             await();
-            att_task<64>(P, A, lds, lp, as, pc);
+            if (A.nh <= 4) att_task<64, 4>(P, A, lds, lp, as, pc);
+            else att_task<64, kMaxGroup>(P, A, lds, lp, as, pc);
         }
     } else {
         await();
@@ -2304,7 +2310,11 @@ __device__ __forceinline__ void run_persistent(const Params &P, const LdsPlan pl
             if (more && threadIdx.x < kInstrDwords) nxt = list[(size_t)(pc + 1) * kInstrDwords + threadIdx.x];
             if (RING) pin_uniform(lp);
             exec_instr<true, RING, PATH>(P, lp, lds, I, pc, dead, nxt, more ? sinstr + ((pc + 1) & 1u) * kInstrDwords : nullptr,
-                                         MULTI && P.forced_tokens != nullptr);
+                                         MULTI && P.forced_tokens != nullptr,
+                                         // (a launch of one step.  The single-step vector kernel tests the argument although it
+                                         // is 1 there by construction: with the constant it measured 2 % slower -- these kernels
+                                         // spill scalar registers, and where the spills land moves with details like this one)
+                                         (PATH == kPathValu && !MULTI) ? P.n_steps <= 1 : (!MULTI || n_steps <= 1));
         }
     }
     // no DMA load may still be writing LDS when the workgroup retires

@@ -844,7 +844,7 @@ int build_schedule(const mk_config *cfg_in, mk_schedule **out)
     best.r_qkv = c_rq[0]; best.r_o = c_ro[0]; best.r_gu = c_rgu[0]; best.r_d = c_rd[0]; best.r_head = c_rh[0];
     best.nc = c_nc[c_nc.size() / 2]; best.bs = 16; best.mfma = mfma;
     best.fuse = cfg.fuse_combine > 0 ? 1 : 0;   // not searched by the cost model: chosen by the caller or by on-device tuning
-    best.att_mc = (mfma && !(cfg.flags & MK_F_VALU_ATTENTION)) ? 1 : 0;
+    best.att_mc = mfma ? 1 : 0;   // (the kernels of the matrix-core path carry only the matrix-core form of the attention task)
     best.page_bytes = kChunkBytes;                      // one page = one 1 KB chunk slot
     // weight-page ring: a pipeline stage is 16 pages (4 per wavefront).  The depth is only searched
     // when asked for (ring_kb == -2): measured on MI355X the direct-load path is the faster one at

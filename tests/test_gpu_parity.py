@@ -105,8 +105,8 @@ def test_c0_greedy_32_steps_match_oracle():
     dict(chunk_rows=16, split_qkv=2, split_o=2, split_gateup=2, split_down=4, attn_chunks=4),
     dict(chunk_rows=8, split_gateup=2, split_down=2), dict(n_workgroups=40, attn_chunks=8), dict(attn_chunks=1),
     dict(use_mfma=1, split_qkv=2, split_o=4, split_gateup=2, split_down=2),
-    # matrix-core kernels: attention on the matrix cores (default there) with one / many chunk tasks, and kept on the vector ALUs
-    dict(use_mfma=1, attn_chunks=1), dict(use_mfma=1, attn_chunks=8, n_workgroups=40), dict(use_mfma=1, flags=mk.MK_F_VALU_ATTENTION),
+    # matrix-core kernels: attention on the matrix cores with one / many chunk tasks
+    dict(use_mfma=1, attn_chunks=1), dict(use_mfma=1, attn_chunks=8, n_workgroups=40),
     # weight-page ring (LDS-DMA stream across task boundaries): shallow, deep, ragged stages, matrix-core path
     dict(ring_kb=16), dict(ring_kb=32, attn_chunks=2), dict(ring_kb=96, chunk_rows=2), dict(ring_kb=64, n_workgroups=24),
     dict(ring_kb=48, use_mfma=1, split_o=2, split_down=2),
