@@ -10,8 +10,9 @@
  * (Sec. 4.1.1, Eq. 1-2), simulated, and the chosen trace is serialised
  * (Sec. 4.2.2, Steps 1-4); Phase II, online execution of the serialised trace
  * with no run-time scheduling decisions (Sec. 4.2.2, "execution-path
- * solidification").  The host engine keeps owning KV-cache allocation and
- * prefill (Sec. 4.3.1); the library owns only the decode step.
+ * solidification").  The host engine keeps owning KV-cache allocation
+ * (Sec. 4.3.1); the library owns the decode step, and can fill the cache from
+ * a prompt with that same step (mk_fill_cache), not with a prefill of its own.
  *
  * Conventions
  *   - Every function returns 0 (MK_OK) or a negative MK_E* code; no C++
