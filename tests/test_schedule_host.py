@@ -428,6 +428,17 @@ def test_residual_sum_level_exists_where_many_partial_rows_would_be_reread():
     mk.mk_destroy(h1)
 
 
+def test_step_calls_refuse_a_handle_that_is_not_bound():
+    """Call order is checked on the host, before anything touches a GPU."""
+    h = build("c0_tiny")
+    for call in (lambda: mk.lib().mk_decode_step(h, None, None, None, None, 1, None),
+                 lambda: mk.lib().mk_fill_cache(h, None, None, None, 1, 4, None),
+                 lambda: mk.lib().mk_decode_step_static(h, None, None, None, None, 1, None)):
+        assert call() == mk.MK_ESTATE
+        assert "before mk_bind_workspace" in mk.mk_last_error()
+    mk.mk_destroy(h)
+
+
 def test_verifier_rejects_list_without_end_and_unknown_opcode():
     h = build("c0_tiny")
     w = mk.mk_instr_get(h, 0, 0)
