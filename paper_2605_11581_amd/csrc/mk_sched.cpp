@@ -196,6 +196,11 @@ static bool lds_budget(const Dims &d, const Tiling &t, LdsBudget &b)
 {
     // reduction area: one slot per wave (matrix-core path) or per (wave, 16-lane row) (VALU path)
     b.cap_outs = t.mfma ? 1024 : 640;   // VALU: a workgroup's whole share of the LM head (about 600 rows at 256 workgroups) is one task
+    // matrix-core path: room for 1536 outputs where the staged activations leave it (at batch 8 a workgroup's nine or ten
+    // gate/up row groups of the 7B shape are then one task instead of two)
+    if (t.mfma && kLdsMax - kLdsRed - (int64_t)kWaves * 1536 * 4 - (int64_t)t.ring_pages * t.page_bytes >=
+                      std::max<int64_t>(att_scratch_bytes(d, t), norm_stage_bytes(d, t)))
+        b.cap_outs = 1536;
     b.red_bytes = (uint32_t)(kWaves * (t.mfma ? 1 : 4) * b.cap_outs * 4);
     const int64_t fixed = kLdsRed + b.red_bytes;
     // pages are the 1 KB chunk slots of the ring; a pipeline stage is 16 of them
