@@ -37,7 +37,7 @@ SPACE: List[Tuple[str, List[int]]] = [
     ("attn_chunks", [4, 8, 16, 32, 64]),
     ("fuse_combine", [0, 1]),
     ("split_down", [1, 2, 4, 8]),
-    ("split_qkv", [1, 2]),
+    ("split_qkv", [1, 2, 4]),
     ("split_gateup", [1, 2]),
     ("rows_head", [8, 16]),
 ]
